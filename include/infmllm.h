@@ -1,0 +1,167 @@
+/*
+ * infmllm.h -- C ABI of the MI355X-native streaming step of Inf-MLLM (arxiv 2409.09086).
+ *
+ * One stream object is one layer of one sequence: a KV cache held to a fixed budget
+ * B = r + R (r relevant tokens chosen by attention weight, R most recent tokens).
+ * Each call of infmllm_step is one prompt arrival of Sec. 3.2: the chunk's K/V are
+ * appended to the t cached rows, the chunk's L queries attend all n = t + L keys, the
+ * column-mean attention weight plus the attention bias of Sec. 3.3 ranks the n - R older
+ * keys, and the cache is compressed to the r best of them plus the R newest (Alg. 1).
+ *
+ * Conventions that hold for every entry point:
+ *   - "device" pointers address HIP device memory of the GPU that is current when
+ *     infmllm_stream_attach is called; "host" pointers address ordinary host memory.
+ *   - The library never allocates or frees device memory.  All device memory, including
+ *     the workspace that holds the cache, is the caller's and must stay valid until the
+ *     attached HIP stream has passed the last call that used it.
+ *   - Calls only enqueue work on the attached HIP stream and return; none synchronises
+ *     except infmllm_stream_len, which needs no device access at all.
+ *   - Every function that returns int returns INFMLLM_OK or a negative INFMLLM_E* code and
+ *     never throws or aborts; infmllm_last_error() gives a message for the calling thread's
+ *     last failure.  A failed call leaves the stream as it was.
+ *   - A stream is not thread-safe; different streams may be used from different threads.
+ *   - Tensors are dense, row-major, token-major: q and out are [chunk_len, heads, head_dim],
+ *     k and v are [chunk_len, kv_heads, head_dim], in the stream's dtype.
+ */
+#ifndef INFMLLM_H
+#define INFMLLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct infmllm_stream infmllm_stream_t; /* opaque, library-owned host object */
+
+enum { INFMLLM_BF16 = 0, INFMLLM_FP32 = 1 };
+
+enum {
+    INFMLLM_OK = 0,
+    INFMLLM_EINVAL = -1,    /* bad argument (range, null pointer, unsupported shape)        */
+    INFMLLM_ENOMEM = -2,    /* workspace too small / host allocation failed                 */
+    INFMLLM_ECAPACITY = -3, /* chunk_len exceeds the stream's max_chunk                     */
+    INFMLLM_ESTATE = -4,    /* call not allowed in this state (step before attach, ...)     */
+    INFMLLM_EHIP = -5       /* a HIP call or kernel launch failed                           */
+};
+
+enum {
+    INFMLLM_PARAM_BIAS = 0,      /* b of Alg. 1 (attention bias, Sec. 3.3); default 1e-4, the
+                                    value Sec. 4.2 uses                                      */
+    INFMLLM_PARAM_SCALE = 1,     /* softmax scale on q.k; default 1/sqrt(head_dim)           */
+    INFMLLM_PARAM_MAX_CHUNK = 2, /* largest chunk_len a step may carry; default = budget.
+                                    Fixes the cache capacity at budget + max_chunk rows      */
+    INFMLLM_PARAM_IMPL = 3       /* debug/test: 0 (default) = bf16 streams run attention and
+                                    scoring on the matrix cores; 1 = every dtype runs the
+                                    plain fp32-arithmetic kernels (fp32 streams always do)   */
+};
+
+/*
+ * Creates a stream (Alg. 1 inputs: retrieval/recent window, number of relevant tokens,
+ * given here as budget = r + recent).  Host-only: touches no device.
+ *   budget   > 0   rows kept after every step (B)
+ *   recent   0..budget  newest rows that are always kept (R); r = budget - recent
+ *   heads    query heads; kv_heads divides heads (grouped-query attention pools the
+ *            heads/kv_heads query heads of a group by their mean before ranking)
+ *   head_dim 64 or 128
+ *   dtype    INFMLLM_BF16 or INFMLLM_FP32 (element type of q, k, v, out and of the cache)
+ *   out      receives the handle; the caller releases it with infmllm_stream_destroy
+ * Errors: EINVAL for any argument out of range, ENOMEM if the host object cannot be made.
+ */
+int infmllm_stream_create(int budget, int recent, int heads, int kv_heads, int head_dim,
+                          int dtype, infmllm_stream_t** out);
+
+/*
+ * Sets b, the softmax scale, max_chunk or the kernel family (Alg. 1 input b; Sec. 3.3).
+ * Only before infmllm_stream_attach (ESTATE afterwards).  EINVAL for an unknown parameter,
+ * a non-finite value, bias < 0, scale <= 0, max_chunk < 1 or impl outside {0, 1}.
+ */
+int infmllm_stream_set_param(infmllm_stream_t* s, int which, double value);
+
+/* Bytes of device workspace the stream needs with its current parameters (0 if s is null). */
+size_t infmllm_stream_workspace_bytes(const infmllm_stream_t* s);
+
+/*
+ * Hands the stream its device workspace (256-byte aligned, at least
+ * infmllm_stream_workspace_bytes(s) bytes, caller-owned) and the HIP stream (a
+ * hipStream_t passed as void*, null for the default stream) all later work is enqueued
+ * on.  The workspace holds the cache (two copies of K and V of budget + max_chunk rows per
+ * kv-head, stream positions and scores) and per-step temporaries; its contents need not be
+ * initialised.  The cache starts empty.  Errors: EINVAL (null/misaligned workspace),
+ * ENOMEM (too small), ESTATE (already attached), EHIP.
+ */
+int infmllm_stream_attach(infmllm_stream_t* s, void* dev_workspace, size_t bytes, void* hip_stream);
+
+/*
+ * One streaming step (Sec. 3.2 and Alg. 1), enqueued on the attached HIP stream:
+ *   append      the chunk's k, v become cache rows t .. t+L-1 (stream positions T .. T+L-1)
+ *   attention   out[i] = softmax_j(scale * q[i].K[j]) V[j] over the t cached keys and the
+ *               chunk's keys up to and including i (causal inside the chunk)
+ *   score       S[j] = mean over the last min(recent, L) query rows (and over the query
+ *               heads of a group) of the attention weight on key j, j < c = n - recent
+ *               (Alg. 1 l.1);  W'[j] = S[j] - (c-1-j) * b / c  (Alg. 1 l.2-4)
+ *   select      the r = budget - recent largest W' per kv-head, ties to the newer key
+ *               (Alg. 1 l.5), in ascending order, followed by [c, n) (Alg. 1 l.6-7)
+ *   compact     cache rows, positions and scores are gathered by that list (Alg. 1 l.8)
+ * While n <= budget nothing is evicted and the list is 0 .. n-1.
+ *
+ *   q, k, v     device, read-only, layouts as stated above; chunk_len = L in 1..max_chunk
+ *   out         device, [L, heads, head_dim], written
+ *   retained    device, int32 [kv_heads, budget]; row h receives the kept indices into the
+ *               n rows that were cached before compaction, ascending; entries from
+ *               *n_retained on are left untouched.  May be null (nothing is reported)
+ *   n_retained  device, int32 scalar = min(n, budget).  May be null
+ * Errors: EINVAL (null q/k/v/out, chunk_len < 1), ECAPACITY (chunk_len > max_chunk),
+ * ESTATE (not attached), EHIP (launch failure).
+ */
+int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* v, int chunk_len,
+                 void* out, int32_t* retained, int32_t* n_retained);
+
+/* Tokens now cached (host bookkeeping: min(tokens streamed, budget)); -1 if s is null. */
+int infmllm_stream_len(const infmllm_stream_t* s);
+
+/* Tokens streamed so far, i.e. the stream position the next chunk starts at; -1 if null. */
+int64_t infmllm_stream_streamed(const infmllm_stream_t* s);
+
+/*
+ * Copies the stream position of every cached row to pos (device, int32 [kv_heads, budget];
+ * the first infmllm_stream_len entries of each row are written).  These are Alg. 1's I
+ * expressed as positions in the whole stream.  Errors: EINVAL, ESTATE, EHIP.
+ */
+int infmllm_stream_positions(infmllm_stream_t* s, int32_t* pos);
+
+/*
+ * Debug/test: copies the cache out.  K, V: device, [kv_heads, len, head_dim] in the stream's
+ * dtype; pos: device int32 [kv_heads, len]; score: device float [kv_heads, len] (the biased
+ * score W' that admitted a row at the last eviction, +inf for rows that have only ever been
+ * inside the recent window).  len = infmllm_stream_len(s).  Any pointer may be null.
+ */
+int infmllm_stream_export(infmllm_stream_t* s, void* K, void* V, int32_t* pos, float* score);
+
+/*
+ * Debug/test: replaces the cache by len rows per kv-head (layouts as for export; pos must
+ * be strictly ascending per head) and sets the number of tokens streamed so far.  Scores
+ * are set to +inf.  Errors: EINVAL (len outside 0..budget, null pointers with len > 0),
+ * ESTATE (not attached), EHIP.
+ */
+int infmllm_stream_import(infmllm_stream_t* s, const void* K, const void* V, const int32_t* pos,
+                          int len, int64_t streamed);
+
+/*
+ * Debug/test: copies the biased scores W' of the most recent evicting step to w (device,
+ * float [kv_heads, c]) and returns c through n_candidates (host int); c = 0 if the last
+ * step did not evict.  Errors: EINVAL, ESTATE, EHIP.
+ */
+int infmllm_stream_last_scores(infmllm_stream_t* s, float* w, int* n_candidates);
+
+/* Message for the calling thread's most recent failure ("" if none).  Never null. */
+const char* infmllm_last_error(void);
+
+/* Releases the host object (not the workspace).  Null is a no-op. */
+void infmllm_stream_destroy(infmllm_stream_t* s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INFMLLM_H */

@@ -1,0 +1,293 @@
+// Host side of the C ABI declared in include/infmllm.h: argument checks, workspace carving,
+// the host bookkeeping of one stream (cached length, tokens streamed, which half of the
+// double-buffered cache is live) and the sequence of kernel launches that makes up one
+// streaming step.  No device memory is allocated here and nothing synchronises.
+#include "../../include/infmllm.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <new>
+#include <string>
+
+#include "launch.h"
+
+using namespace infmllm;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+int fail_hip(hipError_t e, const char* what)
+{
+    return fail(INFMLLM_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+constexpr size_t ALIGN = 256;
+size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+}  // namespace
+
+struct infmllm_stream {
+    Geometry g;
+    int dtype;
+    int impl;            // 0 = matrix cores where the dtype allows, 1 = plain arithmetic
+    bool attached;
+    hipStream_t st;
+    CacheView cache[2];
+    int cur;             // live half of the cache
+    int len;             // rows cached
+    int64_t streamed;    // tokens streamed so far
+    int last_cnd;        // candidates of the most recent evicting step (0 = none)
+    float* lse;          // [Hq][max_chunk]
+    float* Wb;           // [Hkv][cap]
+    int32_t* I;          // [Hkv][B]
+
+    struct Layout {
+        size_t K[2], V[2], pos[2], score[2], lse, Wb, I, total;
+    };
+    Layout layout() const
+    {
+        Layout L;
+        size_t off = 0;
+        const size_t kv = up((size_t)g.Hkv * g.cap * g.d * g.elt);
+        const size_t ps = up((size_t)g.Hkv * g.cap * 4);
+        for (int i = 0; i < 2; ++i) {
+            L.K[i] = off; off += kv;
+            L.V[i] = off; off += kv;
+            L.pos[i] = off; off += ps;
+            L.score[i] = off; off += ps;
+        }
+        L.lse = off; off += up((size_t)g.Hq * g.max_chunk * 4);
+        L.Wb = off; off += ps;
+        L.I = off; off += up((size_t)g.Hkv * g.B * 4);
+        L.total = off;
+        return L;
+    }
+};
+
+extern "C" {
+
+const char* infmllm_last_error(void) { return g_err.c_str(); }
+
+int infmllm_stream_create(int budget, int recent, int heads, int kv_heads, int head_dim, int dtype,
+                          infmllm_stream_t** out)
+{
+    if (!out) return fail(INFMLLM_EINVAL, "create: out is null");
+    *out = nullptr;
+    if (budget <= 0) return fail(INFMLLM_EINVAL, "create: budget must be positive (got %d)", budget);
+    if (recent < 0 || recent > budget)
+        return fail(INFMLLM_EINVAL, "create: recent must lie in 0..budget (got %d, budget %d)", recent, budget);
+    if (heads <= 0 || kv_heads <= 0 || heads % kv_heads != 0)
+        return fail(INFMLLM_EINVAL, "create: kv_heads must divide heads (got %d, %d)", heads, kv_heads);
+    if (head_dim != 64 && head_dim != 128)
+        return fail(INFMLLM_EINVAL, "create: head_dim must be 64 or 128 (got %d)", head_dim);
+    if (dtype != INFMLLM_BF16 && dtype != INFMLLM_FP32)
+        return fail(INFMLLM_EINVAL, "create: unknown dtype %d", dtype);
+    if ((long)budget * 2 > (1L << 24))
+        return fail(INFMLLM_EINVAL, "create: budget %d is beyond the supported 8M rows", budget);
+    infmllm_stream* s = new (std::nothrow) infmllm_stream();
+    if (!s) return fail(INFMLLM_ENOMEM, "create: out of host memory");
+    s->g.B = budget; s->g.R = recent; s->g.Hq = heads; s->g.Hkv = kv_heads; s->g.G = heads / kv_heads;
+    s->g.d = head_dim; s->g.max_chunk = budget; s->g.cap = 2 * budget;
+    s->g.elt = dtype == INFMLLM_BF16 ? 2 : 4;
+    s->g.scale = (float)(1.0 / std::sqrt((double)head_dim));
+    s->g.bias = 1e-4f;
+    s->dtype = dtype; s->impl = 0; s->attached = false; s->st = nullptr; s->cur = 0; s->len = 0;
+    s->streamed = 0; s->last_cnd = 0; s->lse = nullptr; s->Wb = nullptr; s->I = nullptr;
+    *out = s;
+    return INFMLLM_OK;
+}
+
+void infmllm_stream_destroy(infmllm_stream_t* s) { delete s; }
+
+int infmllm_stream_set_param(infmllm_stream_t* s, int which, double value)
+{
+    if (!s) return fail(INFMLLM_EINVAL, "set_param: stream is null");
+    if (s->attached) return fail(INFMLLM_ESTATE, "set_param: parameters are fixed once the stream is attached");
+    if (!std::isfinite(value)) return fail(INFMLLM_EINVAL, "set_param: value is not finite");
+    switch (which) {
+        case INFMLLM_PARAM_BIAS:
+            if (value < 0) return fail(INFMLLM_EINVAL, "set_param: bias must be >= 0");
+            s->g.bias = (float)value;
+            return INFMLLM_OK;
+        case INFMLLM_PARAM_SCALE:
+            if (value <= 0) return fail(INFMLLM_EINVAL, "set_param: scale must be > 0");
+            s->g.scale = (float)value;
+            return INFMLLM_OK;
+        case INFMLLM_PARAM_MAX_CHUNK:
+            if (value < 1 || value > (double)(1 << 24) || value != std::floor(value))
+                return fail(INFMLLM_EINVAL, "set_param: max_chunk must be an integer in 1..2^24");
+            s->g.max_chunk = (int)value;
+            s->g.cap = s->g.B + s->g.max_chunk;
+            return INFMLLM_OK;
+        case INFMLLM_PARAM_IMPL:
+            if (value != 0 && value != 1) return fail(INFMLLM_EINVAL, "set_param: impl must be 0 or 1");
+            s->impl = (int)value;
+            return INFMLLM_OK;
+        default:
+            return fail(INFMLLM_EINVAL, "set_param: unknown parameter %d", which);
+    }
+}
+
+size_t infmllm_stream_workspace_bytes(const infmllm_stream_t* s) { return s ? s->layout().total : 0; }
+
+int infmllm_stream_attach(infmllm_stream_t* s, void* ws, size_t bytes, void* hip_stream)
+{
+    if (!s) return fail(INFMLLM_EINVAL, "attach: stream is null");
+    if (s->attached) return fail(INFMLLM_ESTATE, "attach: stream is already attached");
+    if (!ws) return fail(INFMLLM_EINVAL, "attach: workspace is null");
+    if ((uintptr_t)ws % ALIGN) return fail(INFMLLM_EINVAL, "attach: workspace must be 256-byte aligned");
+    const infmllm_stream::Layout L = s->layout();
+    if (bytes < L.total)
+        return fail(INFMLLM_ENOMEM, "attach: workspace has %zu bytes, %zu needed", bytes, L.total);
+    if ((size_t)s->g.cap * 4 > 150 * 1024 && (s->dtype == INFMLLM_FP32 || s->impl == 1))
+        return fail(INFMLLM_EINVAL, "attach: budget + max_chunk = %d rows is beyond what the plain-arithmetic "
+                                    "attention kernel keeps in LDS (38400)", s->g.cap);
+    char* base = (char*)ws;
+    for (int i = 0; i < 2; ++i) {
+        s->cache[i].K = base + L.K[i];
+        s->cache[i].V = base + L.V[i];
+        s->cache[i].pos = (int32_t*)(base + L.pos[i]);
+        s->cache[i].score = (float*)(base + L.score[i]);
+    }
+    s->lse = (float*)(base + L.lse);
+    s->Wb = (float*)(base + L.Wb);
+    s->I = (int32_t*)(base + L.I);
+    s->st = (hipStream_t)hip_stream;
+    s->cur = 0; s->len = 0; s->streamed = 0; s->last_cnd = 0;
+    s->attached = true;
+    return INFMLLM_OK;
+}
+
+int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* v, int L, void* out,
+                 int32_t* retained, int32_t* n_retained)
+{
+    if (!s) return fail(INFMLLM_EINVAL, "step: stream is null");
+    if (!s->attached) return fail(INFMLLM_ESTATE, "step: stream has no workspace attached");
+    if (!q || !k || !v || !out) return fail(INFMLLM_EINVAL, "step: q, k, v and out must not be null");
+    if (L < 1) return fail(INFMLLM_EINVAL, "step: chunk_len must be >= 1 (got %d)", L);
+    if (L > s->g.max_chunk)
+        return fail(INFMLLM_ECAPACITY, "step: chunk_len %d exceeds max_chunk %d", L, s->g.max_chunk);
+    if (s->streamed + L > (int64_t)INT32_MAX)
+        return fail(INFMLLM_ECAPACITY, "step: stream positions would exceed 2^31-1");
+
+    const Geometry& g = s->g;
+    const CacheView& cur = s->cache[s->cur];
+    const int t = s->len, n = t + L;
+    const bool mfma = (s->dtype == INFMLLM_BF16 && s->impl == 0);
+    hipError_t e;
+
+    if ((e = launch_append(g, cur, k, v, t, L, s->streamed, s->st)) != hipSuccess) return fail_hip(e, "step: append");
+    e = mfma ? launch_attn_mfma(g, cur, q, t, L, out, s->lse, s->st)
+             : launch_attn_simple(g, cur, q, t, L, out, s->lse, s->st);
+    if (e != hipSuccess) return fail_hip(e, "step: attention");
+
+    if (n <= g.B) {
+        // the chunk fits: nothing is evicted
+        if ((e = launch_iota(g, n, retained, n_retained, s->st)) != hipSuccess) return fail_hip(e, "step: index list");
+        s->len = n;
+        s->last_cnd = 0;
+    } else {
+        e = mfma ? launch_score_mfma(g, cur, q, s->lse, t, L, s->Wb, s->st)
+                 : launch_score_simple(g, cur, q, s->lse, t, L, s->Wb, s->st);
+        if (e != hipSuccess) return fail_hip(e, "step: score");
+        if ((e = launch_select(g, s->Wb, n, s->I, retained, n_retained, s->st)) != hipSuccess)
+            return fail_hip(e, "step: select");
+        const CacheView& nxt = s->cache[s->cur ^ 1];
+        if ((e = launch_compact(g, cur, nxt, s->I, s->Wb, n, s->st)) != hipSuccess) return fail_hip(e, "step: compact");
+        s->cur ^= 1;
+        s->len = g.B;
+        s->last_cnd = n - g.R;
+    }
+    s->streamed += L;
+    return INFMLLM_OK;
+}
+
+int infmllm_stream_len(const infmllm_stream_t* s) { return s ? s->len : -1; }
+
+int64_t infmllm_stream_streamed(const infmllm_stream_t* s) { return s ? s->streamed : -1; }
+
+static int copy_rows(infmllm_stream* s, void* dst, size_t dpitch, const void* src, size_t spitch, size_t width,
+                     const char* what)
+{
+    if (width == 0) return INFMLLM_OK;
+    hipError_t e = hipMemcpy2DAsync(dst, dpitch, src, spitch, width, (size_t)s->g.Hkv, hipMemcpyDeviceToDevice, s->st);
+    return e == hipSuccess ? INFMLLM_OK : fail_hip(e, what);
+}
+
+int infmllm_stream_positions(infmllm_stream_t* s, int32_t* pos)
+{
+    if (!s || !pos) return fail(INFMLLM_EINVAL, "positions: null argument");
+    if (!s->attached) return fail(INFMLLM_ESTATE, "positions: stream has no workspace attached");
+    return copy_rows(s, pos, (size_t)s->g.B * 4, s->cache[s->cur].pos, (size_t)s->g.cap * 4, (size_t)s->len * 4,
+                     "positions: copy");
+}
+
+int infmllm_stream_export(infmllm_stream_t* s, void* K, void* V, int32_t* pos, float* score)
+{
+    if (!s) return fail(INFMLLM_EINVAL, "export: stream is null");
+    if (!s->attached) return fail(INFMLLM_ESTATE, "export: stream has no workspace attached");
+    const Geometry& g = s->g;
+    const CacheView& c = s->cache[s->cur];
+    const size_t row = (size_t)g.d * g.elt;
+    int rc = INFMLLM_OK;
+    if (K && rc == INFMLLM_OK) rc = copy_rows(s, K, s->len * row, c.K, g.cap * row, s->len * row, "export: K");
+    if (V && rc == INFMLLM_OK) rc = copy_rows(s, V, s->len * row, c.V, g.cap * row, s->len * row, "export: V");
+    if (pos && rc == INFMLLM_OK)
+        rc = copy_rows(s, pos, (size_t)s->len * 4, c.pos, (size_t)g.cap * 4, (size_t)s->len * 4, "export: pos");
+    if (score && rc == INFMLLM_OK)
+        rc = copy_rows(s, score, (size_t)s->len * 4, c.score, (size_t)g.cap * 4, (size_t)s->len * 4, "export: score");
+    return rc;
+}
+
+int infmllm_stream_import(infmllm_stream_t* s, const void* K, const void* V, const int32_t* pos, int len,
+                          int64_t streamed)
+{
+    if (!s) return fail(INFMLLM_EINVAL, "import: stream is null");
+    if (!s->attached) return fail(INFMLLM_ESTATE, "import: stream has no workspace attached");
+    if (len < 0 || len > s->g.B) return fail(INFMLLM_EINVAL, "import: len must lie in 0..budget (got %d)", len);
+    if (len > 0 && (!K || !V || !pos)) return fail(INFMLLM_EINVAL, "import: K, V and pos must not be null");
+    if (streamed < len || streamed > (int64_t)INT32_MAX) return fail(INFMLLM_EINVAL, "import: bad streamed count");
+    const Geometry& g = s->g;
+    const CacheView& c = s->cache[s->cur];
+    const size_t row = (size_t)g.d * g.elt;
+    int rc = INFMLLM_OK;
+    if (len > 0) {
+        rc = copy_rows(s, c.K, g.cap * row, K, len * row, len * row, "import: K");
+        if (rc == INFMLLM_OK) rc = copy_rows(s, c.V, g.cap * row, V, len * row, len * row, "import: V");
+        if (rc == INFMLLM_OK) rc = copy_rows(s, c.pos, (size_t)g.cap * 4, pos, (size_t)len * 4, (size_t)len * 4, "import: pos");
+        if (rc == INFMLLM_OK) {
+            hipError_t e = launch_fill_inf(g, c.score, len, s->st);
+            if (e != hipSuccess) rc = fail_hip(e, "import: score");
+        }
+        if (rc != INFMLLM_OK) return rc;
+    }
+    s->len = len;
+    s->streamed = streamed;
+    s->last_cnd = 0;
+    return INFMLLM_OK;
+}
+
+int infmllm_stream_last_scores(infmllm_stream_t* s, float* w, int* n_candidates)
+{
+    if (!s || !n_candidates) return fail(INFMLLM_EINVAL, "last_scores: null argument");
+    if (!s->attached) return fail(INFMLLM_ESTATE, "last_scores: stream has no workspace attached");
+    *n_candidates = s->last_cnd;
+    if (s->last_cnd == 0 || !w) return INFMLLM_OK;
+    return copy_rows(s, w, (size_t)s->last_cnd * 4, s->Wb, (size_t)s->g.cap * 4, (size_t)s->last_cnd * 4,
+                     "last_scores: copy");
+}
+
+}  // extern "C"

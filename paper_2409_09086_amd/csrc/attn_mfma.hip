@@ -1,0 +1,412 @@
+// bf16 matrix-core kernels for gfx950: chunk attention (Sec. 3.2) and the column score with
+// the attention bias (Alg. 1 l.1-4).
+//
+// Why two kernels.  S[j] = mean_i p_ij needs the exact softmax weight p_ij = exp(s_ij - lse_i),
+// and lse_i is known only once row i has met every key; a column partial taken under a running
+// maximum cannot be repaired afterwards because the correction is per row.  The probability
+// matrix may not go to HBM, so the scored block's logits are formed twice:
+//
+//   attn_fwd   : row-stationary flash attention.  Computes S^T = K.Q^T on 32x32x16 bf16 MFMA so
+//                that a lane owns one query row: row maxima and sums are in-lane (one exchange
+//                between the two half-waves per tile), and the bf16 weights are already laid
+//                out as the B operand of O^T += V^T.P^T.  V stays row-major in LDS and is read
+//                through the LDS transpose read, which hands each lane four consecutive keys of
+//                one head-dim column.  Writes out and the row log-sum-exp (base 2).
+//   score      : column-stationary.  A wavefront keeps its 64 key rows in registers as B
+//                operands, streams the scored query rows through LDS, forms S = Q.K^T so that a
+//                lane owns one key column, and adds exp2(s - lse) into per-register partial sums.
+//                A column's sum is finished inside one wavefront, so W' does not depend on any
+//                cross-workgroup reduction order.
+//
+// fp32 is kept from the MFMA accumulators to the score: the bf16 rounding of P is applied only
+// to the copy that feeds the P.V product.
+#include "launch.h"
+
+namespace infmllm {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+
+constexpr float LOG2E = 1.4426950408889634f;
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float xhalf(float x) { return __shfl_xor(x, 32); }   // the other half-wave's value
+
+// ---------------------------------------------------------------------------------------------
+// attn_fwd
+//   D    head_dim (64 | 128)
+//   RB   32-row query blocks per workgroup (one wavefront each)
+//   KW   key ways: wavefronts that share a query block and split every key tile between them
+//   KVB  32-key blocks a wavefront handles per tile
+// A workgroup of RB*KW wavefronts loads tiles of KW*KVB*32 cache rows into LDS.
+// ---------------------------------------------------------------------------------------------
+template <int D, int RB, int KW, int KVB>
+struct FwdCfg {
+    static constexpr int NW = RB * KW, NT = 64 * NW;
+    static constexpr int SUB = KVB * 32, TILE = KW * SUB;
+    static constexpr int KP = D * 2 + 16;              // K row pitch in LDS (bytes): 16 rows -> 64 distinct banks
+    static constexpr int VP = D * 2 + 64;              // V row pitch: 4 rows x 64 B windows tile the banks
+    static constexpr int CPR = D / 8;                  // 16-byte chunks per row
+    static constexpr int NLD = TILE * CPR / NT;        // chunks per thread per tensor
+    static constexpr int KBYTES = TILE * KP, VBYTES = TILE * VP;
+    static constexpr int OREG = D / 2;                 // fp32 accumulators of O^T per lane
+    static constexpr int MERGE = (KW - 1) * RB * 64 * (OREG + 2) * 4;
+    static constexpr int LDS = (KBYTES + VBYTES) > MERGE ? (KBYTES + VBYTES) : MERGE;
+    static_assert(TILE * CPR % NT == 0, "tile must split evenly over the threads");
+};
+
+template <int D, int RB, int KW, int KVB>
+__global__ void __launch_bounds__(64 * RB * KW)
+attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+                uint16_t* __restrict__ out, float* __restrict__ lse2, int t, int L, int Hq, int G, int cap,
+                int max_chunk, int hpw, float c /* scale * log2(e) */)
+{
+    using C = FwdCfg<D, RB, KW, KVB>;
+    __shared__ __attribute__((aligned(16))) char smem[C::LDS];
+    char* const sK = smem;
+    char* const sV = smem + C::KBYTES;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
+    const int rb = wave % RB, kw = wave / RB;
+    const int rbph = RB / hpw;                               // row blocks per head inside the workgroup
+    const int ngrp = G / hpw;                                // head groups per kv-head
+    const int h = blockIdx.y / ngrp, hgrp = blockIdx.y % ngrp;
+    const int g = h * G + hgrp * hpw + rb % hpw;             // query head of this wavefront
+    const int row0 = 32 * (blockIdx.x * rbph + rb / hpw);    // first query row of this wavefront
+    const int n = t + L;
+    const int wg_rows_end = min(L, 32 * (int)(blockIdx.x + 1) * rbph);
+    const int n_end = t + wg_rows_end;                       // keys any row of the workgroup can see
+    const int my_row = row0 + l32;
+    const int my_lim = t + min(my_row, L - 1);               // last visible key of my row
+    const int wave_end = (row0 < L) ? t + min(L, row0 + 32) : 0;
+
+    const uint16_t* Kh = K + (size_t)h * cap * D;
+    const uint16_t* Vh = V + (size_t)h * cap * D;
+
+    // query fragments: B operand of S^T = K.Q^T, lane (row l32, half hh) holds Q[row][16s + 8hh .. +8)
+    bf16x8 qf[D / 16];
+    {
+        const bool ok = my_row < L;
+        const uint16_t* qp = q + ((size_t)(ok ? my_row : 0) * Hq + g) * D + 8 * hh;
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (ok) v = *(const u32x4*)(qp + 16 * s);
+            qf[s] = as_bf16x8(v);
+        }
+    }
+
+    f32x16 o[D / 32];
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[b][i] = 0.f;
+    float m_run = -__builtin_inff(), lsum = 0.f;
+
+    // register staging of the next tile
+    u32x4 stK[C::NLD], stV[C::NLD];
+    auto fetch = [&](int kv0) {
+#pragma unroll
+        for (int u = 0; u < C::NLD; ++u) {
+            const int ch = tid + u * C::NT, r = ch / C::CPR, cc = ch % C::CPR;
+            const int kv = kv0 + r;
+            u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
+            if (kv < n) {
+                a = *(const u32x4*)(Kh + (size_t)kv * D + cc * 8);
+                b = *(const u32x4*)(Vh + (size_t)kv * D + cc * 8);
+            }
+            stK[u] = a;
+            stV[u] = b;
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int u = 0; u < C::NLD; ++u) {
+            const int ch = tid + u * C::NT, r = ch / C::CPR, cc = ch % C::CPR;
+            *(u32x4*)(sK + r * C::KP + cc * 16) = stK[u];
+            *(u32x4*)(sV + r * C::VP + cc * 16) = stV[u];
+        }
+    };
+
+    const int ntiles = (n_end + C::TILE - 1) / C::TILE;
+    fetch(0);
+    for (int tile = 0; tile < ntiles; ++tile) {
+        const int kv0 = tile * C::TILE;
+        __syncthreads();                                     // everyone is done with the previous tile
+        stash();
+        __syncthreads();
+        if (tile + 1 < ntiles) fetch(kv0 + C::TILE);
+
+        const int sub0 = kv0 + kw * C::SUB;                  // first key of my slice of the tile
+        if (sub0 >= wave_end) continue;                      // nothing visible for this wavefront
+
+        // ---- S^T = K . Q^T ---------------------------------------------------------------------
+        f32x16 acc[KVB];
+#pragma unroll
+        for (int kb = 0; kb < KVB; ++kb) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[kb][i] = 0.f;
+            const char* kp = sK + (kw * C::SUB + 32 * kb + l32) * C::KP + 16 * hh;
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) {
+                const bf16x8 kf = as_bf16x8(*(const u32x4*)(kp + 32 * s));
+                acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], acc[kb], 0, 0, 0);
+            }
+        }
+        // ---- causal mask on tiles that reach past the first row's limit ------------------------
+        if (sub0 + C::SUB - 1 > t + row0) {
+#pragma unroll
+            for (int kb = 0; kb < KVB; ++kb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int kv = sub0 + 32 * kb + 8 * (i / 4) + 4 * hh + (i % 4);
+                    if (kv > my_lim) acc[kb][i] = -__builtin_inff();
+                }
+        }
+        // ---- online softmax, in-lane along the key axis ----------------------------------------
+        float mx = -__builtin_inff();
+#pragma unroll
+        for (int kb = 0; kb < KVB; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[kb][i]);
+        mx = fmaxf(mx, xhalf(mx));
+        const float m_new = fmaxf(m_run, mx * c);
+        const float m_use = (m_new == -__builtin_inff()) ? 0.f : m_new;
+        const float alpha = fast_exp2(m_run - m_use);
+        m_run = m_new;
+        if (__any(alpha != 1.0f)) {
+            lsum *= alpha;
+#pragma unroll
+            for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[b][i] *= alpha;
+        }
+        // ---- P (fp32 -> bf16 for the product) and O^T += V^T . P^T -----------------------------
+#pragma unroll
+        for (int kb = 0; kb < KVB; ++kb) {
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+                bf16x8 pf;
+#pragma unroll
+                for (int p = 0; p < 8; ++p) {
+                    const float e = fast_exp2(__builtin_fmaf(acc[kb][8 * tt + p], c, -m_use));
+                    lsum += e;
+                    pf[p] = (__bf16)e;
+                }
+                // lane l of a 16-lane block supplies the address of key row (l/4), 4 columns at 4*(l%4)
+                const int j16 = lane & 15, blk = (lane >> 4) & 1;
+                const char* vp = sV + (kw * C::SUB + 32 * kb + 16 * tt + 4 * hh + (j16 >> 2)) * C::VP +
+                                 (16 * blk + 4 * (j16 & 3)) * 2;
+#pragma unroll
+                for (int b = 0; b < D / 32; ++b) {
+                    const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(vp + 64 * b));
+                    const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(vp + 64 * b + 8 * C::VP));
+                    const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+                    o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[b], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // ---- merge the key ways of a query block ---------------------------------------------------
+    if (KW > 1) {
+        __syncthreads();
+        float* mg = (float*)smem;
+        if (kw > 0) {
+            float* w = mg + (size_t)((kw - 1) * RB + rb) * 64 * (C::OREG + 2);
+            w[lane] = m_run;
+            w[64 + lane] = lsum;
+#pragma unroll
+            for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) w[(2 + b * 16 + i) * 64 + lane] = o[b][i];
+        }
+        __syncthreads();
+        if (kw == 0) {
+            for (int k2 = 1; k2 < KW; ++k2) {
+                const float* w = mg + (size_t)((k2 - 1) * RB + rb) * 64 * (C::OREG + 2);
+                const float m2 = w[lane], l2 = w[64 + lane];
+                const float mt = fmaxf(m_run, m2);
+                const float mu = (mt == -__builtin_inff()) ? 0.f : mt;
+                const float a1 = fast_exp2(m_run - mu), a2 = fast_exp2(m2 - mu);
+                lsum = lsum * a1 + l2 * a2;
+#pragma unroll
+                for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o[b][i] = o[b][i] * a1 + w[(2 + b * 16 + i) * 64 + lane] * a2;
+                m_run = mt;
+            }
+        }
+    }
+    if (kw != 0 || my_row >= L) return;
+
+    // ---- normalise and store: lane (row l32, half hh) holds O[row][32b + 8(i/4) + 4hh + i%4] -----
+    const float ltot = lsum + xhalf(lsum);
+    const float inv = 1.0f / ltot;
+    uint16_t* op = out + ((size_t)my_row * Hq + g) * D;
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            bf16x4 w;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[b][4 * a + e] * inv);
+            *(bf16x4*)(op + 32 * b + 8 * a + 4 * hh) = w;
+        }
+    if (hh == 0) lse2[(size_t)g * max_chunk + my_row] = m_run + __builtin_log2f(ltot);
+}
+
+// ---------------------------------------------------------------------------------------------
+// score: W'[h][j] = (1/(G lq)) sum_{g in group h} sum_{i = L-lq}^{L-1} exp2(c q_i.k_j - lse2_i)
+//                   - (cnd-1-j) b / cnd
+// Workgroup = 4 wavefronts x 64 key columns; every scored row sees every candidate column, so
+// there is no mask inside the block.
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(256)
+score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const float* __restrict__ lse2,
+             float* __restrict__ Wb, int L, int lq, int Hq, int G, int cap, int max_chunk, int cnd, float c,
+             float bias)
+{
+    constexpr int QP = D * 2 + 16;                            // pitch of a staged query row
+    constexpr int CPR = D / 8;
+    constexpr int NLD = 32 * CPR / 256;                       // 16-byte chunks per thread per 32-row block
+    __shared__ __attribute__((aligned(16))) char sQ[32 * QP];
+    __shared__ __attribute__((aligned(16))) float sL[32];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
+    const int h = blockIdx.y;
+    const int col0 = blockIdx.x * 256 + wave * 64;
+
+    // key fragments: B operand of S = Q.K^T, lane (column l32, half hh) holds K[col][16s + 8hh .. +8)
+    bf16x8 kf[2][D / 16];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const int col = col0 + 32 * cb + l32;
+        const bool ok = col < cnd;
+        const uint16_t* kp = K + ((size_t)h * cap + (ok ? col : 0)) * D + 8 * hh;
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (ok) v = *(const u32x4*)(kp + 16 * s);
+            kf[cb][s] = as_bf16x8(v);
+        }
+    }
+    f32x16 part[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) part[cb][i] = 0.f;
+
+    const int nblk = (lq + 31) / 32;
+    const int total = G * nblk;                               // 32-row blocks to sweep
+    u32x4 st[NLD > 0 ? NLD : 1];
+    float stl = 0.f;
+    auto fetch = [&](int it) {
+        const int g = h * G + it / nblk, i0 = L - lq + 32 * (it % nblk);
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) {
+            const int ch = tid + u * 256, r = ch / CPR, cc = ch % CPR;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (i0 + r < L) v = *(const u32x4*)(q + ((size_t)(i0 + r) * Hq + g) * D + cc * 8);
+            st[u] = v;
+        }
+        if (tid < 32) stl = (i0 + tid < L) ? lse2[(size_t)g * max_chunk + i0 + tid] : __builtin_inff();
+    };
+    if (total > 0) fetch(0);
+    for (int it = 0; it < total; ++it) {
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) {
+            const int ch = tid + u * 256, r = ch / CPR, cc = ch % CPR;
+            *(u32x4*)(sQ + r * QP + cc * 16) = st[u];
+        }
+        if (tid < 32) sL[tid] = stl;
+        __syncthreads();
+        if (it + 1 < total) fetch(it + 1);
+
+        f32x16 acc[2];
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
+        const char* qp = sQ + l32 * QP + 16 * hh;
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+            const bf16x8 qf = as_bf16x8(*(const u32x4*)(qp + 32 * s));
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[0][s], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[1][s], acc[1], 0, 0, 0);
+        }
+        // lane (column, half hh) holds rows 8a + 4hh + e of the block in register 4a + e
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const f32x4 ls = *(const f32x4*)(sL + 8 * a + 4 * hh);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                part[0][4 * a + e] += fast_exp2(__builtin_fmaf(acc[0][4 * a + e], c, -ls[e]));
+                part[1][4 * a + e] += fast_exp2(__builtin_fmaf(acc[1][4 * a + e], c, -ls[e]));
+            }
+        }
+    }
+    const float norm = (lq > 0) ? 1.0f / (float)(G * lq) : 0.f;
+    const float dstep = bias / (float)cnd;                    // Alg. 1 l.2
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        float s0 = 0.f;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) s0 += (part[cb][4 * a] + part[cb][4 * a + 1]) + (part[cb][4 * a + 2] + part[cb][4 * a + 3]);
+        s0 += xhalf(s0);
+        const int col = col0 + 32 * cb + l32;
+        if (hh == 0 && col < cnd)
+            Wb[(size_t)h * cap + col] = s0 * norm - (float)(cnd - 1 - col) * dstep;     // Alg. 1 l.1, l.3-4
+    }
+}
+
+}  // namespace
+
+hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const void* q, int t, int L, void* out,
+                            float* lse, hipStream_t st)
+{
+    constexpr int RB = 4, KW = 1, KVB = 2;
+    const int hpw = (RB % g.G == 0) ? g.G : ((g.G % RB == 0) ? RB : 1);
+    const int rbph = RB / hpw;
+    const dim3 grid((L + 32 * rbph - 1) / (32 * rbph), g.Hkv * (g.G / hpw)), block(64 * RB * KW);
+    const float cc = g.scale * LOG2E;
+#define INFMLLM_FWD(DD)                                                                                  \
+    hipLaunchKernelGGL((attn_fwd_kernel<DD, RB, KW, KVB>), grid, block, 0, st, (const uint16_t*)q,       \
+                       (const uint16_t*)c.K, (const uint16_t*)c.V, (uint16_t*)out, lse, t, L, g.Hq, g.G, \
+                       g.cap, g.max_chunk, hpw, cc)
+    if (g.d == 128) INFMLLM_FWD(128);
+    else if (g.d == 64) INFMLLM_FWD(64);
+    else return hipErrorInvalidValue;
+#undef INFMLLM_FWD
+    return hipGetLastError();
+}
+
+hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const void* q, const float* lse, int t,
+                             int L, float* Wb, hipStream_t st)
+{
+    const int n = t + L, cnd = n - g.R, lq = g.R < L ? g.R : L;
+    if (cnd <= 0) return hipSuccess;
+    const dim3 grid((cnd + 255) / 256, g.Hkv), block(256);
+    const float cc = g.scale * LOG2E;
+#define INFMLLM_SCORE(DD)                                                                                \
+    hipLaunchKernelGGL((score_kernel<DD>), grid, block, 0, st, (const uint16_t*)q, (const uint16_t*)c.K, \
+                       lse, Wb, L, lq, g.Hq, g.G, g.cap, g.max_chunk, cnd, cc, g.bias)
+    if (g.d == 128) INFMLLM_SCORE(128);
+    else if (g.d == 64) INFMLLM_SCORE(64);
+    else return hipErrorInvalidValue;
+#undef INFMLLM_SCORE
+    return hipGetLastError();
+}
+
+}  // namespace infmllm

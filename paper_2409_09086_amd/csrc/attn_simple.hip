@@ -1,0 +1,209 @@
+// Plain fp32-arithmetic chunk attention and column scoring for gfx950.
+//
+// This is the path of fp32 streams (an fp32 contraction cannot go through the bf16 matrix
+// cores within the 1e-4 output tolerance); bf16 streams use the MFMA kernels instead and
+// reach this file only when the stream was created with the plain-arithmetic override.
+//
+//   attn_simple  : Sec. 3.2 -- the L new queries attend the t cached keys and, causally, the
+//                  chunk's own keys.  One workgroup per (query row, query head): logits into
+//                  LDS, block softmax, then P.V with lanes along head_dim.  Also writes the
+//                  row's log-sum-exp, which the scoring kernel needs.
+//   score_simple : Alg. 1 l.1-4 -- every thread owns one candidate key column (its key row
+//                  lives in registers), sweeps the scored query rows and sums the exact
+//                  softmax weights exp(s - lse); mean over rows and group heads, plus the bias
+//                  ramp.  Column sums are complete inside a thread, so the result does not
+//                  depend on any reduction order across workgroups.
+#include "launch.h"
+
+namespace infmllm {
+
+namespace {
+
+template <typename T> struct Elt;
+template <> struct Elt<float> {
+    static __device__ __forceinline__ float load(const float* p) { return *p; }
+    static __device__ __forceinline__ void store(float* p, float x) { *p = x; }
+};
+template <> struct Elt<uint16_t> {   // bf16 held as raw bits
+    static __device__ __forceinline__ float load(const uint16_t* p) { return __uint_as_float((uint32_t)(*p) << 16); }
+    static __device__ __forceinline__ void store(uint16_t* p, float x)
+    {
+        uint32_t u = __float_as_uint(x);
+        if ((u & 0x7fffffffu) > 0x7f800000u) { *p = (uint16_t)((u >> 16) | 0x40); return; }   // NaN
+        u += 0x7fffu + ((u >> 16) & 1u);                                                      // RNE
+        *p = (uint16_t)(u >> 16);
+    }
+};
+
+__device__ __forceinline__ float block_reduce_max(float x, float* red)
+{
+    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+    const int w = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[w] = x;
+    __syncthreads();
+    float r = red[0];
+    for (int i = 1; i < (int)(blockDim.x >> 6); ++i) r = fmaxf(r, red[i]);
+    return r;
+}
+
+__device__ __forceinline__ float block_reduce_sum(float x, float* red)
+{
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+    const int w = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[w] = x;
+    __syncthreads();
+    float r = red[0];
+    for (int i = 1; i < (int)(blockDim.x >> 6); ++i) r += red[i];
+    return r;
+}
+
+// grid (L, Hq), 256 threads, dynamic LDS: n floats of logits/weights.
+template <typename T, int D>
+__global__ void __launch_bounds__(256)
+attn_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const T* __restrict__ V,
+                   T* __restrict__ out, float* __restrict__ lse, int t, int L, int Hq, int G, int cap,
+                   int max_chunk, float scale)
+{
+    extern __shared__ float p[];                 // [vis]
+    __shared__ float qs[D];
+    __shared__ float red[4];
+    __shared__ float part[256];
+
+    const int i = blockIdx.x, g = blockIdx.y, h = g / G;
+    const int vis = t + i + 1;                   // columns 0 .. t+i are visible
+    const T* Kh = K + (size_t)h * cap * D;
+    const T* Vh = V + (size_t)h * cap * D;
+    const T* qi = q + ((size_t)i * Hq + g) * D;
+    for (int x = threadIdx.x; x < D; x += 256) qs[x] = Elt<T>::load(qi + x);
+    __syncthreads();
+
+    float mx = -__builtin_inff();
+    for (int j = threadIdx.x; j < vis; j += 256) {
+        const T* kj = Kh + (size_t)j * D;
+        float acc = 0.f;
+#pragma unroll 8
+        for (int x = 0; x < D; ++x) acc = fmaf(qs[x], Elt<T>::load(kj + x), acc);
+        acc *= scale;
+        p[j] = acc;
+        mx = fmaxf(mx, acc);
+    }
+    mx = block_reduce_max(mx, red);
+    float sum = 0.f;
+    for (int j = threadIdx.x; j < vis; j += 256) {
+        const float e = expf(p[j] - mx);
+        p[j] = e;
+        sum += e;
+    }
+    sum = block_reduce_sum(sum, red);            // its barriers also publish p[]
+    const float inv = 1.0f / sum;
+
+    constexpr int NG = 256 / D;                  // groups of lanes along the key axis
+    const int x = threadIdx.x % D, grp = threadIdx.x / D;
+    float acc = 0.f;
+    for (int j = grp; j < vis; j += NG) acc = fmaf(p[j], Elt<T>::load(Vh + (size_t)j * D + x), acc);
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x < D) {
+        float o = 0.f;
+#pragma unroll
+        for (int u = 0; u < NG; ++u) o += part[u * D + threadIdx.x];
+        Elt<T>::store(out + ((size_t)i * Hq + g) * D + threadIdx.x, o * inv);
+    }
+    if (threadIdx.x == 0) lse[(size_t)g * max_chunk + i] = mx + logf(sum);
+}
+
+// grid (ceil(cnd/128), Hkv), 128 threads.  Thread = candidate column j.
+template <typename T, int D>
+__global__ void __launch_bounds__(128)
+score_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const float* __restrict__ lse,
+                    float* __restrict__ Wb, int L, int lq, int Hq, int G, int cap, int max_chunk, int cnd,
+                    float scale, float bias)
+{
+    constexpr int RT = 16;                       // query rows staged per round
+    __shared__ float qs[RT][D];
+    __shared__ float ls[RT];
+
+    const int h = blockIdx.y;
+    const int j = blockIdx.x * 128 + threadIdx.x;
+    const bool live = j < cnd;
+    float kr[D];
+    {
+        const T* kj = K + ((size_t)h * cap + (live ? j : 0)) * D;
+#pragma unroll
+        for (int x = 0; x < D; ++x) kr[x] = Elt<T>::load(kj + x);
+    }
+    float acc = 0.f;
+    for (int gg = 0; gg < G; ++gg) {
+        const int g = h * G + gg;
+        for (int i0 = L - lq; i0 < L; i0 += RT) {
+            const int rows = min(RT, L - i0);
+            __syncthreads();
+            for (int e = threadIdx.x; e < rows * D; e += 128) {
+                const int r = e / D, x = e - r * D;
+                qs[r][x] = Elt<T>::load(q + ((size_t)(i0 + r) * Hq + g) * D + x);
+            }
+            if (threadIdx.x < rows) ls[threadIdx.x] = lse[(size_t)g * max_chunk + i0 + threadIdx.x];
+            __syncthreads();
+            for (int r = 0; r < rows; ++r) {
+                float s = 0.f;
+#pragma unroll
+                for (int x = 0; x < D; ++x) s = fmaf(qs[r][x], kr[x], s);
+                acc += expf(s * scale - ls[r]);
+            }
+        }
+    }
+    if (live) {
+        const float S = (lq > 0) ? acc / (float)(G * lq) : 0.f;        // Alg. 1 l.1, pooled over the group
+        const float dstep = bias / (float)cnd;                         // Alg. 1 l.2
+        Wb[(size_t)h * cap + j] = S - (float)(cnd - 1 - j) * dstep;    // Alg. 1 l.3-4
+    }
+}
+
+}  // namespace
+
+hipError_t launch_attn_simple(const Geometry& g, const CacheView& c, const void* q, int t, int L, void* out,
+                              float* lse, hipStream_t st)
+{
+    const dim3 grid(L, g.Hq), block(256);
+    const size_t lds = (size_t)(t + L) * sizeof(float);
+#define INFMLLM_ATTN(TT, DD)                                                                            \
+    do {                                                                                                \
+        if (lds > 48 * 1024) {                                                                          \
+            hipError_t e = hipFuncSetAttribute((const void*)attn_simple_kernel<TT, DD>,                 \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);   \
+            if (e != hipSuccess) return e;                                                              \
+        }                                                                                               \
+        hipLaunchKernelGGL((attn_simple_kernel<TT, DD>), grid, block, lds, st, (const TT*)q,            \
+                           (const TT*)c.K, (const TT*)c.V, (TT*)out, lse, t, L, g.Hq, g.G, g.cap,       \
+                           g.max_chunk, g.scale);                                                       \
+    } while (0)
+    if (g.elt == 4 && g.d == 64) INFMLLM_ATTN(float, 64);
+    else if (g.elt == 4 && g.d == 128) INFMLLM_ATTN(float, 128);
+    else if (g.elt == 2 && g.d == 64) INFMLLM_ATTN(uint16_t, 64);
+    else if (g.elt == 2 && g.d == 128) INFMLLM_ATTN(uint16_t, 128);
+    else return hipErrorInvalidValue;
+#undef INFMLLM_ATTN
+    return hipGetLastError();
+}
+
+hipError_t launch_score_simple(const Geometry& g, const CacheView& c, const void* q, const float* lse, int t,
+                               int L, float* Wb, hipStream_t st)
+{
+    const int n = t + L, cnd = n - g.R, lq = g.R < L ? g.R : L;
+    if (cnd <= 0) return hipSuccess;
+    const dim3 grid((cnd + 127) / 128, g.Hkv), block(128);
+#define INFMLLM_SCORE(TT, DD)                                                                           \
+    hipLaunchKernelGGL((score_simple_kernel<TT, DD>), grid, block, 0, st, (const TT*)q, (const TT*)c.K, \
+                       lse, Wb, L, lq, g.Hq, g.G, g.cap, g.max_chunk, cnd, g.scale, g.bias)
+    if (g.elt == 4 && g.d == 64) INFMLLM_SCORE(float, 64);
+    else if (g.elt == 4 && g.d == 128) INFMLLM_SCORE(float, 128);
+    else if (g.elt == 2 && g.d == 64) INFMLLM_SCORE(uint16_t, 64);
+    else if (g.elt == 2 && g.d == 128) INFMLLM_SCORE(uint16_t, 128);
+    else return hipErrorInvalidValue;
+#undef INFMLLM_SCORE
+    return hipGetLastError();
+}
+
+}  // namespace infmllm

@@ -1,0 +1,152 @@
+// Cache maintenance kernels for gfx950: append (Sec. 3.2, first paragraph), the warm-up index
+// list, and the gather that compresses the cache (Alg. 1 l.8).  All three are pure data
+// movement and HBM-bound: every thread moves 16-byte vectors, a row of head_dim elements is
+// covered by consecutive lanes so that each wavefront touches whole rows.
+#include "launch.h"
+
+namespace infmllm {
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// chunk k/v [L][Hkv][d]  ->  cache rows [h][t+i][d]
+__global__ void __launch_bounds__(256)
+append_kernel(const u32x4* __restrict__ k, const u32x4* __restrict__ v, u32x4* __restrict__ K,
+              u32x4* __restrict__ V, int32_t* __restrict__ pos, float* __restrict__ score, int t, int L,
+              int Hkv, int cap, int vec_per_row, int pos0)
+{
+    const long total = (long)L * Hkv * vec_per_row;
+    for (long idx = (long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (long)gridDim.x * blockDim.x) {
+        const int x = (int)(idx % vec_per_row);
+        const long ih = idx / vec_per_row;
+        const int h = (int)(ih % Hkv);
+        const int i = (int)(ih / Hkv);
+        const long dst = ((long)h * cap + t + i) * vec_per_row + x;
+        K[dst] = k[idx];
+        V[dst] = v[idx];
+        if (x == 0) {
+            pos[(long)h * cap + t + i] = pos0 + i;
+            score[(long)h * cap + t + i] = __builtin_inff();
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256)
+iota_kernel(int32_t* __restrict__ I, int32_t* __restrict__ count, int n, int Hkv, int B)
+{
+    const int total = n * Hkv;
+    for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += gridDim.x * blockDim.x) {
+        const int h = idx / n, j = idx - h * n;
+        if (I) I[(long)h * B + j] = j;
+    }
+    if (count && blockIdx.x == 0 && threadIdx.x == 0) *count = n;
+}
+
+__global__ void __launch_bounds__(256)
+fill_inf_kernel(float* __restrict__ score, int len, int Hkv, int cap)
+{
+    const int total = len * Hkv;
+    for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += gridDim.x * blockDim.x) {
+        const int h = idx / len, j = idx - h * len;
+        score[(long)h * cap + j] = __builtin_inff();
+    }
+}
+
+// dst[h][x] <- src[h][I[h][x]] for x < B.  One thread per 16-byte vector of a row of K and V.
+template <int VPR>   // vectors per row
+__global__ void __launch_bounds__(256)
+compact_kernel(const u32x4* __restrict__ Ks, const u32x4* __restrict__ Vs, const int32_t* __restrict__ ps,
+               u32x4* __restrict__ Kd, u32x4* __restrict__ Vd, int32_t* __restrict__ pd,
+               float* __restrict__ sd, const int32_t* __restrict__ I, const float* __restrict__ Wb,
+               int B, int cap, int cnd)
+{
+    constexpr int ROWS = 256 / VPR;               // rows per block pass
+    const int h = blockIdx.y;
+    const int lane_row = threadIdx.x / VPR, x = threadIdx.x % VPR;
+    const long hb = (long)h * cap;
+    for (int row0 = blockIdx.x * ROWS * 4; row0 < B; row0 += gridDim.x * ROWS * 4) {
+        int src[4];
+        u32x4 kk[4], vv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int r = row0 + u * ROWS + lane_row;
+            src[u] = (r < B) ? I[(long)h * B + r] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (src[u] >= 0) {
+                kk[u] = __builtin_nontemporal_load(&Ks[(hb + src[u]) * VPR + x]);
+                vv[u] = __builtin_nontemporal_load(&Vs[(hb + src[u]) * VPR + x]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int r = row0 + u * ROWS + lane_row;
+            if (src[u] >= 0) {
+                __builtin_nontemporal_store(kk[u], &Kd[(hb + r) * VPR + x]);
+                __builtin_nontemporal_store(vv[u], &Vd[(hb + r) * VPR + x]);
+                if (x == 0) {
+                    pd[hb + r] = ps[hb + src[u]];
+                    sd[hb + r] = (src[u] < cnd) ? Wb[(long)h * cap + src[u]] : __builtin_inff();
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_append(const Geometry& g, const CacheView& c, const void* k, const void* v, int t,
+                         int L, int64_t T, hipStream_t st)
+{
+    const int vpr = g.d * g.elt / 16;
+    const long total = (long)L * g.Hkv * vpr;
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(append_kernel, dim3(blocks), dim3(256), 0, st, (const u32x4*)k, (const u32x4*)v,
+                       (u32x4*)c.K, (u32x4*)c.V, c.pos, c.score, t, L, g.Hkv, g.cap, vpr, (int)T);
+    return hipGetLastError();
+}
+
+hipError_t launch_iota(const Geometry& g, int n, int32_t* user_I, int32_t* user_count, hipStream_t st)
+{
+    if (!user_I && !user_count) return hipSuccess;
+    int blocks = (n * g.Hkv + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(iota_kernel, dim3(blocks), dim3(256), 0, st, user_I, user_count, n, g.Hkv, g.B);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_inf(const Geometry& g, float* score, int len, hipStream_t st)
+{
+    if (len <= 0) return hipSuccess;
+    int blocks = (len * g.Hkv + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(fill_inf_kernel, dim3(blocks), dim3(256), 0, st, score, len, g.Hkv, g.cap);
+    return hipGetLastError();
+}
+
+hipError_t launch_compact(const Geometry& g, const CacheView& src, const CacheView& dst, const int32_t* I,
+                          const float* Wb, int n, hipStream_t st)
+{
+    const int vpr = g.d * g.elt / 16;             // 8 (d=64 bf16), 16 (d=128 bf16 / d=64 fp32), 32 (d=128 fp32)
+    const int rows_per_pass = (256 / vpr) * 4;
+    int bx = (g.B + rows_per_pass - 1) / rows_per_pass;
+    const dim3 grid(bx, g.Hkv), block(256);
+    const int cnd = n - g.R;
+#define INFMLLM_COMPACT(VPR)                                                                          \
+    hipLaunchKernelGGL(compact_kernel<VPR>, grid, block, 0, st, (const u32x4*)src.K, (const u32x4*)src.V, \
+                       src.pos, (u32x4*)dst.K, (u32x4*)dst.V, dst.pos, dst.score, I, Wb, g.B, g.cap, cnd)
+    switch (vpr) {
+        case 8: INFMLLM_COMPACT(8); break;
+        case 16: INFMLLM_COMPACT(16); break;
+        case 32: INFMLLM_COMPACT(32); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef INFMLLM_COMPACT
+    return hipGetLastError();
+}
+
+}  // namespace infmllm

@@ -1,0 +1,67 @@
+// Internal launch interface between the C-ABI host code and the gfx950 kernels.
+// Everything here is asynchronous on the given HIP stream; nothing allocates.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace infmllm {
+
+// Geometry of one stream, fixed at attach time.
+struct Geometry {
+    int B;        // budget (rows kept after a step)
+    int R;        // recent window (newest rows always kept)
+    int Hq;       // query heads
+    int Hkv;      // key/value heads
+    int G;        // Hq / Hkv
+    int d;        // head_dim (64 or 128)
+    int cap;      // cache rows per kv-head = B + max_chunk
+    int max_chunk;
+    int elt;      // bytes per element (2 = bf16, 4 = fp32)
+    float scale;  // softmax scale
+    float bias;   // b of Alg. 1
+};
+
+// One side of the double-buffered cache.
+struct CacheView {
+    void* K;        // [Hkv][cap][d]
+    void* V;        // [Hkv][cap][d]
+    int32_t* pos;   // [Hkv][cap]
+    float* score;   // [Hkv][cap]
+};
+
+// a1: rows t..t+L-1 <- chunk; pos <- T..T+L-1; score <- +inf.
+hipError_t launch_append(const Geometry& g, const CacheView& c, const void* k, const void* v,
+                         int t, int L, int64_t T, hipStream_t st);
+
+// a2 (plain fp32 arithmetic, any dtype): out and per-row log-sum-exp.
+hipError_t launch_attn_simple(const Geometry& g, const CacheView& c, const void* q, int t, int L,
+                              void* out, float* lse, hipStream_t st);
+
+// a3+a4 (plain fp32 arithmetic, any dtype): W'[h][j] for j < cnd = n - R.
+hipError_t launch_score_simple(const Geometry& g, const CacheView& c, const void* q, const float* lse,
+                               int t, int L, float* Wb, hipStream_t st);
+
+// a2 on bf16 MFMA (bf16 streams only).
+hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const void* q, int t, int L,
+                            void* out, float* lse, hipStream_t st);
+
+// a3+a4 on bf16 MFMA (bf16 streams only).
+hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const void* q, const float* lse,
+                             int t, int L, float* Wb, hipStream_t st);
+
+// a5+a6: I[h] = sort_asc(top-r of W'[h][0..cnd)) ++ [cnd, n).  I has row stride B.
+// user_I (row stride B) and user_count may be null.
+hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, int32_t* user_I,
+                         int32_t* user_count, hipStream_t st);
+
+// warm-up: I[h][j] = j for j < n.
+hipError_t launch_iota(const Geometry& g, int n, int32_t* user_I, int32_t* user_count, hipStream_t st);
+
+// score[h][0..len) <- +inf (used when a cache is imported).
+hipError_t launch_fill_inf(const Geometry& g, float* score, int len, hipStream_t st);
+
+// a7: dst rows x < B <- src rows I[h][x]; score <- W'[I] for relevant rows, +inf for recent ones.
+hipError_t launch_compact(const Geometry& g, const CacheView& src, const CacheView& dst,
+                          const int32_t* I, const float* Wb, int n, hipStream_t st);
+
+}  // namespace infmllm

@@ -1,0 +1,154 @@
+// Per-head top-r selection for gfx950 (Alg. 1 l.5-7).
+//
+// One workgroup of 1024 threads per kv-head.  The r-th largest biased score is found with an
+// MSB-first radix select over order-preserving 32-bit keys (four 8-bit digits); digit
+// histograms are built from wavefront ballots of the candidates that still match the
+// prefix, so LDS sees one atomic per distinct digit per wavefront instead of one per key.
+// The kept set {key > T} U {the newest ties of key == T} is then written in ascending
+// index order through a block-wide ballot/popcount scan, followed by the recent window
+// [c, n), which is kept unconditionally.  Ties go to the larger index (the newer key).
+#include "launch.h"
+
+namespace infmllm {
+
+namespace {
+
+constexpr int TPB = 1024;
+constexpr int NW = TPB / 64;
+
+__device__ __forceinline__ uint32_t order_key(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);    // larger float <=> larger key
+}
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+// Adds 1 to hist[digit] for every active lane whose `on` is true, one LDS atomic per distinct
+// digit per wavefront.
+__device__ __forceinline__ void wave_histogram(uint32_t* hist, uint32_t digit, bool on)
+{
+    uint64_t todo = __ballot(on);
+    while (todo) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const uint32_t dl = __shfl(digit, leader);
+        const uint64_t same = __ballot(on && digit == dl);
+        if (lane_id() == leader) atomicAdd(&hist[dl], (uint32_t)__popcll(same));
+        todo &= ~same;
+    }
+}
+
+__global__ void __launch_bounds__(TPB)
+select_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __restrict__ userI,
+              int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t s_prefix, s_remaining, s_ties;
+    __shared__ uint32_t wave_eq[NW], wave_keep[NW];
+    __shared__ uint32_t run_eq, run_keep;
+
+    const int h = blockIdx.x;
+    const float* W = Wb + (size_t)h * cap;
+    int32_t* Ih = I + (size_t)h * B;
+    int32_t* Uh = userI ? userI + (size_t)h * B : nullptr;
+
+    if (r > 0) {
+        // ---- radix select: key of the r-th largest -------------------------------------
+        if (threadIdx.x == 0) { s_prefix = 0; s_remaining = (uint32_t)r; }
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            for (int x = threadIdx.x; x < 256; x += TPB) hist[x] = 0;
+            __syncthreads();
+            const uint32_t prefix = s_prefix;
+            const uint32_t himask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+            for (int j0 = 0; j0 < cnd; j0 += TPB) {
+                const int j = j0 + threadIdx.x;
+                const bool in = j < cnd;
+                const uint32_t key = in ? order_key(W[j]) : 0u;
+                const bool on = in && ((key & himask) == prefix);
+                wave_histogram(hist, (key >> shift) & 0xffu, on);
+            }
+            __syncthreads();
+            if (threadIdx.x < 64) {
+                // wavefront 0 walks the bins from the top; lane l owns bins 255-4l .. 252-4l
+                const int l = threadIdx.x;
+                uint32_t c0 = hist[255 - 4 * l], c1 = hist[254 - 4 * l], c2 = hist[253 - 4 * l], c3 = hist[252 - 4 * l];
+                uint32_t mine = c0 + c1 + c2 + c3, incl = mine;
+                for (int o = 1; o < 64; o <<= 1) {
+                    const uint32_t up = __shfl_up(incl, o);
+                    if (l >= o) incl += up;
+                }
+                const uint32_t before = incl - mine;          // keys in higher bins than my four
+                const uint32_t need = s_remaining;
+                if (before < need && need <= incl) {          // the r-th largest falls in my bins
+                    uint32_t acc = before;
+                    int bin = 255 - 4 * l;
+                    uint32_t cnt = c0;
+                    if (acc + cnt < need) { acc += cnt; --bin; cnt = c1;
+                        if (acc + cnt < need) { acc += cnt; --bin; cnt = c2;
+                            if (acc + cnt < need) { acc += cnt; --bin; cnt = c3; } } }
+                    s_prefix = prefix | ((uint32_t)bin << shift);
+                    s_remaining = need - acc;                 // still to take inside that bin
+                    s_ties = cnt;                             // after the last pass: keys == T
+                }
+            }
+            __syncthreads();
+        }
+        const uint32_t T = s_prefix;
+        const uint32_t skip_eq = s_ties - s_remaining;        // oldest ties that are dropped
+        if (threadIdx.x == 0) { run_eq = 0; run_keep = 0; }
+        __syncthreads();
+
+        // ---- ordered write of the kept candidates -----------------------------------------
+        const int w = threadIdx.x >> 6, l = lane_id();
+        const uint64_t below = (l == 0) ? 0ull : (~0ull >> (64 - l));
+        for (int j0 = 0; j0 < cnd; j0 += TPB) {
+            const int j = j0 + threadIdx.x;
+            const uint32_t key = (j < cnd) ? order_key(W[j]) : 0u;
+            const bool gt = (j < cnd) && key > T;
+            const bool eq = (j < cnd) && key == T;
+            const uint64_t beq = __ballot(eq);
+            if (l == 0) wave_eq[w] = (uint32_t)__popcll(beq);
+            __syncthreads();
+            uint32_t eq_rank = run_eq + (uint32_t)__popcll(beq & below);
+            for (int x = 0; x < w; ++x) eq_rank += wave_eq[x];
+            const bool keep = gt || (eq && eq_rank >= skip_eq);
+            const uint64_t bk = __ballot(keep);
+            if (l == 0) wave_keep[w] = (uint32_t)__popcll(bk);
+            __syncthreads();
+            uint32_t dst = run_keep + (uint32_t)__popcll(bk & below);
+            for (int x = 0; x < w; ++x) dst += wave_keep[x];
+            if (keep) {
+                Ih[dst] = j;
+                if (Uh) Uh[dst] = j;
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                uint32_t te = 0, tk = 0;
+                for (int x = 0; x < NW; ++x) { te += wave_eq[x]; tk += wave_keep[x]; }
+                run_eq += te;
+                run_keep += tk;
+            }
+            __syncthreads();
+        }
+    }
+    // ---- recent window: [c, n) -------------------------------------------------------------
+    for (int x = threadIdx.x; x < R; x += TPB) {
+        Ih[r + x] = cnd + x;
+        if (Uh) Uh[r + x] = cnd + x;
+    }
+    if (user_count && h == 0 && threadIdx.x == 0) *user_count = B;
+}
+
+}  // namespace
+
+hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, int32_t* user_I,
+                         int32_t* user_count, hipStream_t st)
+{
+    const int cnd = n - g.R, r = g.B - g.R;
+    hipLaunchKernelGGL(select_kernel, dim3(g.Hkv), dim3(TPB), 0, st, Wb, I, user_I, user_count, cnd, r, g.R,
+                       g.B, g.cap);
+    return hipGetLastError();
+}
+
+}  // namespace infmllm

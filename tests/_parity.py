@@ -1,0 +1,78 @@
+"""Lock-step comparison of the HIP library with the fp64 oracle on the same seeded chunks.
+
+Output bar: max-abs error 2e-2 for bf16 streams, 1e-4 for fp32 streams.
+Retained sets: identical, except that keys whose fp64 biased score lies within 1e-5
+(relative) of the r-th largest may be swapped; after such a swap the oracle adopts the GPU's
+set so that later steps stay comparable.
+"""
+import numpy as np
+import torch
+
+OUT_TOL = {torch.bfloat16: 2e-2, torch.float32: 1e-4}
+BAND = 1e-5
+
+
+def check_retained(I_gpu, I_orc, Wb, n, budget, recent):
+    """I_gpu, I_orc: [Hkv, count] int arrays.  Wb: oracle biased scores [Hkv, c] or None.
+    Returns the number of (in-band) swapped keys."""
+    assert I_gpu.shape == I_orc.shape, (I_gpu.shape, I_orc.shape)
+    count = I_gpu.shape[1]
+    assert count == min(n, budget)
+    assert (np.diff(I_gpu, axis=1) > 0).all(), "retained indices are not strictly ascending"
+    assert I_gpu.min() >= 0 and I_gpu.max() < n
+    keep_recent = min(recent, n)
+    if keep_recent:
+        assert (I_gpu[:, count - keep_recent:] == np.arange(n - keep_recent, n)).all(), "recent window not retained"
+    swaps = 0
+    for h in range(I_gpu.shape[0]):
+        g, o = set(I_gpu[h].tolist()), set(I_orc[h].tolist())
+        if g == o:
+            continue
+        assert Wb is not None, "sets differ in a step that does not evict"
+        r = budget - recent
+        wr = np.sort(Wb[h])[::-1][r - 1]                      # r-th largest fp64 score
+        diff = np.array(sorted(g ^ o))
+        off = np.abs(Wb[h][diff] - wr)
+        assert (off <= BAND * abs(wr)).all(), (
+            "head %d: retained sets differ outside the tie band: idx %s, |W-W_r| %s, W_r %g"
+            % (h, diff[:8], off[:8], wr))
+        swaps += len(diff) // 2
+    return swaps
+
+
+class LockStep:
+    """Drives a binding.Stream and an OracleStream with the same chunks."""
+
+    def __init__(self, gpu, oracle):
+        self.gpu, self.oracle = gpu, oracle
+        self.swaps = 0
+        self.max_err = 0.0
+        self.steps = 0
+
+    def step(self, q, k, v, check_state=False):
+        dev = self.gpu.device
+        out_g, ret_g, n_g = self.gpu.step(q.to(dev), k.to(dev), v.to(dev))
+        t = len(self.oracle)
+        out_o = self.oracle.attend(q.double().numpy(), k.double().numpy(), v.double().numpy())
+        n = t + q.shape[0]
+        err = float(np.abs(out_g.double().cpu().numpy() - out_o).max())
+        self.max_err = max(self.max_err, err)
+        assert np.isfinite(err) and err <= OUT_TOL[self.gpu.dtype], "step %d: attention output off by %g" % (self.steps, err)
+        count = int(n_g.item())
+        assert count == min(n, self.gpu.budget) == len(self.gpu)
+        sc = self.oracle.scores()
+        I_o = self.oracle.select()
+        I_g = ret_g.cpu().numpy()[:, :count]
+        self.swaps += check_retained(I_g, I_o, None if sc is None else sc[1], n, self.gpu.budget, self.gpu.recent)
+        self.oracle.commit(I_g)
+        if check_state:
+            self.check_state()
+        self.steps += 1
+        return out_g, I_g
+
+    def check_state(self):
+        K, V, pos, score = self.gpu.export()
+        Ko, Vo, po = self.oracle.export()
+        assert (pos.cpu().numpy() == po).all(), "stream positions differ"
+        assert (K.double().cpu().numpy() == Ko).all() and (V.double().cpu().numpy() == Vo).all(), "cache rows differ"
+        assert (self.gpu.positions().cpu().numpy() == po).all()

@@ -1,0 +1,92 @@
+"""GPU parity: the HIP library against the fp64 oracle, element by element, through the C ABI.
+
+Inputs are seeded and synthetic (paper_2409_09086_amd.workloads); the oracle runs on the host in
+the same process.  Bars: attention output max-abs 2e-2 (bf16) / 1e-4 (fp32); retained sets
+identical up to keys within 1e-5 relative of the r-th largest fp64 score.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import OracleStream
+from paper_2409_09086_amd import binding as B
+from paper_2409_09086_amd.workloads import CONFIGS, ChunkStream, random_chunk
+from _parity import LockStep
+
+pytestmark = pytest.mark.gpu
+DT = {"fp32": torch.float32, "bf16": torch.bfloat16}
+
+
+def pair(budget, recent, heads, kv, d, dtype, bias, max_chunk=None, impl=None, scale=None):
+    gpu = B.Stream(budget, recent, heads, kv, d, dtype=DT[dtype], bias=bias, max_chunk=max_chunk, impl=impl, scale=scale)
+    orc = OracleStream(budget, recent, heads, kv, d, bias=float(np.float32(bias)),
+                       scale=None if scale is None else float(np.float32(scale)))
+    if scale is None:
+        orc_scale = float(np.float32(1.0 / np.sqrt(d)))
+        orc = OracleStream(budget, recent, heads, kv, d, bias=float(np.float32(bias)), scale=orc_scale)
+    return LockStep(gpu, orc)
+
+
+@pytest.mark.parametrize("bias", [0.0, 1e-4, 1e-2, 1.0, 512.0])
+def test_cfg1_tiny_fp32_stream(bias):
+    cfg = CONFIGS["cfg1"]
+    ls = pair(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, cfg.dtype, bias, max_chunk=cfg.max_chunk)
+    for step, (q, k, v) in zip(range(cfg.steps), ChunkStream(cfg)):
+        print("cfg1 bias", bias, "step", step, flush=True)
+        ls.step(q, k, v, check_state=True)
+    assert len(ls.gpu) == cfg.budget and ls.gpu.streamed == cfg.steps * cfg.chunk
+    print("max err %.3g swaps %d" % (ls.max_err, ls.swaps))
+
+
+@pytest.mark.parametrize("impl", [1, 0])
+@pytest.mark.parametrize("heads,kv,d,budget,recent,chunks", [
+    (4, 4, 128, 192, 64, [64, 64, 64, 64, 64, 64]),
+    (8, 2, 128, 160, 48, [100, 37, 64, 1, 129, 77, 5, 160]),      # GQA, ragged, L=1, L up to budget
+    (4, 2, 64, 96, 96, [32, 64, 50, 50]),                           # r = 0: pure window
+    (2, 2, 64, 128, 0, [64, 64, 64, 64]),                           # R = 0: nothing pinned
+    (4, 1, 128, 200, 150, [70, 70, 70, 70, 70]),                    # R > L
+])
+def test_small_bf16_streams(impl, heads, kv, d, budget, recent, chunks):
+    ls = pair(budget, recent, heads, kv, d, "bf16", 1e-3, max_chunk=max(chunks), impl=impl)
+    for step, L in enumerate(chunks):
+        print("bf16 impl", impl, (heads, kv, d, budget, recent), "step", step, "L", L, flush=True)
+        q, k, v = random_chunk(100 + step, L, heads, kv, d, "bf16")
+        ls.step(q, k, v, check_state=True)
+    print("max err %.3g swaps %d" % (ls.max_err, ls.swaps))
+
+
+def test_import_then_step_matches_oracle():
+    heads, kv, d, budget, recent, L = 4, 2, 128, 128, 32, 48
+    ls = pair(budget, recent, heads, kv, d, "bf16", 1e-2, max_chunk=L, impl=1)
+    g = torch.Generator().manual_seed(7)
+    K = torch.randn((kv, budget, d), generator=g).bfloat16()
+    V = torch.randn((kv, budget, d), generator=g).bfloat16()
+    pos = torch.arange(0, 3 * budget, 3, dtype=torch.int32).repeat(kv, 1)
+    ls.gpu.load(K.cuda(), V.cuda(), pos.cuda().contiguous(), 5000)
+    ls.oracle.load(K.double().numpy(), V.double().numpy(), pos.numpy(), 5000)
+    q, k, v = random_chunk(8, L, heads, kv, d, "bf16")
+    ls.step(q, k, v, check_state=True)
+    assert ls.gpu.streamed == 5000 + L
+    _, _, p, score = ls.gpu.export()
+    score = score.cpu().numpy()
+    assert np.isinf(score[:, budget - recent:]).all() and np.isfinite(score[:, : budget - recent]).all()
+
+
+def test_step_errors_leave_the_stream_unchanged():
+    s = B.Stream(64, 16, 2, 2, 64, dtype=torch.bfloat16, max_chunk=32, impl=1)
+    q, k, v = [x.cuda() for x in random_chunk(1, 33, 2, 2, 64, "bf16")]
+    with pytest.raises(B.InfMLLMError) as e:
+        s.step(q, k, v)
+    assert e.value.code == B.ECAPACITY and len(s) == 0 and s.streamed == 0
+
+
+@pytest.mark.parametrize("name,steps", [("cfg2", 10), ("cfg3", 6)])
+def test_full_shape_streams_lockstep(name, steps):
+    """The real layer shapes in the launch configuration the benchmark times: warm-up plus the
+    first evicting steps, every output element and every retained set against the oracle."""
+    cfg = CONFIGS[name]
+    ls = pair(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, cfg.dtype, cfg.bias, max_chunk=cfg.max_chunk)
+    for step, (q, k, v) in zip(range(steps), ChunkStream(cfg)):
+        print(name, "step", step, flush=True)
+        ls.step(q, k, v, check_state=(step == steps - 1))
+    print("%s: max err %.3g swaps %d" % (name, ls.max_err, ls.swaps), flush=True)
