@@ -14,8 +14,8 @@
  *   - The library never allocates or frees device memory.  All device memory, including
  *     the workspace that holds the cache, is the caller's and must stay valid until the
  *     attached HIP stream has passed the last call that used it.
- *   - Calls only enqueue work on the attached HIP stream and return; none synchronises
- *     except infmllm_stream_len, which needs no device access at all.
+ *   - Calls only enqueue work on the attached HIP stream and return; none waits for the
+ *     device except infmllm_stream_profile_read.
  *   - Every function that returns int returns INFMLLM_OK or a negative INFMLLM_E* code and
  *     never throws or aborts; infmllm_last_error() gives a message for the calling thread's
  *     last failure.  A failed call leaves the stream as it was.
@@ -154,6 +154,32 @@ int infmllm_stream_import(infmllm_stream_t* s, const void* K, const void* V, con
  * step did not evict.  Errors: EINVAL, ESTATE, EHIP.
  */
 int infmllm_stream_last_scores(infmllm_stream_t* s, float* w, int* n_candidates);
+
+/* Kernels of one step, as indexed by the profiling calls below. */
+enum {
+    INFMLLM_K_APPEND = 0,
+    INFMLLM_K_ATTN = 1,
+    INFMLLM_K_SCORE = 2,
+    INFMLLM_K_SELECT = 3,
+    INFMLLM_K_COMPACT = 4,
+    INFMLLM_K_COUNT = 5
+};
+
+/*
+ * Measurement: brackets every kernel of the next max_steps steps with HIP events on the
+ * attached stream (max_steps = 0 switches this off and releases the events).  The events cost
+ * a few microseconds per step, so whole-step throughput is measured with profiling off.
+ * Errors: EINVAL (max_steps outside 0..4096), ESTATE (not attached), EHIP.
+ */
+int infmllm_stream_profile(infmllm_stream_t* s, int max_steps);
+
+/*
+ * Measurement: waits for the recorded events and returns, per kernel, the summed duration in
+ * milliseconds (ms, host float[INFMLLM_K_COUNT]) and the number of launches that were timed
+ * (launches, host int[INFMLLM_K_COUNT]); then starts over with the same capacity.  This is the
+ * only call that blocks the host.  Errors: EINVAL, EHIP.
+ */
+int infmllm_stream_profile_read(infmllm_stream_t* s, float* ms, int* launches);
 
 /* Message for the calling thread's most recent failure ("" if none).  Never null. */
 const char* infmllm_last_error(void);

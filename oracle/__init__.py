@@ -55,6 +55,11 @@ def _load():
     return _lib
 
 
+def threads():
+    """OpenMP threads the oracle's head-parallel loop uses on this host."""
+    return int(_load().oracle_threads())
+
+
 def _f64(a):
     return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
 

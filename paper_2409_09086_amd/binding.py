@@ -21,7 +21,9 @@ EXPORTS = [
     "infmllm_stream_attach", "infmllm_step", "infmllm_stream_len", "infmllm_stream_streamed",
     "infmllm_stream_positions", "infmllm_stream_export", "infmllm_stream_import",
     "infmllm_stream_last_scores", "infmllm_last_error", "infmllm_stream_destroy",
+    "infmllm_stream_profile", "infmllm_stream_profile_read",
 ]
+KERNELS = ["append", "attn", "score", "select", "compact"]
 
 _lib = None
 
@@ -53,6 +55,8 @@ def lib():
         L.infmllm_stream_export.argtypes = [P, P, P, P, P]
         L.infmllm_stream_import.argtypes = [P, P, P, P, I, ctypes.c_int64]
         L.infmllm_stream_last_scores.argtypes = [P, P, ctypes.POINTER(I)]
+        L.infmllm_stream_profile.argtypes = [P, I]
+        L.infmllm_stream_profile_read.argtypes = [P, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(I)]
         L.infmllm_last_error.restype = ctypes.c_char_p
         L.infmllm_stream_destroy.argtypes = [P]
         L.infmllm_stream_destroy.restype = None
@@ -158,6 +162,16 @@ class Stream:
             self._h, _dev_ptr(K, self.dtype, (self.kv_heads, n, self.head_dim), "K"),
             _dev_ptr(V, self.dtype, (self.kv_heads, n, self.head_dim), "V"),
             _dev_ptr(pos, torch.int32, (self.kv_heads, n), "pos"), n, int(streamed)))
+
+    def profile(self, max_steps):
+        _check(lib().infmllm_stream_profile(self._h, int(max_steps)))
+
+    def profile_read(self):
+        """{kernel: (total ms, launches)} of the steps recorded since the last read."""
+        ms = (ctypes.c_float * len(KERNELS))()
+        cnt = (ctypes.c_int * len(KERNELS))()
+        _check(lib().infmllm_stream_profile_read(self._h, ms, cnt))
+        return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(KERNELS)}
 
     def last_scores(self):
         """Biased scores W' [kv_heads, c] of the most recent evicting step, or None."""

@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "launch.h"
 
@@ -53,6 +54,22 @@ struct infmllm_stream {
     float* lse;          // [Hq][max_chunk]
     float* Wb;           // [Hkv][cap]
     int32_t* I;          // [Hkv][B]
+    // optional per-kernel timing: one event pair per kernel per step, up to prof_cap steps
+    std::vector<hipEvent_t> prof_ev;   // [prof_cap][INFMLLM_K_COUNT][2]
+    std::vector<char> prof_used;       // [prof_cap][INFMLLM_K_COUNT]
+    int prof_cap = 0, prof_steps = 0;
+
+    void mark(int kernel, int edge)
+    {
+        if (prof_steps >= prof_cap) return;
+        const size_t slot = (size_t)prof_steps * INFMLLM_K_COUNT + kernel;
+        if (hipEventRecord(prof_ev[slot * 2 + edge], st) == hipSuccess && edge == 1) prof_used[slot] = 1;
+    }
+    void drop_events()
+    {
+        for (hipEvent_t e : prof_ev) (void)hipEventDestroy(e);
+        prof_ev.clear(); prof_used.clear(); prof_cap = 0; prof_steps = 0;
+    }
 
     struct Layout {
         size_t K[2], V[2], pos[2], score[2], lse, Wb, I, total;
@@ -110,7 +127,12 @@ int infmllm_stream_create(int budget, int recent, int heads, int kv_heads, int h
     return INFMLLM_OK;
 }
 
-void infmllm_stream_destroy(infmllm_stream_t* s) { delete s; }
+void infmllm_stream_destroy(infmllm_stream_t* s)
+{
+    if (!s) return;
+    s->drop_events();
+    delete s;
+}
 
 int infmllm_stream_set_param(infmllm_stream_t* s, int which, double value)
 {
@@ -189,10 +211,14 @@ int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* 
     const bool mfma = (s->dtype == INFMLLM_BF16 && s->impl == 0);
     hipError_t e;
 
+    s->mark(INFMLLM_K_APPEND, 0);
     if ((e = launch_append(g, cur, k, v, t, L, s->streamed, s->st)) != hipSuccess) return fail_hip(e, "step: append");
+    s->mark(INFMLLM_K_APPEND, 1);
+    s->mark(INFMLLM_K_ATTN, 0);
     e = mfma ? launch_attn_mfma(g, cur, q, t, L, out, s->lse, s->st)
              : launch_attn_simple(g, cur, q, t, L, out, s->lse, s->st);
     if (e != hipSuccess) return fail_hip(e, "step: attention");
+    s->mark(INFMLLM_K_ATTN, 1);
 
     if (n <= g.B) {
         // the chunk fits: nothing is evicted
@@ -200,18 +226,65 @@ int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* 
         s->len = n;
         s->last_cnd = 0;
     } else {
+        s->mark(INFMLLM_K_SCORE, 0);
         e = mfma ? launch_score_mfma(g, cur, q, s->lse, t, L, s->Wb, s->st)
                  : launch_score_simple(g, cur, q, s->lse, t, L, s->Wb, s->st);
         if (e != hipSuccess) return fail_hip(e, "step: score");
+        s->mark(INFMLLM_K_SCORE, 1);
+        s->mark(INFMLLM_K_SELECT, 0);
         if ((e = launch_select(g, s->Wb, n, s->I, retained, n_retained, s->st)) != hipSuccess)
             return fail_hip(e, "step: select");
+        s->mark(INFMLLM_K_SELECT, 1);
         const CacheView& nxt = s->cache[s->cur ^ 1];
+        s->mark(INFMLLM_K_COMPACT, 0);
         if ((e = launch_compact(g, cur, nxt, s->I, s->Wb, n, s->st)) != hipSuccess) return fail_hip(e, "step: compact");
+        s->mark(INFMLLM_K_COMPACT, 1);
         s->cur ^= 1;
         s->len = g.B;
         s->last_cnd = n - g.R;
     }
     s->streamed += L;
+    if (s->prof_steps < s->prof_cap) ++s->prof_steps;
+    return INFMLLM_OK;
+}
+
+int infmllm_stream_profile(infmllm_stream_t* s, int max_steps)
+{
+    if (!s) return fail(INFMLLM_EINVAL, "profile: stream is null");
+    if (!s->attached) return fail(INFMLLM_ESTATE, "profile: stream has no workspace attached");
+    if (max_steps < 0 || max_steps > 4096) return fail(INFMLLM_EINVAL, "profile: max_steps must lie in 0..4096");
+    s->drop_events();
+    const size_t nev = (size_t)max_steps * INFMLLM_K_COUNT * 2;
+    s->prof_ev.reserve(nev);
+    for (size_t i = 0; i < nev; ++i) {
+        hipEvent_t ev;
+        hipError_t e = hipEventCreate(&ev);
+        if (e != hipSuccess) { s->drop_events(); return fail_hip(e, "profile: hipEventCreate"); }
+        s->prof_ev.push_back(ev);
+    }
+    s->prof_used.assign((size_t)max_steps * INFMLLM_K_COUNT, 0);
+    s->prof_cap = max_steps;
+    s->prof_steps = 0;
+    return INFMLLM_OK;
+}
+
+int infmllm_stream_profile_read(infmllm_stream_t* s, float* ms, int* launches)
+{
+    if (!s || !ms || !launches) return fail(INFMLLM_EINVAL, "profile_read: null argument");
+    for (int k = 0; k < INFMLLM_K_COUNT; ++k) { ms[k] = 0.f; launches[k] = 0; }
+    for (int step = 0; step < s->prof_steps; ++step)
+        for (int k = 0; k < INFMLLM_K_COUNT; ++k) {
+            const size_t slot = (size_t)step * INFMLLM_K_COUNT + k;
+            if (!s->prof_used[slot]) continue;
+            hipError_t e = hipEventSynchronize(s->prof_ev[slot * 2 + 1]);
+            float dt = 0.f;
+            if (e == hipSuccess) e = hipEventElapsedTime(&dt, s->prof_ev[slot * 2], s->prof_ev[slot * 2 + 1]);
+            if (e != hipSuccess) return fail_hip(e, "profile_read: event");
+            ms[k] += dt;
+            ++launches[k];
+            s->prof_used[slot] = 0;
+        }
+    s->prof_steps = 0;
     return INFMLLM_OK;
 }
 
