@@ -87,8 +87,8 @@ size_t infmllm_stream_workspace_bytes(const infmllm_stream_t* s);
  * infmllm_stream_workspace_bytes(s) bytes, caller-owned) and the HIP stream (a
  * hipStream_t passed as void*, null for the default stream) all later work is enqueued
  * on.  The workspace holds the cache (two copies of K and V of budget + max_chunk rows per
- * kv-head, stream positions and scores) and per-step temporaries; its contents need not be
- * initialised.  The cache starts empty.  Errors: EINVAL (null/misaligned workspace),
+ * kv-head, stream positions and scores) and per-step temporaries; attach enqueues a clear of
+ * the whole workspace on that stream.  The cache starts empty.  Errors: EINVAL (null/misaligned workspace),
  * ENOMEM (too small), ESTATE (already attached), EHIP.
  */
 int infmllm_stream_attach(infmllm_stream_t* s, void* dev_workspace, size_t bytes, void* hip_stream);

@@ -78,7 +78,7 @@ struct infmllm_stream {
     {
         Layout L;
         size_t off = 0;
-        const size_t kv = up((size_t)g.Hkv * g.cap * g.d * g.elt);
+        const size_t kv = up(((size_t)g.Hkv * g.cap + CACHE_PAD_ROWS) * g.d * g.elt);
         const size_t ps = up((size_t)g.Hkv * g.cap * 4);
         for (int i = 0; i < 2; ++i) {
             L.K[i] = off; off += kv;
@@ -178,6 +178,11 @@ int infmllm_stream_attach(infmllm_stream_t* s, void* ws, size_t bytes, void* hip
         return fail(INFMLLM_EINVAL, "attach: budget + max_chunk = %d rows is beyond what the plain-arithmetic "
                                     "attention kernel keeps in LDS (38400)", s->g.cap);
     char* base = (char*)ws;
+    {
+        // kernels that read whole key tiles rely on every byte of the cache being finite
+        hipError_t e = hipMemsetAsync(ws, 0, L.total, (hipStream_t)hip_stream);
+        if (e != hipSuccess) return fail_hip(e, "attach: clearing the workspace");
+    }
     for (int i = 0; i < 2; ++i) {
         s->cache[i].K = base + L.K[i];
         s->cache[i].V = base + L.V[i];

@@ -20,6 +20,8 @@
 //
 // fp32 is kept from the MFMA accumulators to the score: the bf16 rounding of P is applied only
 // to the copy that feeds the P.V product.
+#include <cstdlib>
+
 #include "launch.h"
 
 namespace infmllm {
@@ -34,12 +36,20 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 
 constexpr float LOG2E = 1.4426950408889634f;
+constexpr int FWD_MAX_TILE = CACHE_PAD_ROWS;     // a key tile may run this far past the last cached row
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ float xhalf(float x) { return __shfl_xor(x, 32); }   // the other half-wave's value
+
+// max of a value and the other half-wave's value (lane l with lane l ^ 32), in every lane
+__device__ __forceinline__ float xhalf_max(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 
 // ---------------------------------------------------------------------------------------------
 // attn_fwd
@@ -57,33 +67,53 @@ struct FwdCfg {
     static constexpr int VP = D * 2 + 64;              // V row pitch: 4 rows x 64 B windows tile the banks
     static constexpr int CPR = D / 8;                  // 16-byte chunks per row
     static constexpr int NLD = TILE * CPR / NT;        // chunks per thread per tensor
-    static constexpr int KBYTES = TILE * KP, VBYTES = TILE * VP;
+    static constexpr int LD_RSTEP = NT / CPR;          // rows between a thread's consecutive chunks
+    static constexpr int KBYTES = TILE * KP, VBYTES = TILE * VP, BUF = KBYTES + VBYTES;
+    static constexpr int NBUF = (2 * BUF <= 160 * 1024) ? 2 : 1;
     static constexpr int OREG = D / 2;                 // fp32 accumulators of O^T per lane
     static constexpr int MERGE = (KW - 1) * RB * 64 * (OREG + 2) * 4;
-    static constexpr int LDS = (KBYTES + VBYTES) > MERGE ? (KBYTES + VBYTES) : MERGE;
-    static_assert(TILE * CPR % NT == 0, "tile must split evenly over the threads");
+    static constexpr int LDS = (NBUF * BUF) > MERGE ? (NBUF * BUF) : MERGE;
+    static_assert(TILE * CPR % NT == 0 && NT % CPR == 0, "tile must split evenly over the threads");
+    static_assert(TILE <= FWD_MAX_TILE, "workspace padding assumes smaller tiles");
 };
+
+// A reference maximum is only moved when a row's running maximum has grown by more than this
+// (base-2 exponent): exp2(s - ref) then stays below 2^8, well inside bf16/fp32 range, and the
+// accumulators are rescaled a handful of times per row instead of once per tile.
+constexpr float RESCALE_TAU = 8.0f;
 
 template <int D, int RB, int KW, int KVB>
 __global__ void __launch_bounds__(64 * RB * KW)
 attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                 uint16_t* __restrict__ out, float* __restrict__ lse2, int t, int L, int Hq, int G, int cap,
-                int max_chunk, int hpw, float c /* scale * log2(e) */)
+                int max_chunk, int hpw, int ntile, int ny, float c /* scale * log2(e) */)
 {
     using C = FwdCfg<D, RB, KW, KVB>;
     __shared__ __attribute__((aligned(16))) char smem[C::LDS];
-    char* const sK = smem;
-    char* const sV = smem + C::KBYTES;
 
+    // Workgroup -> (row tile, head group).  Consecutive workgroup ids go round-robin over the 8
+    // XCDs; all row tiles of one kv-head are given ids of one residue class so that they share
+    // that XCD's L2 copy of the head's K and V.
+    int bx, by;
+    {
+        const int bid = blockIdx.x;
+        if ((ny & 7) == 0) {
+            const int xcd = bid & 7, li = bid >> 3;
+            by = xcd + 8 * (li / ntile);
+            bx = ntile - 1 - li % ntile;                     // longest (most keys visible) tiles first
+        } else {
+            by = bid / ntile;
+            bx = ntile - 1 - bid % ntile;
+        }
+    }
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
     const int rb = wave % RB, kw = wave / RB;
     const int rbph = RB / hpw;                               // row blocks per head inside the workgroup
     const int ngrp = G / hpw;                                // head groups per kv-head
-    const int h = blockIdx.y / ngrp, hgrp = blockIdx.y % ngrp;
+    const int h = by / ngrp, hgrp = by % ngrp;
     const int g = h * G + hgrp * hpw + rb % hpw;             // query head of this wavefront
-    const int row0 = 32 * (blockIdx.x * rbph + rb / hpw);    // first query row of this wavefront
-    const int n = t + L;
-    const int wg_rows_end = min(L, 32 * (int)(blockIdx.x + 1) * rbph);
+    const int row0 = 32 * (bx * rbph + rb / hpw);            // first query row of this wavefront
+    const int wg_rows_end = min(L, 32 * (bx + 1) * rbph);
     const int n_end = t + wg_rows_end;                       // keys any row of the workgroup can see
     const int my_row = row0 + l32;
     const int my_lim = t + min(my_row, L - 1);               // last visible key of my row
@@ -99,8 +129,8 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
         const uint16_t* qp = q + ((size_t)(ok ? my_row : 0) * Hq + g) * D + 8 * hh;
 #pragma unroll
         for (int s = 0; s < D / 16; ++s) {
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (ok) v = *(const u32x4*)(qp + 16 * s);
+            u32x4 v = *(const u32x4*)(qp + 16 * s);
+            if (!ok) v = u32x4{0u, 0u, 0u, 0u};
             qf[s] = as_bf16x8(v);
         }
     }
@@ -110,120 +140,146 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
     for (int b = 0; b < D / 32; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[b][i] = 0.f;
-    float m_run = -__builtin_inff(), lsum = 0.f;
+    float m_ref = -__builtin_inff(), m_use = 0.f, lsum = 0.f;
 
-    // register staging of the next tile
+    // Register staging of the next tile.  A tile may run past the last cached row: the cache
+    // buffers are padded by FWD_MAX_TILE rows and hold only finite values, the logits of such
+    // rows are masked, and a finite V row times a zero weight adds nothing.
     u32x4 stK[C::NLD], stV[C::NLD];
+    uint32_t ld_off[C::NLD];                                 // element offsets inside a tile, loop-invariant
+#pragma unroll
+    for (int u = 0; u < C::NLD; ++u) ld_off[u] = (uint32_t)((tid / C::CPR + u * C::LD_RSTEP) * D + (tid % C::CPR) * 8);
     auto fetch = [&](int kv0) {
+        const uint16_t* kt = Kh + (size_t)kv0 * D;           // uniform: scalar base + per-lane 32-bit offset
+        const uint16_t* vt = Vh + (size_t)kv0 * D;
 #pragma unroll
         for (int u = 0; u < C::NLD; ++u) {
-            const int ch = tid + u * C::NT, r = ch / C::CPR, cc = ch % C::CPR;
-            const int kv = kv0 + r;
-            u32x4 a = {0u, 0u, 0u, 0u}, b = {0u, 0u, 0u, 0u};
-            if (kv < n) {
-                a = *(const u32x4*)(Kh + (size_t)kv * D + cc * 8);
-                b = *(const u32x4*)(Vh + (size_t)kv * D + cc * 8);
-            }
-            stK[u] = a;
-            stV[u] = b;
+            stK[u] = *(const u32x4*)(kt + ld_off[u]);
+            stV[u] = *(const u32x4*)(vt + ld_off[u]);
         }
     };
-    auto stash = [&]() {
+    const int st_k = (tid / C::CPR) * C::KP + (tid % C::CPR) * 16;
+    const int st_v = C::KBYTES + (tid / C::CPR) * C::VP + (tid % C::CPR) * 16;
+    auto stash = [&](int buf) {
+        char* base = smem + buf * C::BUF;
 #pragma unroll
         for (int u = 0; u < C::NLD; ++u) {
-            const int ch = tid + u * C::NT, r = ch / C::CPR, cc = ch % C::CPR;
-            *(u32x4*)(sK + r * C::KP + cc * 16) = stK[u];
-            *(u32x4*)(sV + r * C::VP + cc * 16) = stV[u];
+            *(u32x4*)(base + st_k + u * C::LD_RSTEP * C::KP) = stK[u];
+            *(u32x4*)(base + st_v + u * C::LD_RSTEP * C::VP) = stV[u];
         }
     };
+
+    // byte offsets of this lane's fragments inside a buffer
+    const int koff = (kw * C::SUB + l32) * C::KP + 16 * hh;
+    // transpose read: lane l of a 16-lane block supplies the address of key row l/4, 4 columns at 4*(l%4)
+    const int voff = C::KBYTES + (kw * C::SUB + 4 * hh + ((lane & 15) >> 2)) * C::VP +
+                     (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
 
     const int ntiles = (n_end + C::TILE - 1) / C::TILE;
     fetch(0);
+    if (C::NBUF == 2) {
+        stash(0);
+        if (ntiles > 1) fetch(C::TILE);
+        __syncthreads();
+    }
     for (int tile = 0; tile < ntiles; ++tile) {
         const int kv0 = tile * C::TILE;
-        __syncthreads();                                     // everyone is done with the previous tile
-        stash();
-        __syncthreads();
-        if (tile + 1 < ntiles) fetch(kv0 + C::TILE);
+        const int buf = (C::NBUF == 2) ? (tile & 1) : 0;
+        if (C::NBUF == 1) {
+            __syncthreads();                                 // everyone is done with the previous tile
+            stash(0);
+            __syncthreads();
+            if (tile + 1 < ntiles) fetch(kv0 + C::TILE);
+        }
+        const char* const kbase = smem + buf * C::BUF + koff;
+        const char* const vbase = smem + buf * C::BUF + voff;
 
         const int sub0 = kv0 + kw * C::SUB;                  // first key of my slice of the tile
-        if (sub0 >= wave_end) continue;                      // nothing visible for this wavefront
-
-        // ---- S^T = K . Q^T ---------------------------------------------------------------------
-        f32x16 acc[KVB];
+        if (sub0 < wave_end) {                               // else nothing visible for this wavefront
+            // ---- S^T = K . Q^T -----------------------------------------------------------------
+            f32x16 acc[KVB];
 #pragma unroll
-        for (int kb = 0; kb < KVB; ++kb) {
+            for (int kb = 0; kb < KVB; ++kb) {
+                bf16x8 kf[D / 16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[kb][i] = 0.f;
-            const char* kp = sK + (kw * C::SUB + 32 * kb + l32) * C::KP + 16 * hh;
+                for (int s = 0; s < D / 16; ++s) kf[s] = as_bf16x8(*(const u32x4*)(kbase + 32 * kb * C::KP + 32 * s));
 #pragma unroll
-            for (int s = 0; s < D / 16; ++s) {
-                const bf16x8 kf = as_bf16x8(*(const u32x4*)(kp + 32 * s));
-                acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], acc[kb], 0, 0, 0);
+                for (int i = 0; i < 16; ++i) acc[kb][i] = 0.f;
+#pragma unroll
+                for (int s = 0; s < D / 16; ++s)
+                    acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], acc[kb], 0, 0, 0);
             }
-        }
-        // ---- causal mask on tiles that reach past the first row's limit ------------------------
-        if (sub0 + C::SUB - 1 > t + row0) {
+            // ---- causal mask on tiles that reach past the first row's limit --------------------
+            if (sub0 + C::SUB - 1 > t + row0) {
+#pragma unroll
+                for (int kb = 0; kb < KVB; ++kb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int kv = sub0 + 32 * kb + 8 * (i / 4) + 4 * hh + (i % 4);
+                        if (kv > my_lim) acc[kb][i] = -__builtin_inff();
+                    }
+            }
+            // ---- online softmax, in-lane along the key axis, lazily moved reference ------------
+            float mx = acc[0][0];
 #pragma unroll
             for (int kb = 0; kb < KVB; ++kb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int kv = sub0 + 32 * kb + 8 * (i / 4) + 4 * hh + (i % 4);
-                    if (kv > my_lim) acc[kb][i] = -__builtin_inff();
-                }
-        }
-        // ---- online softmax, in-lane along the key axis ----------------------------------------
-        float mx = -__builtin_inff();
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[kb][i]);
+            mx = xhalf_max(mx) * c;
+            if (__any(mx > m_ref + RESCALE_TAU)) {
+                const float m_new = fmaxf(m_ref, mx);
+                const float mu = (m_new == -__builtin_inff()) ? 0.f : m_new;
+                const float alpha = fast_exp2(m_ref - mu);   // m_ref = -inf gives 0
+                m_ref = m_new;
+                m_use = mu;
+                lsum *= alpha;
 #pragma unroll
-        for (int kb = 0; kb < KVB; ++kb)
+                for (int b = 0; b < D / 32; ++b)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[kb][i]);
-        mx = fmaxf(mx, xhalf(mx));
-        const float m_new = fmaxf(m_run, mx * c);
-        const float m_use = (m_new == -__builtin_inff()) ? 0.f : m_new;
-        const float alpha = fast_exp2(m_run - m_use);
-        m_run = m_new;
-        if (__any(alpha != 1.0f)) {
-            lsum *= alpha;
+                    for (int i = 0; i < 16; ++i) o[b][i] *= alpha;
+            }
+            // ---- P (fp32 -> bf16 for the product) and O^T += V^T . P^T -------------------------
 #pragma unroll
-            for (int b = 0; b < D / 32; ++b)
+            for (int kb = 0; kb < KVB; ++kb) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) o[b][i] *= alpha;
-        }
-        // ---- P (fp32 -> bf16 for the product) and O^T += V^T . P^T -----------------------------
+                for (int tt = 0; tt < 2; ++tt) {
+                    bf16x4 vlo[D / 32], vhi[D / 32];
 #pragma unroll
-        for (int kb = 0; kb < KVB; ++kb) {
+                    for (int b = 0; b < D / 32; ++b) {
+                        const char* vp = vbase + (32 * kb + 16 * tt) * C::VP + 64 * b;
+                        vlo[b] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)vp);
+                        vhi[b] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(vp + 8 * C::VP));
+                    }
+                    bf16x8 pf;
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt) {
-                bf16x8 pf;
+                    for (int p = 0; p < 8; ++p) {
+                        const float e = fast_exp2(__builtin_fmaf(acc[kb][8 * tt + p], c, -m_use));
+                        lsum += e;
+                        pf[p] = (__bf16)e;
+                    }
 #pragma unroll
-                for (int p = 0; p < 8; ++p) {
-                    const float e = fast_exp2(__builtin_fmaf(acc[kb][8 * tt + p], c, -m_use));
-                    lsum += e;
-                    pf[p] = (__bf16)e;
-                }
-                // lane l of a 16-lane block supplies the address of key row (l/4), 4 columns at 4*(l%4)
-                const int j16 = lane & 15, blk = (lane >> 4) & 1;
-                const char* vp = sV + (kw * C::SUB + 32 * kb + 16 * tt + 4 * hh + (j16 >> 2)) * C::VP +
-                                 (16 * blk + 4 * (j16 & 3)) * 2;
-#pragma unroll
-                for (int b = 0; b < D / 32; ++b) {
-                    const bf16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(vp + 64 * b));
-                    const bf16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(vp + 64 * b + 8 * C::VP));
-                    const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-                    o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[b], 0, 0, 0);
+                    for (int b = 0; b < D / 32; ++b) {
+                        const bf16x8 vf = __builtin_shufflevector(vlo[b], vhi[b], 0, 1, 2, 3, 4, 5, 6, 7);
+                        o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[b], 0, 0, 0);
+                    }
                 }
             }
+        }
+        if (C::NBUF == 2) {
+            // the other buffer was last read one iteration ago, before the barrier that ended it
+            if (tile + 1 < ntiles) stash(buf ^ 1);
+            if (tile + 2 < ntiles) fetch(kv0 + 2 * C::TILE);
+            __syncthreads();
         }
     }
 
     // ---- merge the key ways of a query block ---------------------------------------------------
     if (KW > 1) {
-        __syncthreads();
+        if (C::NBUF == 1) __syncthreads();
         float* mg = (float*)smem;
         if (kw > 0) {
             float* w = mg + (size_t)((kw - 1) * RB + rb) * 64 * (C::OREG + 2);
-            w[lane] = m_run;
+            w[lane] = m_ref;
             w[64 + lane] = lsum;
 #pragma unroll
             for (int b = 0; b < D / 32; ++b)
@@ -235,15 +291,15 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
             for (int k2 = 1; k2 < KW; ++k2) {
                 const float* w = mg + (size_t)((k2 - 1) * RB + rb) * 64 * (C::OREG + 2);
                 const float m2 = w[lane], l2 = w[64 + lane];
-                const float mt = fmaxf(m_run, m2);
+                const float mt = fmaxf(m_ref, m2);
                 const float mu = (mt == -__builtin_inff()) ? 0.f : mt;
-                const float a1 = fast_exp2(m_run - mu), a2 = fast_exp2(m2 - mu);
+                const float a1 = fast_exp2(m_ref - mu), a2 = fast_exp2(m2 - mu);
                 lsum = lsum * a1 + l2 * a2;
 #pragma unroll
                 for (int b = 0; b < D / 32; ++b)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) o[b][i] = o[b][i] * a1 + w[(2 + b * 16 + i) * 64 + lane] * a2;
-                m_run = mt;
+                m_ref = mt;
             }
         }
     }
@@ -262,7 +318,7 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
             for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[b][4 * a + e] * inv);
             *(bf16x4*)(op + 32 * b + 8 * a + 4 * hh) = w;
         }
-    if (hh == 0) lse2[(size_t)g * max_chunk + my_row] = m_run + __builtin_log2f(ltot);
+    if (hh == 0) lse2[(size_t)g * max_chunk + my_row] = m_ref + __builtin_log2f(ltot);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -373,23 +429,36 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
 
 }  // namespace
 
+template <int D, int RB, int KW, int KVB>
+hipError_t launch_fwd_cfg(const Geometry& g, const CacheView& c, const void* q, int t, int L, void* out, float* lse,
+                          hipStream_t st)
+{
+    const int hpw = (RB % g.G == 0) ? g.G : ((g.G % RB == 0) ? RB : 1);
+    const int rbph = RB / hpw;
+    const int ntile = (L + 32 * rbph - 1) / (32 * rbph), ny = g.Hkv * (g.G / hpw);
+    hipLaunchKernelGGL((attn_fwd_kernel<D, RB, KW, KVB>), dim3(ntile * ny), dim3(64 * RB * KW), 0, st,
+                       (const uint16_t*)q, (const uint16_t*)c.K, (const uint16_t*)c.V, (uint16_t*)out, lse, t, L,
+                       g.Hq, g.G, g.cap, g.max_chunk, hpw, ntile, ny, g.scale * LOG2E);
+    return hipGetLastError();
+}
+
 hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const void* q, int t, int L, void* out,
                             float* lse, hipStream_t st)
 {
-    constexpr int RB = 4, KW = 1, KVB = 2;
-    const int hpw = (RB % g.G == 0) ? g.G : ((g.G % RB == 0) ? RB : 1);
-    const int rbph = RB / hpw;
-    const dim3 grid((L + 32 * rbph - 1) / (32 * rbph), g.Hkv * (g.G / hpw)), block(64 * RB * KW);
-    const float cc = g.scale * LOG2E;
-#define INFMLLM_FWD(DD)                                                                                  \
-    hipLaunchKernelGGL((attn_fwd_kernel<DD, RB, KW, KVB>), grid, block, 0, st, (const uint16_t*)q,       \
-                       (const uint16_t*)c.K, (const uint16_t*)c.V, (uint16_t*)out, lse, t, L, g.Hq, g.G, \
-                       g.cap, g.max_chunk, hpw, cc)
-    if (g.d == 128) INFMLLM_FWD(128);
-    else if (g.d == 64) INFMLLM_FWD(64);
-    else return hipErrorInvalidValue;
-#undef INFMLLM_FWD
-    return hipGetLastError();
+    static const int variant = [] { const char* e = getenv("INFMLLM_FWD"); return e ? atoi(e) : -1; }();
+    if (g.d == 64) return launch_fwd_cfg<64, 4, 1, 2>(g, c, q, t, L, out, lse, st);
+    if (g.d != 128) return hipErrorInvalidValue;
+    // 128 query rows per workgroup when that still gives every CU a workgroup, else 64 rows with
+    // the key tile split four ways inside the workgroup
+    const int blocks32 = g.Hq * ((L + 31) / 32);
+    const int v = variant >= 0 ? variant : (blocks32 >= 4 * 200 ? 1 : 2);
+    switch (v) {
+        case 1: return launch_fwd_cfg<128, 4, 2, 2>(g, c, q, t, L, out, lse, st);
+        case 2: return launch_fwd_cfg<128, 2, 4, 1>(g, c, q, t, L, out, lse, st);
+        case 3: return launch_fwd_cfg<128, 4, 2, 1>(g, c, q, t, L, out, lse, st);
+        case 4: return launch_fwd_cfg<128, 4, 1, 4>(g, c, q, t, L, out, lse, st);
+        default: return launch_fwd_cfg<128, 4, 1, 2>(g, c, q, t, L, out, lse, st);
+    }
 }
 
 hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const void* q, const float* lse, int t,

@@ -6,6 +6,11 @@
 
 namespace infmllm {
 
+// Every K and V buffer of the cache is followed by this many rows of padding, and the whole
+// workspace is zeroed when it is attached: the matrix-core attention kernel reads whole key
+// tiles and may run this far past the last cached row (into finite data it then masks).
+constexpr int CACHE_PAD_ROWS = 256;
+
 // Geometry of one stream, fixed at attach time.
 struct Geometry {
     int B;        // budget (rows kept after a step)

@@ -77,15 +77,19 @@ def test_host_state_machine_without_a_device():
     assert L.infmllm_stream_len(None) == -1 and L.infmllm_stream_workspace_bytes(None) == 0
 
 
-def test_step_argument_checks_after_a_fake_attach():
-    """attach only records pointers, so the host-side checks of step can be exercised with a
-    made-up workspace address as long as every call is refused before any launch."""
+@pytest.mark.gpu
+def test_step_argument_checks_after_attach():
+    """host-side checks of step on an attached stream: every call is refused before any launch"""
+    import torch
+    ws = torch.empty(1 << 22, dtype=torch.uint8, device="cuda:0")
+    addr = (ws.data_ptr() + 255) // 256 * 256
     L = B.lib()
     rc, h = make()
     assert L.infmllm_stream_set_param(h, B.PARAM_MAX_CHUNK, 8.0) == B.OK
     need = L.infmllm_stream_workspace_bytes(h)
-    assert L.infmllm_stream_attach(h, ctypes.c_void_p(1 << 20), need, None) == B.OK
-    assert L.infmllm_stream_attach(h, ctypes.c_void_p(1 << 20), need, None) == B.ESTATE
+    assert need < (1 << 22) - 256
+    assert L.infmllm_stream_attach(h, ctypes.c_void_p(addr), need, None) == B.OK
+    assert L.infmllm_stream_attach(h, ctypes.c_void_p(addr), need, None) == B.ESTATE
     assert L.infmllm_stream_set_param(h, B.PARAM_BIAS, 0.1) == B.ESTATE
     one = ctypes.c_void_p(256)
     assert L.infmllm_step(h, None, one, one, 4, one, None, None) == B.EINVAL
