@@ -54,6 +54,7 @@ struct infmllm_stream {
     float* lse;          // [Hq][max_chunk]
     float* Wb;           // [Hkv][cap]
     int32_t* I;          // [Hkv][B]
+    FwdScratch fwd;      // key-split partials of the matrix-core attention
     // optional per-kernel timing: one event pair per kernel per step, up to prof_cap steps
     std::vector<hipEvent_t> prof_ev;   // [prof_cap][INFMLLM_K_COUNT][2]
     std::vector<char> prof_used;       // [prof_cap][INFMLLM_K_COUNT]
@@ -72,7 +73,8 @@ struct infmllm_stream {
     }
 
     struct Layout {
-        size_t K[2], V[2], pos[2], score[2], lse, Wb, I, total;
+        size_t K[2], V[2], pos[2], score[2], lse, Wb, I, part_o, part_ml, total;
+        size_t part_rows;
     };
     Layout layout() const
     {
@@ -89,6 +91,11 @@ struct infmllm_stream {
         L.lse = off; off += up((size_t)g.Hq * g.max_chunk * 4);
         L.Wb = off; off += ps;
         L.I = off; off += up((size_t)g.Hkv * g.B * 4);
+        // key-split partials (bf16 streams): only chunks too short to fill the chip are split,
+        // so the scratch covers min(max_chunk, 4096) rows at up to 4 splits
+        L.part_rows = (g.elt == 2 && g.d == 128) ? (size_t)4 * (g.max_chunk < 4096 ? g.max_chunk : 4096) : 0;
+        L.part_o = off; off += up(L.part_rows * g.Hq * g.d * 4);
+        L.part_ml = off; off += up(L.part_rows * g.Hq * 2 * 4);
         L.total = off;
         return L;
     }
@@ -192,6 +199,9 @@ int infmllm_stream_attach(infmllm_stream_t* s, void* ws, size_t bytes, void* hip
     s->lse = (float*)(base + L.lse);
     s->Wb = (float*)(base + L.Wb);
     s->I = (int32_t*)(base + L.I);
+    s->fwd.part_o = (float*)(base + L.part_o);
+    s->fwd.part_ml = (float*)(base + L.part_ml);
+    s->fwd.part_rows = L.part_rows;
     s->st = (hipStream_t)hip_stream;
     s->cur = 0; s->len = 0; s->streamed = 0; s->last_cnd = 0;
     s->attached = true;
@@ -220,7 +230,7 @@ int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* 
     if ((e = launch_append(g, cur, k, v, t, L, s->streamed, s->st)) != hipSuccess) return fail_hip(e, "step: append");
     s->mark(INFMLLM_K_APPEND, 1);
     s->mark(INFMLLM_K_ATTN, 0);
-    e = mfma ? launch_attn_mfma(g, cur, q, t, L, out, s->lse, s->st)
+    e = mfma ? launch_attn_mfma(g, cur, q, t, L, out, s->lse, s->fwd, s->st)
              : launch_attn_simple(g, cur, q, t, L, out, s->lse, s->st);
     if (e != hipSuccess) return fail_hip(e, "step: attention");
     s->mark(INFMLLM_K_ATTN, 1);

@@ -23,33 +23,13 @@
 #include <cstdlib>
 
 #include "launch.h"
+#include "mfma_common.h"
 
 namespace infmllm {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
-
-constexpr float LOG2E = 1.4426950408889634f;
 constexpr int FWD_MAX_TILE = CACHE_PAD_ROWS;     // a key tile may run this far past the last cached row
-
-__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-__device__ __forceinline__ float xhalf(float x) { return __shfl_xor(x, 32); }   // the other half-wave's value
-
-// max of a value and the other half-wave's value (lane l with lane l ^ 32), in every lane
-__device__ __forceinline__ float xhalf_max(float x)
-{
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
 
 // ---------------------------------------------------------------------------------------------
 // attn_fwd
@@ -76,11 +56,6 @@ struct FwdCfg {
     static_assert(TILE * CPR % NT == 0 && NT % CPR == 0, "tile must split evenly over the threads");
     static_assert(TILE <= FWD_MAX_TILE, "workspace padding assumes smaller tiles");
 };
-
-// A reference maximum is only moved when a row's running maximum has grown by more than this
-// (base-2 exponent): exp2(s - ref) then stays below 2^8, well inside bf16/fp32 range, and the
-// accumulators are rescaled a handful of times per row instead of once per tile.
-constexpr float RESCALE_TAU = 8.0f;
 
 template <int D, int RB, int KW, int KVB>
 __global__ void __launch_bounds__(64 * RB * KW)
@@ -324,106 +299,140 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
 // ---------------------------------------------------------------------------------------------
 // score: W'[h][j] = (1/(G lq)) sum_{g in group h} sum_{i = L-lq}^{L-1} exp2(c q_i.k_j - lse2_i)
 //                   - (cnd-1-j) b / cnd
-// Workgroup = 4 wavefronts x 64 key columns; every scored row sees every candidate column, so
-// there is no mask inside the block.
+// Workgroup = 8 wavefronts: 4 column groups (32*CB key columns each, held in registers) x 2 row
+// groups that take alternate 32-row query blocks and add their partial column sums through LDS
+// at the end.  Query blocks are double-buffered in LDS.  Every scored row sees every candidate
+// column, so there is no mask inside the block.
 // ---------------------------------------------------------------------------------------------
-template <int D>
-__global__ void __launch_bounds__(256)
+template <int D, int CB>
+__global__ void __launch_bounds__(512)
 score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const float* __restrict__ lse2,
              float* __restrict__ Wb, int L, int lq, int Hq, int G, int cap, int max_chunk, int cnd, float c,
              float bias)
 {
     constexpr int QP = D * 2 + 16;                            // pitch of a staged query row
     constexpr int CPR = D / 8;
-    constexpr int NLD = 32 * CPR / 256;                       // 16-byte chunks per thread per 32-row block
-    __shared__ __attribute__((aligned(16))) char sQ[32 * QP];
-    __shared__ __attribute__((aligned(16))) float sL[32];
+    constexpr int NLD = 64 * CPR / 512;                       // 16-byte chunks per thread per pair of blocks
+    constexpr int QBYTES = 64 * QP;
+    constexpr int BUF = QBYTES + 64 * 4;                      // rows + their log-sum-exp
+    __shared__ __attribute__((aligned(16))) char smem[2 * BUF];
+    __shared__ float s_part[4 * CB * 32];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
+    const int cg = wave & 3, rg = wave >> 2;                  // column group, row group
     const int h = blockIdx.y;
-    const int col0 = blockIdx.x * 256 + wave * 64;
+    const int col0 = blockIdx.x * (128 * CB) + cg * (32 * CB);
 
     // key fragments: B operand of S = Q.K^T, lane (column l32, half hh) holds K[col][16s + 8hh .. +8)
-    bf16x8 kf[2][D / 16];
+    bf16x8 kf[CB][D / 16];
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
+    for (int cb = 0; cb < CB; ++cb) {
         const int col = col0 + 32 * cb + l32;
         const bool ok = col < cnd;
         const uint16_t* kp = K + ((size_t)h * cap + (ok ? col : 0)) * D + 8 * hh;
 #pragma unroll
         for (int s = 0; s < D / 16; ++s) {
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (ok) v = *(const u32x4*)(kp + 16 * s);
+            u32x4 v = *(const u32x4*)(kp + 16 * s);
+            if (!ok) v = u32x4{0u, 0u, 0u, 0u};
             kf[cb][s] = as_bf16x8(v);
         }
     }
-    f32x16 part[2];
+    f32x16 part[CB];
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+    for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) part[cb][i] = 0.f;
 
-    const int nblk = (lq + 31) / 32;
-    const int total = G * nblk;                               // 32-row blocks to sweep
-    u32x4 st[NLD > 0 ? NLD : 1];
+    const int nblk = (lq + 31) / 32;                          // 32-row blocks per query head
+    const int total = G * nblk;                               // blocks to sweep, two per iteration
+    const int niter = (total + 1) / 2;
+    u32x4 st[NLD];
     float stl = 0.f;
     auto fetch = [&](int it) {
-        const int g = h * G + it / nblk, i0 = L - lq + 32 * (it % nblk);
 #pragma unroll
         for (int u = 0; u < NLD; ++u) {
-            const int ch = tid + u * 256, r = ch / CPR, cc = ch % CPR;
+            const int ch = tid + u * 512, r = ch / CPR, cc = ch % CPR;        // r in 0..63
+            const int blk = 2 * it + (r >> 5);
+            const int g = h * G + blk / nblk, i = L - lq + 32 * (blk % nblk) + (r & 31);
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (i0 + r < L) v = *(const u32x4*)(q + ((size_t)(i0 + r) * Hq + g) * D + cc * 8);
+            if (blk < total && i < L) v = *(const u32x4*)(q + ((size_t)i * Hq + g) * D + cc * 8);
             st[u] = v;
         }
-        if (tid < 32) stl = (i0 + tid < L) ? lse2[(size_t)g * max_chunk + i0 + tid] : __builtin_inff();
+        if (tid < 64) {
+            const int blk = 2 * it + (tid >> 5);
+            const int g = h * G + blk / nblk, i = L - lq + 32 * (blk % nblk) + (tid & 31);
+            stl = (blk < total && i < L) ? lse2[(size_t)g * max_chunk + i] : __builtin_inff();   // +inf: weight 0
+        }
     };
-    if (total > 0) fetch(0);
-    for (int it = 0; it < total; ++it) {
-        __syncthreads();
+    auto stash = [&](int buf) {
+        char* base = smem + buf * BUF;
 #pragma unroll
         for (int u = 0; u < NLD; ++u) {
-            const int ch = tid + u * 256, r = ch / CPR, cc = ch % CPR;
-            *(u32x4*)(sQ + r * QP + cc * 16) = st[u];
+            const int ch = tid + u * 512, r = ch / CPR, cc = ch % CPR;
+            *(u32x4*)(base + r * QP + cc * 16) = st[u];
         }
-        if (tid < 32) sL[tid] = stl;
-        __syncthreads();
-        if (it + 1 < total) fetch(it + 1);
-
-        f32x16 acc[2];
+        if (tid < 64) *(float*)(base + QBYTES + tid * 4) = stl;
+    };
+    if (niter > 0) {
+        fetch(0);
+        stash(0);
+        if (niter > 1) fetch(1);
+    }
+    __syncthreads();
+    for (int it = 0; it < niter; ++it) {
+        const char* base = smem + (it & 1) * BUF;
+        const char* qp = base + (32 * rg + l32) * QP + 16 * hh;
+        const float* sl = (const float*)(base + QBYTES) + 32 * rg;
+        f32x16 acc[CB];
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
+        for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
-        const char* qp = sQ + l32 * QP + 16 * hh;
+        bf16x8 qf[D / 16];
 #pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-            const bf16x8 qf = as_bf16x8(*(const u32x4*)(qp + 32 * s));
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[0][s], acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[1][s], acc[1], 0, 0, 0);
-        }
+        for (int s = 0; s < D / 16; ++s) qf[s] = as_bf16x8(*(const u32x4*)(qp + 32 * s));
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s)
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+                acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[s], kf[cb][s], acc[cb], 0, 0, 0);
         // lane (column, half hh) holds rows 8a + 4hh + e of the block in register 4a + e
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
-            const f32x4 ls = *(const f32x4*)(sL + 8 * a + 4 * hh);
+            const f32x4 ls = *(const f32x4*)(sl + 8 * a + 4 * hh);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                part[0][4 * a + e] += fast_exp2(__builtin_fmaf(acc[0][4 * a + e], c, -ls[e]));
-                part[1][4 * a + e] += fast_exp2(__builtin_fmaf(acc[1][4 * a + e], c, -ls[e]));
-            }
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    part[cb][4 * a + e] += fast_exp2(__builtin_fmaf(acc[cb][4 * a + e], c, -ls[e]));
         }
+        // the other buffer was last read one iteration ago, before the barrier that ended it
+        if (it + 1 < niter) stash((it + 1) & 1);
+        if (it + 2 < niter) fetch(it + 2);
+        __syncthreads();
     }
-    const float norm = (lq > 0) ? 1.0f / (float)(G * lq) : 0.f;
-    const float dstep = bias / (float)cnd;                    // Alg. 1 l.2
+    // column sums: 16 registers, the two half-waves, then the two row groups (fixed order)
+    float sum[CB];
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
+    for (int cb = 0; cb < CB; ++cb) {
         float s0 = 0.f;
 #pragma unroll
         for (int a = 0; a < 4; ++a) s0 += (part[cb][4 * a] + part[cb][4 * a + 1]) + (part[cb][4 * a + 2] + part[cb][4 * a + 3]);
-        s0 += xhalf(s0);
-        const int col = col0 + 32 * cb + l32;
-        if (hh == 0 && col < cnd)
-            Wb[(size_t)h * cap + col] = s0 * norm - (float)(cnd - 1 - col) * dstep;     // Alg. 1 l.1, l.3-4
+        sum[cb] = s0 + xhalf(s0);
+        if (rg == 1 && hh == 0) s_part[(cg * CB + cb) * 32 + l32] = sum[cb];
+    }
+    __syncthreads();
+    if (rg == 0 && hh == 0) {
+        const float norm = (lq > 0) ? 1.0f / (float)(G * lq) : 0.f;
+        const float dstep = bias / (float)cnd;                // Alg. 1 l.2
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            const int col = col0 + 32 * cb + l32;
+            if (col < cnd) {
+                const float tot = sum[cb] + s_part[(cg * CB + cb) * 32 + l32];
+                Wb[(size_t)h * cap + col] = tot * norm - (float)(cnd - 1 - col) * dstep;   // Alg. 1 l.1, l.3-4
+            }
+        }
     }
 }
 
@@ -443,15 +452,17 @@ hipError_t launch_fwd_cfg(const Geometry& g, const CacheView& c, const void* q, 
 }
 
 hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const void* q, int t, int L, void* out,
-                            float* lse, hipStream_t st)
+                            float* lse, const FwdScratch& sc, hipStream_t st)
 {
     static const int variant = [] { const char* e = getenv("INFMLLM_FWD"); return e ? atoi(e) : -1; }();
+    static const int split = [] { const char* e = getenv("INFMLLM_SPLIT"); return e ? atoi(e) : 0; }();
     if (g.d == 64) return launch_fwd_cfg<64, 4, 1, 2>(g, c, q, t, L, out, lse, st);
     if (g.d != 128) return hipErrorInvalidValue;
     // 128 query rows per workgroup when that still gives every CU a workgroup, else 64 rows with
     // the key tile split four ways inside the workgroup
     const int blocks32 = g.Hq * ((L + 31) / 32);
     const int v = variant >= 0 ? variant : (blocks32 >= 4 * 200 ? 1 : 2);
+    if (v >= 10) return launch_attn_fwd64(g, c, q, t, L, out, lse, sc, v - 10, split > 0 ? split : 1, st);
     switch (v) {
         case 1: return launch_fwd_cfg<128, 4, 2, 2>(g, c, q, t, L, out, lse, st);
         case 2: return launch_fwd_cfg<128, 2, 4, 1>(g, c, q, t, L, out, lse, st);
@@ -466,13 +477,17 @@ hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const void* 
 {
     const int n = t + L, cnd = n - g.R, lq = g.R < L ? g.R : L;
     if (cnd <= 0) return hipSuccess;
-    const dim3 grid((cnd + 255) / 256, g.Hkv), block(256);
     const float cc = g.scale * LOG2E;
-#define INFMLLM_SCORE(DD)                                                                                \
-    hipLaunchKernelGGL((score_kernel<DD>), grid, block, 0, st, (const uint16_t*)q, (const uint16_t*)c.K, \
+    // 256 columns per workgroup unless that leaves CUs without one
+    const bool wide = (long)((cnd + 255) / 256) * g.Hkv >= 200;
+    const dim3 grid(wide ? (cnd + 255) / 256 : (cnd + 127) / 128, g.Hkv), block(512);
+#define INFMLLM_SCORE(DD, CB)                                                                              \
+    hipLaunchKernelGGL((score_kernel<DD, CB>), grid, block, 0, st, (const uint16_t*)q, (const uint16_t*)c.K, \
                        lse, Wb, L, lq, g.Hq, g.G, g.cap, g.max_chunk, cnd, cc, g.bias)
-    if (g.d == 128) INFMLLM_SCORE(128);
-    else if (g.d == 64) INFMLLM_SCORE(64);
+    if (g.d == 128 && wide) INFMLLM_SCORE(128, 2);
+    else if (g.d == 128) INFMLLM_SCORE(128, 1);
+    else if (g.d == 64 && wide) INFMLLM_SCORE(64, 2);
+    else if (g.d == 64) INFMLLM_SCORE(64, 1);
     else return hipErrorInvalidValue;
 #undef INFMLLM_SCORE
     return hipGetLastError();

@@ -46,9 +46,21 @@ hipError_t launch_attn_simple(const Geometry& g, const CacheView& c, const void*
 hipError_t launch_score_simple(const Geometry& g, const CacheView& c, const void* q, const float* lse,
                                int t, int L, float* Wb, hipStream_t st);
 
+// Scratch of the matrix-core attention when the key range of a row tile is split over several
+// workgroups: un-normalised fp32 partial outputs [split][row][head][d] and (max, sum) pairs.
+struct FwdScratch {
+    float* part_o;
+    float* part_ml;
+    size_t part_rows;     // split * rows the buffers can hold
+};
+
 // a2 on bf16 MFMA (bf16 streams only).
 hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const void* q, int t, int L,
-                            void* out, float* lse, hipStream_t st);
+                            void* out, float* lse, const FwdScratch& sc, hipStream_t st);
+
+// a2 on bf16 MFMA, 64 query rows per wavefront, head_dim 128; nsplit > 1 adds the combine kernel.
+hipError_t launch_attn_fwd64(const Geometry& g, const CacheView& c, const void* q, int t, int L, void* out,
+                             float* lse, const FwdScratch& sc, int variant, int nsplit, hipStream_t st);
 
 // a3+a4 on bf16 MFMA (bf16 streams only).
 hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const void* q, const float* lse,

@@ -140,14 +140,152 @@ select_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __
     if (user_count && h == 0 && threadIdx.x == 0) *user_count = B;
 }
 
+
+// Same selection with the candidates of a head held in registers (KPT keys per thread, key
+// k*1024 + tid in slot k): the scores are read from memory once, the first digit (sign and
+// exponent bits, a handful of distinct values) is counted through ballots, the later digits
+// (spread evenly) through plain LDS atomics, and the ordered write needs four barriers in all.
+template <int KPT>
+__global__ void __launch_bounds__(TPB)
+select_reg_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __restrict__ userI,
+                  int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t s_prefix, s_remaining, s_ties;
+    __shared__ uint32_t tab_eq[KPT * NW], tab_keep[KPT * NW];
+
+    const int h = blockIdx.x, tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+    const float* W = Wb + (size_t)h * cap;
+    int32_t* Ih = I + (size_t)h * B;
+    int32_t* Uh = userI ? userI + (size_t)h * B : nullptr;
+
+    if (r > 0) {
+        uint32_t key[KPT];
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) {
+            const int j = k * TPB + tid;
+            key[k] = (j < cnd) ? order_key(W[j]) : 0u;        // 0 is below every real key
+        }
+        if (tid == 0) { s_prefix = 0; s_remaining = (uint32_t)r; }
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+            const uint32_t prefix = s_prefix;
+            const uint32_t himask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+#pragma unroll
+            for (int k = 0; k < KPT; ++k) {
+                const bool on = (k * TPB + tid < cnd) && ((key[k] & himask) == prefix);
+                const uint32_t digit = (key[k] >> shift) & 0xffu;
+                if (pass == 0) wave_histogram(hist, digit, on);
+                else if (on) atomicAdd(&hist[digit], 1u);
+            }
+            __syncthreads();
+            if (tid < 64) {
+                uint32_t c0 = hist[255 - 4 * l], c1 = hist[254 - 4 * l], c2 = hist[253 - 4 * l], c3 = hist[252 - 4 * l];
+                uint32_t mine = c0 + c1 + c2 + c3, incl = mine;
+                for (int o = 1; o < 64; o <<= 1) {
+                    const uint32_t up = __shfl_up(incl, o);
+                    if (l >= o) incl += up;
+                }
+                const uint32_t before = incl - mine, need = s_remaining;
+                if (before < need && need <= incl) {
+                    uint32_t acc = before;
+                    int bin = 255 - 4 * l;
+                    uint32_t cnt = c0;
+                    if (acc + cnt < need) { acc += cnt; --bin; cnt = c1;
+                        if (acc + cnt < need) { acc += cnt; --bin; cnt = c2;
+                            if (acc + cnt < need) { acc += cnt; --bin; cnt = c3; } } }
+                    s_prefix = prefix | ((uint32_t)bin << shift);
+                    s_remaining = need - acc;
+                    s_ties = cnt;
+                }
+            }
+            __syncthreads();
+        }
+        const uint32_t T = s_prefix;
+        const uint32_t skip_eq = s_ties - s_remaining;        // oldest ties that are dropped
+        const uint64_t below = (l == 0) ? 0ull : (~0ull >> (64 - l));
+
+        // rank among the ties, in index order: slot k, wavefront w, lane
+        uint64_t beq[KPT];
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) {
+            beq[k] = __ballot((k * TPB + tid < cnd) && key[k] == T);
+            if (l == 0) tab_eq[k * NW + w] = (uint32_t)__popcll(beq[k]);
+        }
+        __syncthreads();
+        if (tid < 64) {                                       // exclusive scan of the KPT*NW counts
+            uint32_t run = 0;
+            for (int base = 0; base < KPT * NW; base += 64) {
+                const int idx = base + l;
+                const uint32_t v = idx < KPT * NW ? tab_eq[idx] : 0u;
+                uint32_t incl = v;
+                for (int o = 1; o < 64; o <<= 1) {
+                    const uint32_t up = __shfl_up(incl, o);
+                    if (l >= o) incl += up;
+                }
+                if (idx < KPT * NW) tab_eq[idx] = run + incl - v;
+                run += __shfl(incl, 63);
+            }
+        }
+        __syncthreads();
+        uint64_t bkeep[KPT];
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) {
+            const bool in = k * TPB + tid < cnd;
+            const uint32_t eq_rank = tab_eq[k * NW + w] + (uint32_t)__popcll(beq[k] & below);
+            const bool keep = in && (key[k] > T || (key[k] == T && eq_rank >= skip_eq));
+            bkeep[k] = __ballot(keep);
+            if (l == 0) tab_keep[k * NW + w] = (uint32_t)__popcll(bkeep[k]);
+        }
+        __syncthreads();
+        if (tid < 64) {
+            uint32_t run = 0;
+            for (int base = 0; base < KPT * NW; base += 64) {
+                const int idx = base + l;
+                const uint32_t v = idx < KPT * NW ? tab_keep[idx] : 0u;
+                uint32_t incl = v;
+                for (int o = 1; o < 64; o <<= 1) {
+                    const uint32_t up = __shfl_up(incl, o);
+                    if (l >= o) incl += up;
+                }
+                if (idx < KPT * NW) tab_keep[idx] = run + incl - v;
+                run += __shfl(incl, 63);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) {
+            if ((bkeep[k] >> l) & 1ull) {
+                const uint32_t dst = tab_keep[k * NW + w] + (uint32_t)__popcll(bkeep[k] & below);
+                const int j = k * TPB + tid;
+                Ih[dst] = j;
+                if (Uh) Uh[dst] = j;
+            }
+        }
+    }
+    for (int x = tid; x < R; x += TPB) {                      // recent window: [c, n)
+        Ih[r + x] = cnd + x;
+        if (Uh) Uh[r + x] = cnd + x;
+    }
+    if (user_count && h == 0 && tid == 0) *user_count = B;
+}
+
 }  // namespace
 
 hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, int32_t* user_I,
                          int32_t* user_count, hipStream_t st)
 {
     const int cnd = n - g.R, r = g.B - g.R;
-    hipLaunchKernelGGL(select_kernel, dim3(g.Hkv), dim3(TPB), 0, st, Wb, I, user_I, user_count, cnd, r, g.R,
-                       g.B, g.cap);
+#define INFMLLM_SELECT(KERNEL)                                                                           \
+    hipLaunchKernelGGL(KERNEL, dim3(g.Hkv), dim3(TPB), 0, st, Wb, I, user_I, user_count, cnd, r, g.R, g.B, g.cap)
+    if (cnd <= 2 * TPB) INFMLLM_SELECT(select_reg_kernel<2>);
+    else if (cnd <= 4 * TPB) INFMLLM_SELECT(select_reg_kernel<4>);
+    else if (cnd <= 8 * TPB) INFMLLM_SELECT(select_reg_kernel<8>);
+    else if (cnd <= 16 * TPB) INFMLLM_SELECT(select_reg_kernel<16>);
+    else INFMLLM_SELECT(select_kernel);                      // candidates stay in memory
+#undef INFMLLM_SELECT
     return hipGetLastError();
 }
 
