@@ -87,6 +87,9 @@ def main():
     ap.add_argument("--chunks", type=int, default=32, help="distinct chunks kept in HBM and cycled through")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--impl", type=int, default=None, help="debug: 1 = plain-arithmetic kernels")
+    ap.add_argument("--copy-calib", type=int, default=0, metavar="MIB",
+                    help="also run an elementwise copy of this many MiB (reads MIB, writes MIB) three times, as "
+                         "the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this path runs on one GPU (heads would shard with no communication); "
@@ -130,6 +133,14 @@ def main():
             rc = lib.infmllm_step(h, a[0], a[1], a[2], L, po, pr, pn)
             if rc != 0:
                 raise RuntimeError(binding.last_error())
+
+    if args.copy_calib:
+        src = torch.ones(args.copy_calib << 18, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     run(warmup, 0)
     torch.cuda.synchronize()

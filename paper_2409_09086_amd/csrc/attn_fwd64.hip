@@ -378,6 +378,14 @@ hipError_t launch64(const Geometry& g, const CacheView& c, const void* q, int t,
                        g.scale * LOG2E);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || nsplit == 1) return e;
+    return launch_attn_combine(g, sc, L, nsplit, out, lse, st);
+}
+
+}  // namespace
+
+hipError_t launch_attn_combine(const Geometry& g, const FwdScratch& sc, int L, int nsplit, void* out, float* lse,
+                               hipStream_t st)
+{
     const long total = (long)L * g.Hq * 16;
     int blocks = (int)((total + 255) / 256);
     if (blocks > 2048) blocks = 2048;
@@ -385,8 +393,6 @@ hipError_t launch64(const Geometry& g, const CacheView& c, const void* q, int t,
                        lse, L, g.Hq, g.max_chunk, nsplit);
     return hipGetLastError();
 }
-
-}  // namespace
 
 hipError_t launch_attn_fwd64(const Geometry& g, const CacheView& c, const void* q, int t, int L, void* out,
                              float* lse, const FwdScratch& sc, int variant, int nsplit, hipStream_t st)

@@ -61,7 +61,8 @@ template <int D, int RB, int KW, int KVB>
 __global__ void __launch_bounds__(64 * RB * KW)
 attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                 uint16_t* __restrict__ out, float* __restrict__ lse2, int t, int L, int Hq, int G, int cap,
-                int max_chunk, int hpw, int ntile, int ny, float c /* scale * log2(e) */)
+                int max_chunk, int hpw, int ntile, int ny, int nsplit, float* __restrict__ part_o,
+                float* __restrict__ part_ml, float c /* scale * log2(e) */)
 {
     using C = FwdCfg<D, RB, KW, KVB>;
     __shared__ __attribute__((aligned(16))) char smem[C::LDS];
@@ -69,17 +70,22 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
     // Workgroup -> (row tile, head group).  Consecutive workgroup ids go round-robin over the 8
     // XCDs; all row tiles of one kv-head are given ids of one residue class so that they share
     // that XCD's L2 copy of the head's K and V.
-    int bx, by;
+    // With nsplit > 1 the key range of a row tile is cut into nsplit pieces handled by different
+    // workgroups; each writes an un-normalised partial and a second kernel combines them.
+    int bx, by, sp;
     {
-        const int bid = blockIdx.x;
+        const int bid = blockIdx.x, per_y = ntile * nsplit;
+        int rem;
         if ((ny & 7) == 0) {
             const int xcd = bid & 7, li = bid >> 3;
-            by = xcd + 8 * (li / ntile);
-            bx = ntile - 1 - li % ntile;                     // longest (most keys visible) tiles first
+            by = xcd + 8 * (li / per_y);
+            rem = li % per_y;
         } else {
-            by = bid / ntile;
-            bx = ntile - 1 - bid % ntile;
+            by = bid / per_y;
+            rem = bid % per_y;
         }
+        bx = ntile - 1 - rem / nsplit;                       // longest (most keys visible) tiles first
+        sp = rem % nsplit;
     }
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
     const int rb = wave % RB, kw = wave / RB;
@@ -150,14 +156,15 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
     const int voff = C::KBYTES + (kw * C::SUB + 4 * hh + ((lane & 15) >> 2)) * C::VP +
                      (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
 
-    const int ntiles = (n_end + C::TILE - 1) / C::TILE;
-    fetch(0);
+    const int ntiles_all = (n_end + C::TILE - 1) / C::TILE;
+    const int tile_lo = (int)((long)ntiles_all * sp / nsplit), ntiles = (int)((long)ntiles_all * (sp + 1) / nsplit);
+    if (tile_lo < ntiles) fetch(tile_lo * C::TILE);
     if (C::NBUF == 2) {
-        stash(0);
-        if (ntiles > 1) fetch(C::TILE);
+        if (tile_lo < ntiles) stash(tile_lo & 1);
+        if (tile_lo + 1 < ntiles) fetch((tile_lo + 1) * C::TILE);
         __syncthreads();
     }
-    for (int tile = 0; tile < ntiles; ++tile) {
+    for (int tile = tile_lo; tile < ntiles; ++tile) {
         const int kv0 = tile * C::TILE;
         const int buf = (C::NBUF == 2) ? (tile & 1) : 0;
         if (C::NBUF == 1) {
@@ -282,6 +289,25 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
 
     // ---- normalise and store: lane (row l32, half hh) holds O[row][32b + 8(i/4) + 4hh + i%4] -----
     const float ltot = lsum + xhalf(lsum);
+    if (nsplit > 1) {
+        // un-normalised partial of this key split: [split][row][head][D] fp32, (m, l) beside it
+        const size_t rowi = ((size_t)sp * L + my_row) * Hq + g;
+        float* pp = part_o + rowi * D;
+#pragma unroll
+        for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                f32x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = o[b][4 * a + e];
+                *(f32x4*)(pp + 32 * b + 8 * a + 4 * hh) = w;
+            }
+        if (hh == 0) {
+            part_ml[rowi * 2] = m_ref;
+            part_ml[rowi * 2 + 1] = ltot;
+        }
+        return;
+    }
     const float inv = 1.0f / ltot;
     uint16_t* op = out + ((size_t)my_row * Hq + g) * D;
 #pragma unroll
@@ -440,15 +466,19 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
 
 template <int D, int RB, int KW, int KVB>
 hipError_t launch_fwd_cfg(const Geometry& g, const CacheView& c, const void* q, int t, int L, void* out, float* lse,
-                          hipStream_t st)
+                          const FwdScratch& sc, int nsplit, hipStream_t st)
 {
     const int hpw = (RB % g.G == 0) ? g.G : ((g.G % RB == 0) ? RB : 1);
     const int rbph = RB / hpw;
     const int ntile = (L + 32 * rbph - 1) / (32 * rbph), ny = g.Hkv * (g.G / hpw);
-    hipLaunchKernelGGL((attn_fwd_kernel<D, RB, KW, KVB>), dim3(ntile * ny), dim3(64 * RB * KW), 0, st,
+    if (D != 128 || (nsplit > 1 && (size_t)nsplit * L > sc.part_rows)) nsplit = 1;   // no scratch: no split
+    hipLaunchKernelGGL((attn_fwd_kernel<D, RB, KW, KVB>), dim3(ntile * ny * nsplit), dim3(64 * RB * KW), 0, st,
                        (const uint16_t*)q, (const uint16_t*)c.K, (const uint16_t*)c.V, (uint16_t*)out, lse, t, L,
-                       g.Hq, g.G, g.cap, g.max_chunk, hpw, ntile, ny, g.scale * LOG2E);
-    return hipGetLastError();
+                       g.Hq, g.G, g.cap, g.max_chunk, hpw, ntile, ny, nsplit, sc.part_o, sc.part_ml,
+                       g.scale * LOG2E);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || nsplit == 1) return e;
+    return launch_attn_combine(g, sc, L, nsplit, out, lse, st);
 }
 
 hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const void* q, int t, int L, void* out,
@@ -456,19 +486,23 @@ hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const void* q
 {
     static const int variant = [] { const char* e = getenv("INFMLLM_FWD"); return e ? atoi(e) : -1; }();
     static const int split = [] { const char* e = getenv("INFMLLM_SPLIT"); return e ? atoi(e) : 0; }();
-    if (g.d == 64) return launch_fwd_cfg<64, 4, 1, 2>(g, c, q, t, L, out, lse, st);
+    const int ns = split > 0 ? split : 1;
+    if (g.d == 64) return launch_fwd_cfg<64, 4, 1, 2>(g, c, q, t, L, out, lse, sc, 1, st);
     if (g.d != 128) return hipErrorInvalidValue;
     // 128 query rows per workgroup when that still gives every CU a workgroup, else 64 rows with
     // the key tile split four ways inside the workgroup
     const int blocks32 = g.Hq * ((L + 31) / 32);
     const int v = variant >= 0 ? variant : (blocks32 >= 4 * 200 ? 1 : 2);
-    if (v >= 10) return launch_attn_fwd64(g, c, q, t, L, out, lse, sc, v - 10, split > 0 ? split : 1, st);
+    if (v >= 20) return launch_attn_fwd_dma(g, c, q, t, L, out, lse, sc, v - 20, ns, st);
+    if (v >= 10) return launch_attn_fwd64(g, c, q, t, L, out, lse, sc, v - 10, ns, st);
     switch (v) {
-        case 1: return launch_fwd_cfg<128, 4, 2, 2>(g, c, q, t, L, out, lse, st);
-        case 2: return launch_fwd_cfg<128, 2, 4, 1>(g, c, q, t, L, out, lse, st);
-        case 3: return launch_fwd_cfg<128, 4, 2, 1>(g, c, q, t, L, out, lse, st);
-        case 4: return launch_fwd_cfg<128, 4, 1, 4>(g, c, q, t, L, out, lse, st);
-        default: return launch_fwd_cfg<128, 4, 1, 2>(g, c, q, t, L, out, lse, st);
+        case 1: return launch_fwd_cfg<128, 4, 2, 2>(g, c, q, t, L, out, lse, sc, ns, st);
+        case 2: return launch_fwd_cfg<128, 2, 4, 1>(g, c, q, t, L, out, lse, sc, ns, st);
+        case 3: return launch_fwd_cfg<128, 4, 2, 1>(g, c, q, t, L, out, lse, sc, ns, st);
+        case 4: return launch_fwd_cfg<128, 2, 2, 1>(g, c, q, t, L, out, lse, sc, ns, st);
+        case 5: return launch_fwd_cfg<128, 4, 1, 1>(g, c, q, t, L, out, lse, sc, ns, st);
+        case 6: return launch_fwd_cfg<128, 2, 2, 2>(g, c, q, t, L, out, lse, sc, ns, st);
+        default: return launch_fwd_cfg<128, 4, 1, 2>(g, c, q, t, L, out, lse, sc, ns, st);
     }
 }
 

@@ -58,6 +58,14 @@ struct FwdScratch {
 hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const void* q, int t, int L,
                             void* out, float* lse, const FwdScratch& sc, hipStream_t st);
 
+// a2 on bf16 MFMA with direct global->LDS tile loads (head_dim 128).
+hipError_t launch_attn_fwd_dma(const Geometry& g, const CacheView& c, const void* q, int t, int L, void* out,
+                               float* lse, const FwdScratch& sc, int variant, int nsplit, hipStream_t st);
+
+// Second pass of a key-split attention launch (head_dim 128): merges the partials into out and lse.
+hipError_t launch_attn_combine(const Geometry& g, const FwdScratch& sc, int L, int nsplit, void* out, float* lse,
+                               hipStream_t st);
+
 // a2 on bf16 MFMA, 64 query rows per wavefront, head_dim 128; nsplit > 1 adds the combine kernel.
 hipError_t launch_attn_fwd64(const Geometry& g, const CacheView& c, const void* q, int t, int L, void* out,
                              float* lse, const FwdScratch& sc, int variant, int nsplit, hipStream_t st);
