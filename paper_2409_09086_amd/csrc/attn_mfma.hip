@@ -333,8 +333,8 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
 template <int D, int CB>
 __global__ void __launch_bounds__(512)
 score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const float* __restrict__ lse2,
-             float* __restrict__ Wb, int L, int lq, int Hq, int G, int cap, int max_chunk, int cnd, float c,
-             float bias)
+             float* __restrict__ Wb, int L, int lq, int Hq, int Hkv, int G, int cap, int max_chunk, int cnd,
+             int nxb, float c, float bias)
 {
     constexpr int QP = D * 2 + 16;                            // pitch of a staged query row
     constexpr int CPR = D / 8;
@@ -346,8 +346,21 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
     const int cg = wave & 3, rg = wave >> 2;                  // column group, row group
-    const int h = blockIdx.y;
-    const int col0 = blockIdx.x * (128 * CB) + cg * (32 * CB);
+    // all column blocks of a kv-head get workgroup ids of one residue class mod 8, i.e. one XCD,
+    // so that the head's scored queries are fetched into one L2 only
+    int h, bx;
+    {
+        const int bid = blockIdx.x;
+        if ((Hkv & 7) == 0) {
+            const int xcd = bid & 7, li = bid >> 3;
+            h = xcd + 8 * (li / nxb);
+            bx = li % nxb;
+        } else {
+            h = bid / nxb;
+            bx = bid % nxb;
+        }
+    }
+    const int col0 = bx * (128 * CB) + cg * (32 * CB);
 
     // key fragments: B operand of S = Q.K^T, lane (column l32, half hh) holds K[col][16s + 8hh .. +8)
     bf16x8 kf[CB][D / 16];
@@ -514,10 +527,11 @@ hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const void* 
     const float cc = g.scale * LOG2E;
     // 256 columns per workgroup unless that leaves CUs without one
     const bool wide = (long)((cnd + 255) / 256) * g.Hkv >= 200;
-    const dim3 grid(wide ? (cnd + 255) / 256 : (cnd + 127) / 128, g.Hkv), block(512);
+    const int nxb = wide ? (cnd + 255) / 256 : (cnd + 127) / 128;
+    const dim3 grid(nxb * g.Hkv), block(512);
 #define INFMLLM_SCORE(DD, CB)                                                                              \
     hipLaunchKernelGGL((score_kernel<DD, CB>), grid, block, 0, st, (const uint16_t*)q, (const uint16_t*)c.K, \
-                       lse, Wb, L, lq, g.Hq, g.G, g.cap, g.max_chunk, cnd, cc, g.bias)
+                       lse, Wb, L, lq, g.Hq, g.Hkv, g.G, g.cap, g.max_chunk, cnd, nxb, cc, g.bias)
     if (g.d == 128 && wide) INFMLLM_SCORE(128, 2);
     else if (g.d == 128) INFMLLM_SCORE(128, 1);
     else if (g.d == 64 && wide) INFMLLM_SCORE(64, 2);

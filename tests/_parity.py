@@ -70,6 +70,15 @@ class LockStep:
         self.steps += 1
         return out_g, I_g
 
+    def adopt_gpu_state(self):
+        """Spot-check protocol for late steps: the oracle takes over the GPU's exported cache."""
+        K, V, pos, _ = self.gpu.export()
+        self.oracle.load(K.double().cpu().numpy(), V.double().cpu().numpy(), pos.cpu().numpy(), self.gpu.streamed)
+
+    def gpu_only(self, q, k, v):
+        dev = self.gpu.device
+        return self.gpu.step(q.to(dev), k.to(dev), v.to(dev))
+
     def check_state(self):
         K, V, pos, score = self.gpu.export()
         Ko, Vo, po = self.oracle.export()

@@ -80,7 +80,7 @@ def test_step_errors_leave_the_stream_unchanged():
     assert e.value.code == B.ECAPACITY and len(s) == 0 and s.streamed == 0
 
 
-@pytest.mark.parametrize("name,steps", [("cfg2", 10), ("cfg3", 6)])
+@pytest.mark.parametrize("name,steps", [("cfg2", 10), ("cfg3", 6), ("cfg4", 13), ("cfg5", 6)])
 def test_full_shape_streams_lockstep(name, steps):
     """The real layer shapes in the launch configuration the benchmark times: warm-up plus the
     first evicting steps, every output element and every retained set against the oracle."""
@@ -90,3 +90,26 @@ def test_full_shape_streams_lockstep(name, steps):
         print(name, "step", step, flush=True)
         ls.step(q, k, v, check_state=(step == steps - 1))
     print("%s: max err %.3g swaps %d" % (name, ls.max_err, ls.swaps), flush=True)
+
+
+@pytest.mark.parametrize("name,skip,steps", [("cfg2", 40, 3), ("cfg4", 25, 5), ("cfg5", 47, 3)])
+def test_late_steps_spot_check(name, skip, steps):
+    """Steps far into a stream, which the oracle cannot reach on its own: the GPU runs `skip`
+    steps alone, the oracle adopts the exported cache (bit-exact rows and positions), and the
+    next steps are compared in lock-step.  cfg5's window covers the chunk at 100 000 tokens in
+    which the recurring key bank returns; cfg4's covers a frame with a trailing text query."""
+    cfg = CONFIGS[name]
+    ls = pair(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, cfg.dtype, cfg.bias, max_chunk=cfg.max_chunk)
+    stream = ChunkStream(cfg)
+    for step in range(skip):
+        ls.gpu_only(*next(stream))
+    torch.cuda.synchronize()
+    assert len(ls.gpu) == cfg.budget
+    pos = ls.gpu.positions().cpu().numpy()
+    assert (np.diff(pos, axis=1) > 0).all() and pos.max() < ls.gpu.streamed
+    assert (pos[:, -cfg.recent:] == np.arange(ls.gpu.streamed - cfg.recent, ls.gpu.streamed)).all()
+    ls.adopt_gpu_state()
+    for step in range(skip, skip + steps):
+        print(name, "late step", step, flush=True)
+        ls.step(*next(stream), check_state=(step == skip + steps - 1))
+    print("%s late: max err %.3g swaps %d" % (name, ls.max_err, ls.swaps), flush=True)
