@@ -226,11 +226,17 @@ int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* 
     const bool mfma = (s->dtype == INFMLLM_BF16 && s->impl == 0);
     hipError_t e;
 
-    s->mark(INFMLLM_K_APPEND, 0);
-    if ((e = launch_append(g, cur, k, v, t, L, s->streamed, s->st)) != hipSuccess) return fail_hip(e, "step: append");
-    s->mark(INFMLLM_K_APPEND, 1);
+    // An evicting step on the matrix-core path never appends: attention, scoring and the gather
+    // read the chunk's rows in place and the gather writes the survivors into the other half.
+    const bool in_place = mfma && n > g.B;
+    const KeySource ks = in_place ? KeySource{t, k, v} : KeySource{n, nullptr, nullptr};
+    if (!in_place) {
+        s->mark(INFMLLM_K_APPEND, 0);
+        if ((e = launch_append(g, cur, k, v, t, L, s->streamed, s->st)) != hipSuccess) return fail_hip(e, "step: append");
+        s->mark(INFMLLM_K_APPEND, 1);
+    }
     s->mark(INFMLLM_K_ATTN, 0);
-    e = mfma ? launch_attn_mfma(g, cur, q, t, L, out, s->lse, s->fwd, s->st)
+    e = mfma ? launch_attn_mfma(g, cur, ks, q, t, L, out, s->lse, s->fwd, s->st)
              : launch_attn_simple(g, cur, q, t, L, out, s->lse, s->st);
     if (e != hipSuccess) return fail_hip(e, "step: attention");
     s->mark(INFMLLM_K_ATTN, 1);
@@ -242,7 +248,7 @@ int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* 
         s->last_cnd = 0;
     } else {
         s->mark(INFMLLM_K_SCORE, 0);
-        e = mfma ? launch_score_mfma(g, cur, q, s->lse, t, L, s->Wb, s->st)
+        e = mfma ? launch_score_mfma(g, cur, ks, q, s->lse, t, L, s->Wb, s->st)
                  : launch_score_simple(g, cur, q, s->lse, t, L, s->Wb, s->st);
         if (e != hipSuccess) return fail_hip(e, "step: score");
         s->mark(INFMLLM_K_SCORE, 1);
@@ -252,7 +258,7 @@ int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* 
         s->mark(INFMLLM_K_SELECT, 1);
         const CacheView& nxt = s->cache[s->cur ^ 1];
         s->mark(INFMLLM_K_COMPACT, 0);
-        if ((e = launch_compact(g, cur, nxt, s->I, s->Wb, n, s->st)) != hipSuccess) return fail_hip(e, "step: compact");
+        if ((e = launch_compact(g, cur, ks, s->streamed, nxt, s->I, s->Wb, n, s->st)) != hipSuccess) return fail_hip(e, "step: compact");
         s->mark(INFMLLM_K_COMPACT, 1);
         s->cur ^= 1;
         s->len = g.B;

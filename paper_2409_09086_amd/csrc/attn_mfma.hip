@@ -60,6 +60,7 @@ struct FwdCfg {
 template <int D, int RB, int KW, int KVB>
 __global__ void __launch_bounds__(64 * RB * KW)
 attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+                const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc, int tc,
                 uint16_t* __restrict__ out, float* __restrict__ lse2, int t, int L, int Hq, int G, int cap,
                 int max_chunk, int hpw, int ntile, int ny, int nsplit, float* __restrict__ part_o,
                 float* __restrict__ part_ml, float c /* scale * log2(e) */)
@@ -130,13 +131,30 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
     uint32_t ld_off[C::NLD];                                 // element offsets inside a tile, loop-invariant
 #pragma unroll
     for (int u = 0; u < C::NLD; ++u) ld_off[u] = (uint32_t)((tid / C::CPR + u * C::LD_RSTEP) * D + (tid % C::CPR) * 8);
+    // Rows below tc come from the cache; rows from tc on are the chunk's own keys, read in place
+    // from the token-major chunk tensors (row stride Hkv*D), so that an evicting step needs no
+    // separate append pass.
+    const int Hkv = Hq / G;
+    const int n = t + L;
     auto fetch = [&](int kv0) {
-        const uint16_t* kt = Kh + (size_t)kv0 * D;           // uniform: scalar base + per-lane 32-bit offset
-        const uint16_t* vt = Vh + (size_t)kv0 * D;
+        if (kv0 + C::TILE <= tc) {
+            const uint16_t* kt = Kh + (size_t)kv0 * D;       // uniform: scalar base + per-lane 32-bit offset
+            const uint16_t* vt = Vh + (size_t)kv0 * D;
 #pragma unroll
-        for (int u = 0; u < C::NLD; ++u) {
-            stK[u] = *(const u32x4*)(kt + ld_off[u]);
-            stV[u] = *(const u32x4*)(vt + ld_off[u]);
+            for (int u = 0; u < C::NLD; ++u) {
+                stK[u] = *(const u32x4*)(kt + ld_off[u]);
+                stV[u] = *(const u32x4*)(vt + ld_off[u]);
+            }
+        } else {
+            const int col8 = (tid % C::CPR) * 8;
+#pragma unroll
+            for (int u = 0; u < C::NLD; ++u) {
+                const int kv = min(kv0 + tid / C::CPR + u * C::LD_RSTEP, n - 1);   // rows past n are masked anyway
+                const bool cached = kv < tc;
+                const size_t off = cached ? ((size_t)h * cap + kv) * D + col8 : ((size_t)(kv - tc) * Hkv + h) * D + col8;
+                stK[u] = *(const u32x4*)((cached ? K : kc) + off);
+                stV[u] = *(const u32x4*)((cached ? V : vc) + off);
+            }
         }
     };
     const int st_k = (tid / C::CPR) * C::KP + (tid % C::CPR) * 16;
@@ -332,7 +350,8 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
 // ---------------------------------------------------------------------------------------------
 template <int D, int CB>
 __global__ void __launch_bounds__(512)
-score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const float* __restrict__ lse2,
+score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ kc, int tc,
+             const float* __restrict__ lse2,
              float* __restrict__ Wb, int L, int lq, int Hq, int Hkv, int G, int cap, int max_chunk, int cnd,
              int nxb, float c, float bias)
 {
@@ -368,7 +387,8 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
     for (int cb = 0; cb < CB; ++cb) {
         const int col = col0 + 32 * cb + l32;
         const bool ok = col < cnd;
-        const uint16_t* kp = K + ((size_t)h * cap + (ok ? col : 0)) * D + 8 * hh;
+        const int cc = ok ? col : 0;
+        const uint16_t* kp = (cc < tc ? K + ((size_t)h * cap + cc) * D : kc + ((size_t)(cc - tc) * Hkv + h) * D) + 8 * hh;
 #pragma unroll
         for (int s = 0; s < D / 16; ++s) {
             u32x4 v = *(const u32x4*)(kp + 16 * s);
@@ -475,52 +495,88 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
     }
 }
 
+// Second pass of a key-split launch (head_dim 128):
+// out[row][head][:] = sum_s w_s O_s / sum_s w_s l_s with w_s = exp2(m_s - max m); lse2 = max m + log2(sum).
+// One thread per 8 output columns.  A kernel boundary is the one ordering across XCDs that needs
+// no cache maintenance, which is why the merge is not done by the last workgroup to finish.
+__global__ void __launch_bounds__(256)
+attn_combine_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, uint16_t* __restrict__ out,
+                    float* __restrict__ lse2, int L, int Hq, int max_chunk, int nsplit)
+{
+    constexpr int D = 128;
+    const long total = (long)L * Hq * (D / 8);
+    for (long idx = (long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (long)gridDim.x * blockDim.x) {
+        const int x = (int)(idx % (D / 8));
+        const long rowi = idx / (D / 8);                      // row * Hq + head
+        float mt = -__builtin_inff();
+        for (int s = 0; s < nsplit; ++s) mt = fmaxf(mt, part_ml[((size_t)s * L * Hq + rowi) * 2]);
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, lt = 0.f;
+        for (int s = 0; s < nsplit; ++s) {
+            const size_t r = (size_t)s * L * Hq + rowi;
+            const float w = fast_exp2(part_ml[r * 2] - mt);   // an empty split has m = -inf, weight 0
+            lt += w * part_ml[r * 2 + 1];
+            const f32x4 a = *(const f32x4*)(part_o + r * D + 8 * x), b = *(const f32x4*)(part_o + r * D + 8 * x + 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { acc[e] += w * a[e]; acc[4 + e] += w * b[e]; }
+        }
+        const float inv = 1.0f / lt;
+        bf16x8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (__bf16)(acc[e] * inv);
+        *(bf16x8*)(out + rowi * D + 8 * x) = o;
+        if (x == 0) {
+            const int row = (int)(rowi / Hq), g = (int)(rowi % Hq);
+            lse2[(size_t)g * max_chunk + row] = mt + __builtin_log2f(lt);
+        }
+    }
+}
+
 }  // namespace
 
 template <int D, int RB, int KW, int KVB>
-hipError_t launch_fwd_cfg(const Geometry& g, const CacheView& c, const void* q, int t, int L, void* out, float* lse,
-                          const FwdScratch& sc, int nsplit, hipStream_t st)
+hipError_t launch_fwd_cfg(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q, int t, int L,
+                          void* out, float* lse, const FwdScratch& sc, int nsplit, hipStream_t st)
 {
     const int hpw = (RB % g.G == 0) ? g.G : ((g.G % RB == 0) ? RB : 1);
     const int rbph = RB / hpw;
     const int ntile = (L + 32 * rbph - 1) / (32 * rbph), ny = g.Hkv * (g.G / hpw);
     if (D != 128 || (nsplit > 1 && (size_t)nsplit * L > sc.part_rows)) nsplit = 1;   // no scratch: no split
     hipLaunchKernelGGL((attn_fwd_kernel<D, RB, KW, KVB>), dim3(ntile * ny * nsplit), dim3(64 * RB * KW), 0, st,
-                       (const uint16_t*)q, (const uint16_t*)c.K, (const uint16_t*)c.V, (uint16_t*)out, lse, t, L,
-                       g.Hq, g.G, g.cap, g.max_chunk, hpw, ntile, ny, nsplit, sc.part_o, sc.part_ml,
-                       g.scale * LOG2E);
+                       (const uint16_t*)q, (const uint16_t*)c.K, (const uint16_t*)c.V, (const uint16_t*)ks.k,
+                       (const uint16_t*)ks.v, ks.rows, (uint16_t*)out, lse, t, L, g.Hq, g.G, g.cap, g.max_chunk,
+                       hpw, ntile, ny, nsplit, sc.part_o, sc.part_ml, g.scale * LOG2E);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || nsplit == 1) return e;
-    return launch_attn_combine(g, sc, L, nsplit, out, lse, st);
+    const long total = (long)L * g.Hq * 16;
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(blocks), dim3(256), 0, st, sc.part_o, sc.part_ml, (uint16_t*)out,
+                       lse, L, g.Hq, g.max_chunk, nsplit);
+    return hipGetLastError();
 }
 
-hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const void* q, int t, int L, void* out,
-                            float* lse, const FwdScratch& sc, hipStream_t st)
+hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q, int t, int L,
+                            void* out, float* lse, const FwdScratch& sc, hipStream_t st)
 {
     static const int variant = [] { const char* e = getenv("INFMLLM_FWD"); return e ? atoi(e) : -1; }();
     static const int split = [] { const char* e = getenv("INFMLLM_SPLIT"); return e ? atoi(e) : 0; }();
     const int ns = split > 0 ? split : 1;
-    if (g.d == 64) return launch_fwd_cfg<64, 4, 1, 2>(g, c, q, t, L, out, lse, sc, 1, st);
+    if (g.d == 64) return launch_fwd_cfg<64, 4, 1, 2>(g, c, ks, q, t, L, out, lse, sc, 1, st);
     if (g.d != 128) return hipErrorInvalidValue;
     // 128 query rows per workgroup when that still gives every CU a workgroup, else 64 rows with
     // the key tile split four ways inside the workgroup
     const int blocks32 = g.Hq * ((L + 31) / 32);
     const int v = variant >= 0 ? variant : (blocks32 >= 4 * 200 ? 1 : 2);
-    if (v >= 20) return launch_attn_fwd_dma(g, c, q, t, L, out, lse, sc, v - 20, ns, st);
-    if (v >= 10) return launch_attn_fwd64(g, c, q, t, L, out, lse, sc, v - 10, ns, st);
     switch (v) {
-        case 1: return launch_fwd_cfg<128, 4, 2, 2>(g, c, q, t, L, out, lse, sc, ns, st);
-        case 2: return launch_fwd_cfg<128, 2, 4, 1>(g, c, q, t, L, out, lse, sc, ns, st);
-        case 3: return launch_fwd_cfg<128, 4, 2, 1>(g, c, q, t, L, out, lse, sc, ns, st);
-        case 4: return launch_fwd_cfg<128, 2, 2, 1>(g, c, q, t, L, out, lse, sc, ns, st);
-        case 5: return launch_fwd_cfg<128, 4, 1, 1>(g, c, q, t, L, out, lse, sc, ns, st);
-        case 6: return launch_fwd_cfg<128, 2, 2, 2>(g, c, q, t, L, out, lse, sc, ns, st);
-        default: return launch_fwd_cfg<128, 4, 1, 2>(g, c, q, t, L, out, lse, sc, ns, st);
+        case 1: return launch_fwd_cfg<128, 4, 2, 2>(g, c, ks, q, t, L, out, lse, sc, ns, st);
+        case 2: return launch_fwd_cfg<128, 2, 4, 1>(g, c, ks, q, t, L, out, lse, sc, ns, st);
+        case 3: return launch_fwd_cfg<128, 4, 2, 1>(g, c, ks, q, t, L, out, lse, sc, ns, st);
+        default: return launch_fwd_cfg<128, 4, 1, 2>(g, c, ks, q, t, L, out, lse, sc, ns, st);
     }
 }
 
-hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const void* q, const float* lse, int t,
-                             int L, float* Wb, hipStream_t st)
+hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q,
+                             const float* lse, int t, int L, float* Wb, hipStream_t st)
 {
     const int n = t + L, cnd = n - g.R, lq = g.R < L ? g.R : L;
     if (cnd <= 0) return hipSuccess;
@@ -531,7 +587,8 @@ hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const void* 
     const dim3 grid(nxb * g.Hkv), block(512);
 #define INFMLLM_SCORE(DD, CB)                                                                              \
     hipLaunchKernelGGL((score_kernel<DD, CB>), grid, block, 0, st, (const uint16_t*)q, (const uint16_t*)c.K, \
-                       lse, Wb, L, lq, g.Hq, g.Hkv, g.G, g.cap, g.max_chunk, cnd, nxb, cc, g.bias)
+                       (const uint16_t*)ks.k, ks.rows, lse, Wb, L, lq, g.Hq, g.Hkv, g.G, g.cap, g.max_chunk,  \
+                       cnd, nxb, cc, g.bias)
     if (g.d == 128 && wide) INFMLLM_SCORE(128, 2);
     else if (g.d == 128) INFMLLM_SCORE(128, 1);
     else if (g.d == 64 && wide) INFMLLM_SCORE(64, 2);

@@ -58,6 +58,7 @@ fill_inf_kernel(float* __restrict__ score, int len, int Hkv, int cap)
 template <int VPR>   // vectors per row
 __global__ void __launch_bounds__(256)
 compact_kernel(const u32x4* __restrict__ Ks, const u32x4* __restrict__ Vs, const int32_t* __restrict__ ps,
+               const u32x4* __restrict__ kc, const u32x4* __restrict__ vc, int tc, int pos0, int Hkv,
                u32x4* __restrict__ Kd, u32x4* __restrict__ Vd, int32_t* __restrict__ pd,
                float* __restrict__ sd, const int32_t* __restrict__ I, const float* __restrict__ Wb,
                int B, int cap, int cnd)
@@ -77,8 +78,10 @@ compact_kernel(const u32x4* __restrict__ Ks, const u32x4* __restrict__ Vs, const
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             if (src[u] >= 0) {
-                kk[u] = __builtin_nontemporal_load(&Ks[(hb + src[u]) * VPR + x]);
-                vv[u] = __builtin_nontemporal_load(&Vs[(hb + src[u]) * VPR + x]);
+                const bool cached = src[u] < tc;          // else the row is still in the chunk tensors
+                const long off = cached ? (hb + src[u]) * VPR + x : ((long)(src[u] - tc) * Hkv + h) * VPR + x;
+                kk[u] = __builtin_nontemporal_load((cached ? Ks : kc) + off);
+                vv[u] = __builtin_nontemporal_load((cached ? Vs : vc) + off);
             }
         }
 #pragma unroll
@@ -88,7 +91,7 @@ compact_kernel(const u32x4* __restrict__ Ks, const u32x4* __restrict__ Vs, const
                 __builtin_nontemporal_store(kk[u], &Kd[(hb + r) * VPR + x]);
                 __builtin_nontemporal_store(vv[u], &Vd[(hb + r) * VPR + x]);
                 if (x == 0) {
-                    pd[hb + r] = ps[hb + src[u]];
+                    pd[hb + r] = (src[u] < tc) ? ps[hb + src[u]] : pos0 + (src[u] - tc);
                     sd[hb + r] = (src[u] < cnd) ? Wb[(long)h * cap + src[u]] : __builtin_inff();
                 }
             }
@@ -128,8 +131,8 @@ hipError_t launch_fill_inf(const Geometry& g, float* score, int len, hipStream_t
     return hipGetLastError();
 }
 
-hipError_t launch_compact(const Geometry& g, const CacheView& src, const CacheView& dst, const int32_t* I,
-                          const float* Wb, int n, hipStream_t st)
+hipError_t launch_compact(const Geometry& g, const CacheView& src, const KeySource& ks, int64_t T,
+                          const CacheView& dst, const int32_t* I, const float* Wb, int n, hipStream_t st)
 {
     const int vpr = g.d * g.elt / 16;             // 8 (d=64 bf16), 16 (d=128 bf16 / d=64 fp32), 32 (d=128 fp32)
     const int rows_per_pass = (256 / vpr) * 4;
@@ -138,7 +141,8 @@ hipError_t launch_compact(const Geometry& g, const CacheView& src, const CacheVi
     const int cnd = n - g.R;
 #define INFMLLM_COMPACT(VPR)                                                                          \
     hipLaunchKernelGGL(compact_kernel<VPR>, grid, block, 0, st, (const u32x4*)src.K, (const u32x4*)src.V, \
-                       src.pos, (u32x4*)dst.K, (u32x4*)dst.V, dst.pos, dst.score, I, Wb, g.B, g.cap, cnd)
+                       src.pos, (const u32x4*)ks.k, (const u32x4*)ks.v, ks.rows, (int)T, g.Hkv, (u32x4*)dst.K,  \
+                       (u32x4*)dst.V, dst.pos, dst.score, I, Wb, g.B, g.cap, cnd)
     switch (vpr) {
         case 8: INFMLLM_COMPACT(8); break;
         case 16: INFMLLM_COMPACT(16); break;

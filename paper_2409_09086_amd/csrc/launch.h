@@ -54,25 +54,22 @@ struct FwdScratch {
     size_t part_rows;     // split * rows the buffers can hold
 };
 
+// Where the keys and values of a step live.  Rows below `rows` come from the cache; rows from
+// `rows` on are taken straight from the chunk tensors k, v ([L][Hkv][d]) as chunk row j - rows.
+// With rows = n (after an append) the chunk pointers are never used.
+struct KeySource {
+    int rows;
+    const void* k;
+    const void* v;
+};
+
 // a2 on bf16 MFMA (bf16 streams only).
-hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const void* q, int t, int L,
+hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q, int t, int L,
                             void* out, float* lse, const FwdScratch& sc, hipStream_t st);
 
-// a2 on bf16 MFMA with direct global->LDS tile loads (head_dim 128).
-hipError_t launch_attn_fwd_dma(const Geometry& g, const CacheView& c, const void* q, int t, int L, void* out,
-                               float* lse, const FwdScratch& sc, int variant, int nsplit, hipStream_t st);
-
-// Second pass of a key-split attention launch (head_dim 128): merges the partials into out and lse.
-hipError_t launch_attn_combine(const Geometry& g, const FwdScratch& sc, int L, int nsplit, void* out, float* lse,
-                               hipStream_t st);
-
-// a2 on bf16 MFMA, 64 query rows per wavefront, head_dim 128; nsplit > 1 adds the combine kernel.
-hipError_t launch_attn_fwd64(const Geometry& g, const CacheView& c, const void* q, int t, int L, void* out,
-                             float* lse, const FwdScratch& sc, int variant, int nsplit, hipStream_t st);
-
 // a3+a4 on bf16 MFMA (bf16 streams only).
-hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const void* q, const float* lse,
-                             int t, int L, float* Wb, hipStream_t st);
+hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q,
+                             const float* lse, int t, int L, float* Wb, hipStream_t st);
 
 // a5+a6: I[h] = sort_asc(top-r of W'[h][0..cnd)) ++ [cnd, n).  I has row stride B.
 // user_I (row stride B) and user_count may be null.
@@ -86,7 +83,8 @@ hipError_t launch_iota(const Geometry& g, int n, int32_t* user_I, int32_t* user_
 hipError_t launch_fill_inf(const Geometry& g, float* score, int len, hipStream_t st);
 
 // a7: dst rows x < B <- src rows I[h][x]; score <- W'[I] for relevant rows, +inf for recent ones.
-hipError_t launch_compact(const Geometry& g, const CacheView& src, const CacheView& dst,
-                          const int32_t* I, const float* Wb, int n, hipStream_t st);
+// Rows at or above ks.rows are gathered from the chunk tensors; their position is T + (row - ks.rows).
+hipError_t launch_compact(const Geometry& g, const CacheView& src, const KeySource& ks, int64_t T,
+                          const CacheView& dst, const int32_t* I, const float* Wb, int n, hipStream_t st);
 
 }  // namespace infmllm
