@@ -30,13 +30,15 @@ def algorithmic_work(cfg, L, t):
     d, Hq, Hkv = cfg.head_dim, cfg.heads, cfg.kv_heads
     elt = 2 if cfg.dtype == "bf16" else 4
     pairs = L * t + L * (L + 1) // 2                         # visible (query, key) pairs per head
-    c, lq = n - R, min(R, L)
+    c, lq, r = n - R, min(R, L), B - R
+    row = 2 * (2 * d * elt) + 16                            # K and V read + written, position and score
     return {
         "attn": {"flops": 4.0 * d * pairs * Hq, "bytes": elt * d * (2 * n * Hkv + 2 * L * Hq)},
         "score": {"flops": 2.0 * d * lq * c * Hq, "bytes": elt * d * (c * Hkv + lq * Hq) + 4 * c * Hkv},
         "append": {"bytes": 2 * (2 * L * Hkv * d * elt) + 8 * L * Hkv},
-        "select": {"bytes": 4 * c * Hkv + 4 * B * Hkv},
-        "compact": {"bytes": 2 * (2 * B * d * elt * Hkv) + 2 * 8 * B * Hkv},
+        # the select launch also moves the R recent rows (always kept) on workgroups of its own
+        "select": {"bytes": 4 * c * Hkv + 4 * B * Hkv + row * R * Hkv},
+        "compact": {"bytes": row * r * Hkv},
     }
 
 

@@ -253,10 +253,10 @@ int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* 
         if (e != hipSuccess) return fail_hip(e, "step: score");
         s->mark(INFMLLM_K_SCORE, 1);
         s->mark(INFMLLM_K_SELECT, 0);
-        if ((e = launch_select(g, s->Wb, n, s->I, retained, n_retained, s->st)) != hipSuccess)
+        const CacheView& nxt = s->cache[s->cur ^ 1];
+        if ((e = launch_select(g, s->Wb, n, s->I, retained, n_retained, cur, ks, s->streamed, nxt, s->st)) != hipSuccess)
             return fail_hip(e, "step: select");
         s->mark(INFMLLM_K_SELECT, 1);
-        const CacheView& nxt = s->cache[s->cur ^ 1];
         s->mark(INFMLLM_K_COMPACT, 0);
         if ((e = launch_compact(g, cur, ks, s->streamed, nxt, s->I, s->Wb, n, s->st)) != hipSuccess) return fail_hip(e, "step: compact");
         s->mark(INFMLLM_K_COMPACT, 1);

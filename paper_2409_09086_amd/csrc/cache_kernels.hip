@@ -54,26 +54,27 @@ fill_inf_kernel(float* __restrict__ score, int len, int Hkv, int cap)
     }
 }
 
-// dst[h][x] <- src[h][I[h][x]] for x < B.  One thread per 16-byte vector of a row of K and V.
+// dst[h][x] <- src[h][I[h][x]] for x < rows (the relevant rows; I has row stride B).  One thread per
+// 16-byte vector of a row of K and V.
 template <int VPR>   // vectors per row
 __global__ void __launch_bounds__(256)
 compact_kernel(const u32x4* __restrict__ Ks, const u32x4* __restrict__ Vs, const int32_t* __restrict__ ps,
                const u32x4* __restrict__ kc, const u32x4* __restrict__ vc, int tc, int pos0, int Hkv,
                u32x4* __restrict__ Kd, u32x4* __restrict__ Vd, int32_t* __restrict__ pd,
                float* __restrict__ sd, const int32_t* __restrict__ I, const float* __restrict__ Wb,
-               int B, int cap, int cnd)
+               int B, int rows, int cap)
 {
     constexpr int ROWS = 256 / VPR;               // rows per block pass
     const int h = blockIdx.y;
     const int lane_row = threadIdx.x / VPR, x = threadIdx.x % VPR;
     const long hb = (long)h * cap;
-    for (int row0 = blockIdx.x * ROWS * 4; row0 < B; row0 += gridDim.x * ROWS * 4) {
+    for (int row0 = blockIdx.x * ROWS * 4; row0 < rows; row0 += gridDim.x * ROWS * 4) {
         int src[4];
         u32x4 kk[4], vv[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int r = row0 + u * ROWS + lane_row;
-            src[u] = (r < B) ? I[(long)h * B + r] : -1;
+            src[u] = (r < rows) ? I[(long)h * B + r] : -1;
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -92,7 +93,7 @@ compact_kernel(const u32x4* __restrict__ Ks, const u32x4* __restrict__ Vs, const
                 __builtin_nontemporal_store(vv[u], &Vd[(hb + r) * VPR + x]);
                 if (x == 0) {
                     pd[hb + r] = (src[u] < tc) ? ps[hb + src[u]] : pos0 + (src[u] - tc);
-                    sd[hb + r] = (src[u] < cnd) ? Wb[(long)h * cap + src[u]] : __builtin_inff();
+                    sd[hb + r] = Wb[(long)h * cap + src[u]];
                 }
             }
         }
@@ -136,13 +137,15 @@ hipError_t launch_compact(const Geometry& g, const CacheView& src, const KeySour
 {
     const int vpr = g.d * g.elt / 16;             // 8 (d=64 bf16), 16 (d=128 bf16 / d=64 fp32), 32 (d=128 fp32)
     const int rows_per_pass = (256 / vpr) * 4;
-    int bx = (g.B + rows_per_pass - 1) / rows_per_pass;
+    const int rows = g.B - g.R;                   // the recent rows have been moved already
+    (void)n;
+    if (rows <= 0) return hipSuccess;
+    int bx = (rows + rows_per_pass - 1) / rows_per_pass;
     const dim3 grid(bx, g.Hkv), block(256);
-    const int cnd = n - g.R;
 #define INFMLLM_COMPACT(VPR)                                                                          \
     hipLaunchKernelGGL(compact_kernel<VPR>, grid, block, 0, st, (const u32x4*)src.K, (const u32x4*)src.V, \
                        src.pos, (const u32x4*)ks.k, (const u32x4*)ks.v, ks.rows, (int)T, g.Hkv, (u32x4*)dst.K,  \
-                       (u32x4*)dst.V, dst.pos, dst.score, I, Wb, g.B, g.cap, cnd)
+                       (u32x4*)dst.V, dst.pos, dst.score, I, Wb, g.B, rows, g.cap)
     switch (vpr) {
         case 8: INFMLLM_COMPACT(8); break;
         case 16: INFMLLM_COMPACT(16); break;

@@ -72,9 +72,11 @@ hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySou
                              const float* lse, int t, int L, float* Wb, hipStream_t st);
 
 // a5+a6: I[h] = sort_asc(top-r of W'[h][0..cnd)) ++ [cnd, n).  I has row stride B.
-// user_I (row stride B) and user_count may be null.
+// user_I (row stride B) and user_count may be null.  The same launch also moves the recent
+// window (rows cnd..n-1 of src / the chunk) to rows r..B-1 of dst, on workgroups of its own.
 hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, int32_t* user_I,
-                         int32_t* user_count, hipStream_t st);
+                         int32_t* user_count, const CacheView& src, const KeySource& ks, int64_t T,
+                         const CacheView& dst, hipStream_t st);
 
 // warm-up: I[h][j] = j for j < n.
 hipError_t launch_iota(const Geometry& g, int n, int32_t* user_I, int32_t* user_count, hipStream_t st);
@@ -82,7 +84,7 @@ hipError_t launch_iota(const Geometry& g, int n, int32_t* user_I, int32_t* user_
 // score[h][0..len) <- +inf (used when a cache is imported).
 hipError_t launch_fill_inf(const Geometry& g, float* score, int len, hipStream_t st);
 
-// a7: dst rows x < B <- src rows I[h][x]; score <- W'[I] for relevant rows, +inf for recent ones.
+// a7: dst rows x < B - R <- src rows I[h][x], score <- W'[I] (the recent rows were moved by launch_select).
 // Rows at or above ks.rows are gathered from the chunk tensors; their position is T + (row - ks.rows).
 hipError_t launch_compact(const Geometry& g, const CacheView& src, const KeySource& ks, int64_t T,
                           const CacheView& dst, const int32_t* I, const float* Wb, int n, hipStream_t st);

@@ -38,10 +38,46 @@ __device__ __forceinline__ void wave_histogram(uint32_t* hist, uint32_t digit, b
     }
 }
 
+// The recent window [c, n) is kept whatever the scores say (Alg. 1 l.6), so its rows can move to
+// their final place, rows r .. B-1 of the other cache half, while the selection is still being
+// worked out.  The selection occupies one workgroup per kv-head; the workgroups with
+// blockIdx.x >= Hkv of the same launch do this copy on the CUs the selection leaves idle.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+struct RecentCopy {
+    const u32x4* Ks; const u32x4* Vs; const int32_t* ps;      // live cache half
+    const u32x4* kc; const u32x4* vc;                         // chunk tensors (rows >= tc), may be null
+    u32x4* Kd; u32x4* Vd; int32_t* pd; float* sd;             // other half
+    int tc, pos0, vpr, ncopy;                                 // vpr = 16-byte vectors per row
+};
+
+__device__ __forceinline__ void copy_recent(const RecentCopy& rc, int Hkv, int cnd, int r, int R, int cap)
+{
+    const long total = (long)Hkv * R * rc.vpr;
+    const int wg = blockIdx.x - Hkv;
+    for (long idx = (long)wg * TPB + threadIdx.x; idx < total; idx += (long)rc.ncopy * TPB) {
+        const int x = (int)(idx % rc.vpr);
+        const long hr = idx / rc.vpr;
+        const int row = (int)(hr % R), h = (int)(hr / R);
+        const int src = cnd + row, dst = r + row;
+        const bool cached = src < rc.tc;
+        const long so = cached ? ((long)h * cap + src) * rc.vpr + x : ((long)(src - rc.tc) * Hkv + h) * rc.vpr + x;
+        const long dof = ((long)h * cap + dst) * rc.vpr + x;
+        const u32x4 kk = __builtin_nontemporal_load((cached ? rc.Ks : rc.kc) + so);
+        const u32x4 vv = __builtin_nontemporal_load((cached ? rc.Vs : rc.vc) + so);
+        __builtin_nontemporal_store(kk, rc.Kd + dof);
+        __builtin_nontemporal_store(vv, rc.Vd + dof);
+        if (x == 0) {
+            rc.pd[(long)h * cap + dst] = cached ? rc.ps[(long)h * cap + src] : rc.pos0 + (src - rc.tc);
+            rc.sd[(long)h * cap + dst] = __builtin_inff();
+        }
+    }
+}
+
 __global__ void __launch_bounds__(TPB)
 select_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __restrict__ userI,
-              int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap)
+              int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap, int Hkv, RecentCopy rc)
 {
+    if ((int)blockIdx.x >= Hkv) { copy_recent(rc, Hkv, cnd, r, R, cap); return; }
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_prefix, s_remaining, s_ties;
     __shared__ uint32_t wave_eq[NW], wave_keep[NW];
@@ -148,8 +184,9 @@ select_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __
 template <int KPT>
 __global__ void __launch_bounds__(TPB)
 select_reg_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __restrict__ userI,
-                  int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap)
+                  int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap, int Hkv, RecentCopy rc)
 {
+    if ((int)blockIdx.x >= Hkv) { copy_recent(rc, Hkv, cnd, r, R, cap); return; }
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_prefix, s_remaining, s_ties;
     __shared__ uint32_t tab_eq[KPT * NW], tab_keep[KPT * NW];
@@ -275,11 +312,22 @@ select_reg_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t
 }  // namespace
 
 hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, int32_t* user_I,
-                         int32_t* user_count, hipStream_t st)
+                         int32_t* user_count, const CacheView& src, const KeySource& ks, int64_t T,
+                         const CacheView& dst, hipStream_t st)
 {
     const int cnd = n - g.R, r = g.B - g.R;
+    RecentCopy rc;
+    rc.Ks = (const u32x4*)src.K; rc.Vs = (const u32x4*)src.V; rc.ps = src.pos;
+    rc.kc = (const u32x4*)ks.k; rc.vc = (const u32x4*)ks.v;
+    rc.Kd = (u32x4*)dst.K; rc.Vd = (u32x4*)dst.V; rc.pd = dst.pos; rc.sd = dst.score;
+    rc.tc = ks.rows; rc.pos0 = (int)T; rc.vpr = g.d * g.elt / 16;
+    // enough copy workgroups to cover the recent rows once with a few vectors per thread
+    const long vecs = (long)g.Hkv * g.R * rc.vpr;
+    long want = (vecs + 4 * TPB - 1) / (4 * TPB);
+    rc.ncopy = (int)(want > 448 ? 448 : want);
+    const dim3 grid(g.Hkv + rc.ncopy);
 #define INFMLLM_SELECT(KERNEL)                                                                           \
-    hipLaunchKernelGGL(KERNEL, dim3(g.Hkv), dim3(TPB), 0, st, Wb, I, user_I, user_count, cnd, r, g.R, g.B, g.cap)
+    hipLaunchKernelGGL(KERNEL, grid, dim3(TPB), 0, st, Wb, I, user_I, user_count, cnd, r, g.R, g.B, g.cap, g.Hkv, rc)
     if (cnd <= 2 * TPB) INFMLLM_SELECT(select_reg_kernel<2>);
     else if (cnd <= 4 * TPB) INFMLLM_SELECT(select_reg_kernel<4>);
     else if (cnd <= 8 * TPB) INFMLLM_SELECT(select_reg_kernel<8>);
