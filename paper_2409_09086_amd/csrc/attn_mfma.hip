@@ -145,7 +145,18 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
                 stK[u] = *(const u32x4*)(kt + ld_off[u]);
                 stV[u] = *(const u32x4*)(vt + ld_off[u]);
             }
+        } else if (kv0 >= tc && kv0 + C::TILE <= n) {
+            // the whole tile lies inside the chunk: same scheme with the chunk's row stride
+            const uint16_t* kt = kc + ((size_t)(kv0 - tc) * Hkv + h) * D;
+            const uint16_t* vt = vc + ((size_t)(kv0 - tc) * Hkv + h) * D;
+#pragma unroll
+            for (int u = 0; u < C::NLD; ++u) {
+                const uint32_t off = (uint32_t)((tid / C::CPR + u * C::LD_RSTEP) * Hkv * D + (tid % C::CPR) * 8);
+                stK[u] = *(const u32x4*)(kt + off);
+                stV[u] = *(const u32x4*)(vt + off);
+            }
         } else {
+            // a tile that straddles the cache/chunk boundary or runs past the last key
             const int col8 = (tid % C::CPR) * 8;
 #pragma unroll
             for (int u = 0; u < C::NLD; ++u) {
@@ -407,20 +418,29 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
     const int niter = (total + 1) / 2;
     u32x4 st[NLD];
     float stl = 0.f;
+    // (head, block-in-head) of the next pair of blocks to fetch: kept as running scalars so that
+    // the fetch needs no per-thread division
+    int fg = 0, fb = 0;
     auto fetch = [&](int it) {
+        const int gA = fg, bA = fb;
+        int gB = fg, bB = fb + 1;
+        if (bB >= nblk) { bB = 0; ++gB; }
+        fb = bB + 1; fg = gB;
+        if (fb >= nblk) { fb = 0; ++fg; }
+        const bool okB = 2 * it + 1 < total;
 #pragma unroll
         for (int u = 0; u < NLD; ++u) {
             const int ch = tid + u * 512, r = ch / CPR, cc = ch % CPR;        // r in 0..63
-            const int blk = 2 * it + (r >> 5);
-            const int g = h * G + blk / nblk, i = L - lq + 32 * (blk % nblk) + (r & 31);
+            const bool second = r >= 32;
+            const int g = h * G + (second ? gB : gA), i = L - lq + 32 * (second ? bB : bA) + (r & 31);
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (blk < total && i < L) v = *(const u32x4*)(q + ((size_t)i * Hq + g) * D + cc * 8);
+            if ((!second || okB) && i < L) v = *(const u32x4*)(q + ((size_t)i * Hq + g) * D + cc * 8);
             st[u] = v;
         }
         if (tid < 64) {
-            const int blk = 2 * it + (tid >> 5);
-            const int g = h * G + blk / nblk, i = L - lq + 32 * (blk % nblk) + (tid & 31);
-            stl = (blk < total && i < L) ? lse2[(size_t)g * max_chunk + i] : __builtin_inff();   // +inf: weight 0
+            const bool second = tid >= 32;
+            const int g = h * G + (second ? gB : gA), i = L - lq + 32 * (second ? bB : bA) + (tid & 31);
+            stl = ((!second || okB) && i < L) ? lse2[(size_t)g * max_chunk + i] : __builtin_inff();   // +inf: weight 0
         }
     };
     auto stash = [&](int buf) {
