@@ -236,7 +236,8 @@ int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* 
         s->mark(INFMLLM_K_APPEND, 1);
     }
     s->mark(INFMLLM_K_ATTN, 0);
-    e = mfma ? launch_attn_mfma(g, cur, ks, q, t, L, out, s->lse, s->fwd, s->st)
+    int nsplit = 1;     // > 1: the attention left key-split partials that the select launch merges into out
+    e = mfma ? launch_attn_mfma(g, cur, ks, q, t, L, out, s->lse, s->fwd, /*defer_combine=*/n > g.B, &nsplit, s->st)
              : launch_attn_simple(g, cur, q, t, L, out, s->lse, s->st);
     if (e != hipSuccess) return fail_hip(e, "step: attention");
     s->mark(INFMLLM_K_ATTN, 1);
@@ -248,13 +249,14 @@ int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* 
         s->last_cnd = 0;
     } else {
         s->mark(INFMLLM_K_SCORE, 0);
-        e = mfma ? launch_score_mfma(g, cur, ks, q, s->lse, t, L, s->Wb, s->st)
+        e = mfma ? launch_score_mfma(g, cur, ks, q, s->lse, s->fwd, nsplit, t, L, s->Wb, s->st)
                  : launch_score_simple(g, cur, q, s->lse, t, L, s->Wb, s->st);
         if (e != hipSuccess) return fail_hip(e, "step: score");
         s->mark(INFMLLM_K_SCORE, 1);
         s->mark(INFMLLM_K_SELECT, 0);
         const CacheView& nxt = s->cache[s->cur ^ 1];
-        if ((e = launch_select(g, s->Wb, n, s->I, retained, n_retained, cur, ks, s->streamed, nxt, s->st)) != hipSuccess)
+        const CombineJob cj{s->fwd.part_o, s->fwd.part_ml, out, L, g.Hq, nsplit};
+        if ((e = launch_select(g, s->Wb, n, s->I, retained, n_retained, cur, ks, s->streamed, nxt, cj, s->st)) != hipSuccess)
             return fail_hip(e, "step: select");
         s->mark(INFMLLM_K_SELECT, 1);
         s->mark(INFMLLM_K_COMPACT, 0);

@@ -362,7 +362,7 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
 template <int D, int CB>
 __global__ void __launch_bounds__(512)
 score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ kc, int tc,
-             const float* __restrict__ lse2,
+             const float* __restrict__ lse2, const float* __restrict__ part_ml, int nsplit,
              float* __restrict__ Wb, int L, int lq, int Hq, int Hkv, int G, int cap, int max_chunk, int cnd,
              int nxb, float c, float bias)
 {
@@ -371,8 +371,10 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
     constexpr int NLD = 64 * CPR / 512;                       // 16-byte chunks per thread per pair of blocks
     constexpr int QBYTES = 64 * QP;
     constexpr int BUF = QBYTES + 64 * 4;                      // rows + their log-sum-exp
+    constexpr int LSE_ROWS = 4096;                            // scored rows whose log-sum-exp is kept in LDS
     __shared__ __attribute__((aligned(16))) char smem[2 * BUF];
     __shared__ float s_part[4 * CB * 32];
+    __shared__ float s_lse[LSE_ROWS];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
     const int cg = wave & 3, rg = wave >> 2;                  // column group, row group
@@ -416,8 +418,26 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
     const int nblk = (lq + 31) / 32;                          // 32-row blocks per query head
     const int total = G * nblk;                               // blocks to sweep, two per iteration
     const int niter = (total + 1) / 2;
+    // Row log-sum-exp of every scored row of the group, once per workgroup: row (gg, i) -> s_lse[gg*lq + i].
+    // After a key-split attention launch it is derived from the partials: max m + log2(sum_s l_s 2^(m_s - max m)).
+    auto row_lse = [&](int g, int i) -> float {
+        if (nsplit <= 1) return lse2[(size_t)g * max_chunk + i];
+        float mt = -__builtin_inff();
+        for (int sp = 0; sp < nsplit; ++sp) mt = fmaxf(mt, part_ml[(((size_t)sp * L + i) * Hq + g) * 2]);
+        float lt = 0.f;
+        for (int sp = 0; sp < nsplit; ++sp) {
+            const size_t r = (((size_t)sp * L + i) * Hq + g) * 2;
+            lt += fast_exp2(part_ml[r] - mt) * part_ml[r + 1];
+        }
+        return mt + __builtin_log2f(lt);
+    };
+    const bool lse_in_lds = G * lq <= LSE_ROWS;
+    if (lse_in_lds)
+        for (int x = tid; x < G * lq; x += 512) s_lse[x] = row_lse(h * G + x / lq, L - lq + x % lq);
+
     u32x4 st[NLD];
-    float stl = 0.f;
+    float stl = 0.f;                                          // log-sum-exp of the staged row, or ...
+    int stl_idx = -1;                                         // ... its index in s_lse (looked up when it is staged)
     // (head, block-in-head) of the next pair of blocks to fetch: kept as running scalars so that
     // the fetch needs no per-thread division
     int fg = 0, fb = 0;
@@ -440,7 +460,13 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
         if (tid < 64) {
             const bool second = tid >= 32;
             const int g = h * G + (second ? gB : gA), i = L - lq + 32 * (second ? bB : bA) + (tid & 31);
-            stl = ((!second || okB) && i < L) ? lse2[(size_t)g * max_chunk + i] : __builtin_inff();   // +inf: weight 0
+            stl = __builtin_inff();                           // +inf: weight 0
+            stl_idx = -1;
+            if ((!second || okB) && i < L) {
+                const int gg = second ? gB : gA;
+                if (lse_in_lds) stl_idx = gg * lq + (i - (L - lq));
+                else stl = row_lse(h * G + gg, i);
+            }
         }
     };
     auto stash = [&](int buf) {
@@ -450,10 +476,11 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
             const int ch = tid + u * 512, r = ch / CPR, cc = ch % CPR;
             *(u32x4*)(base + r * QP + cc * 16) = st[u];
         }
-        if (tid < 64) *(float*)(base + QBYTES + tid * 4) = stl;
+        if (tid < 64) *(float*)(base + QBYTES + tid * 4) = (stl_idx >= 0) ? s_lse[stl_idx] : stl;
     };
+    if (niter > 0) fetch(0);                                  // in flight while s_lse is being completed
+    __syncthreads();                                          // s_lse is complete
     if (niter > 0) {
-        fetch(0);
         stash(0);
         if (niter > 1) fetch(1);
     }
@@ -555,7 +582,8 @@ attn_combine_kernel(const float* __restrict__ part_o, const float* __restrict__ 
 
 template <int D, int RB, int KW, int KVB>
 hipError_t launch_fwd_cfg(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q, int t, int L,
-                          void* out, float* lse, const FwdScratch& sc, int nsplit, hipStream_t st)
+                          void* out, float* lse, const FwdScratch& sc, int nsplit, bool defer_combine, int* nsplit_out,
+                          hipStream_t st)
 {
     const int hpw = (RB % g.G == 0) ? g.G : ((g.G % RB == 0) ? RB : 1);
     const int rbph = RB / hpw;
@@ -566,7 +594,8 @@ hipError_t launch_fwd_cfg(const Geometry& g, const CacheView& c, const KeySource
                        (const uint16_t*)ks.v, ks.rows, (uint16_t*)out, lse, t, L, g.Hq, g.G, g.cap, g.max_chunk,
                        hpw, ntile, ny, nsplit, sc.part_o, sc.part_ml, g.scale * LOG2E);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || nsplit == 1) return e;
+    *nsplit_out = (defer_combine && e == hipSuccess) ? nsplit : 1;
+    if (e != hipSuccess || nsplit == 1 || defer_combine) return e;
     const long total = (long)L * g.Hq * 16;
     int blocks = (int)((total + 255) / 256);
     if (blocks > 2048) blocks = 2048;
@@ -576,27 +605,34 @@ hipError_t launch_fwd_cfg(const Geometry& g, const CacheView& c, const KeySource
 }
 
 hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q, int t, int L,
-                            void* out, float* lse, const FwdScratch& sc, hipStream_t st)
+                            void* out, float* lse, const FwdScratch& sc, bool defer_combine, int* nsplit,
+                            hipStream_t st)
 {
     static const int variant = [] { const char* e = getenv("INFMLLM_FWD"); return e ? atoi(e) : -1; }();
     static const int split = [] { const char* e = getenv("INFMLLM_SPLIT"); return e ? atoi(e) : 0; }();
-    const int ns = split > 0 ? split : 1;
-    if (g.d == 64) return launch_fwd_cfg<64, 4, 1, 2>(g, c, ks, q, t, L, out, lse, sc, 1, st);
+    *nsplit = 1;
+    if (g.d == 64) return launch_fwd_cfg<64, 4, 1, 2>(g, c, ks, q, t, L, out, lse, sc, 1, false, nsplit, st);
     if (g.d != 128) return hipErrorInvalidValue;
-    // 128 query rows per workgroup when that still gives every CU a workgroup, else 64 rows with
-    // the key tile split four ways inside the workgroup
-    const int blocks32 = g.Hq * ((L + 31) / 32);
-    const int v = variant >= 0 ? variant : (blocks32 >= 4 * 200 ? 1 : 2);
+    // 128 query rows x 64 keys per wavefront-tile is the efficient shape (57 % MFMA utilisation on the
+    // CUs it occupies); when that grid would cover only about half of the chip (cfg2: 128 workgroups),
+    // 64-row workgroups with four key ways inside the workgroup are faster.  Splitting the key range
+    // over workgroups (INFMLLM_SPLIT, merged by the select launch or a combine kernel) was measured
+    // to gain nothing at the five workloads -- the partials cost what the extra workgroups save --
+    // and is off by default.
+    const int wgs128 = g.Hq * ((L + 31) / 32) / 4;
+    const int ns = split > 0 ? split : 1;
+    const int v = variant >= 0 ? variant : (wgs128 >= 140 ? 1 : 2);
     switch (v) {
-        case 1: return launch_fwd_cfg<128, 4, 2, 2>(g, c, ks, q, t, L, out, lse, sc, ns, st);
-        case 2: return launch_fwd_cfg<128, 2, 4, 1>(g, c, ks, q, t, L, out, lse, sc, ns, st);
-        case 3: return launch_fwd_cfg<128, 4, 2, 1>(g, c, ks, q, t, L, out, lse, sc, ns, st);
-        default: return launch_fwd_cfg<128, 4, 1, 2>(g, c, ks, q, t, L, out, lse, sc, ns, st);
+        case 1: return launch_fwd_cfg<128, 4, 2, 2>(g, c, ks, q, t, L, out, lse, sc, ns, defer_combine, nsplit, st);
+        case 2: return launch_fwd_cfg<128, 2, 4, 1>(g, c, ks, q, t, L, out, lse, sc, ns, defer_combine, nsplit, st);
+        case 3: return launch_fwd_cfg<128, 4, 2, 1>(g, c, ks, q, t, L, out, lse, sc, ns, defer_combine, nsplit, st);
+        default: return launch_fwd_cfg<128, 4, 1, 2>(g, c, ks, q, t, L, out, lse, sc, ns, defer_combine, nsplit, st);
     }
 }
 
 hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q,
-                             const float* lse, int t, int L, float* Wb, hipStream_t st)
+                             const float* lse, const FwdScratch& sc, int nsplit, int t, int L, float* Wb,
+                             hipStream_t st)
 {
     const int n = t + L, cnd = n - g.R, lq = g.R < L ? g.R : L;
     if (cnd <= 0) return hipSuccess;
@@ -607,7 +643,8 @@ hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySou
     const dim3 grid(nxb * g.Hkv), block(512);
 #define INFMLLM_SCORE(DD, CB)                                                                              \
     hipLaunchKernelGGL((score_kernel<DD, CB>), grid, block, 0, st, (const uint16_t*)q, (const uint16_t*)c.K, \
-                       (const uint16_t*)ks.k, ks.rows, lse, Wb, L, lq, g.Hq, g.Hkv, g.G, g.cap, g.max_chunk,  \
+                       (const uint16_t*)ks.k, ks.rows, lse, sc.part_ml, nsplit, Wb, L, lq, g.Hq, g.Hkv, g.G, g.cap, \
+                       g.max_chunk,                                                                          \
                        cnd, nxb, cc, g.bias)
     if (g.d == 128 && wide) INFMLLM_SCORE(128, 2);
     else if (g.d == 128) INFMLLM_SCORE(128, 1);

@@ -63,20 +63,34 @@ struct KeySource {
     const void* v;
 };
 
-// a2 on bf16 MFMA (bf16 streams only).
+// a2 on bf16 MFMA (bf16 streams only).  Short chunks are run with the key range of every row tile
+// split over several workgroups, which leaves un-normalised partials in `sc`; *nsplit receives
+// the number of splits (1 = out and lse are final).  With defer_combine the merge of the partials
+// into `out` is left to the caller (launch_select does it on otherwise idle CUs); without it a
+// combine kernel is launched here and *nsplit is 1.
 hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q, int t, int L,
-                            void* out, float* lse, const FwdScratch& sc, hipStream_t st);
+                            void* out, float* lse, const FwdScratch& sc, bool defer_combine, int* nsplit,
+                            hipStream_t st);
 
 // a3+a4 on bf16 MFMA (bf16 streams only).
+// nsplit > 1: the row log-sum-exp is derived from the partials in `sc` instead of read from lse.
 hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q,
-                             const float* lse, int t, int L, float* Wb, hipStream_t st);
+                             const float* lse, const FwdScratch& sc, int nsplit, int t, int L, float* Wb,
+                             hipStream_t st);
 
 // a5+a6: I[h] = sort_asc(top-r of W'[h][0..cnd)) ++ [cnd, n).  I has row stride B.
 // user_I (row stride B) and user_count may be null.  The same launch also moves the recent
 // window (rows cnd..n-1 of src / the chunk) to rows r..B-1 of dst, on workgroups of its own.
+// With cj.nsplit > 1 further workgroups merge the attention partials into cj.out (head_dim 128).
+struct CombineJob {
+    const float* part_o;
+    const float* part_ml;
+    void* out;            // [L][Hq][128] bf16
+    int L, Hq, nsplit;
+};
 hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, int32_t* user_I,
                          int32_t* user_count, const CacheView& src, const KeySource& ks, int64_t T,
-                         const CacheView& dst, hipStream_t st);
+                         const CacheView& dst, const CombineJob& cj, hipStream_t st);
 
 // warm-up: I[h][j] = j for j < n.
 hipError_t launch_iota(const Geometry& g, int n, int32_t* user_I, int32_t* user_count, hipStream_t st);

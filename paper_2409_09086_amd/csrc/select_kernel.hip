@@ -73,10 +73,45 @@ __device__ __forceinline__ void copy_recent(const RecentCopy& rc, int Hkv, int c
     }
 }
 
+// Workgroups beyond the copy workgroups merge the key-split partials of the attention launch
+// (head_dim 128): out[row][head][:] = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max m).
+// Nothing later in the step reads `out`, so this too runs beside the selection.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ void combine_partials(const CombineJob& cj, int first_wg, int nwg)
+{
+    constexpr int D = 128;
+    const long total = (long)cj.L * cj.Hq * (D / 8);
+    const size_t plane = (size_t)cj.L * cj.Hq;
+    uint16_t* out = (uint16_t*)cj.out;
+    for (long idx = (long)(blockIdx.x - first_wg) * TPB + threadIdx.x; idx < total; idx += (long)nwg * TPB) {
+        const int x = (int)(idx % (D / 8));
+        const long rowi = idx / (D / 8);                      // row * Hq + head
+        float mt = -__builtin_inff();
+        for (int s = 0; s < cj.nsplit; ++s) mt = fmaxf(mt, cj.part_ml[(s * plane + rowi) * 2]);
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, lt = 0.f;
+        for (int s = 0; s < cj.nsplit; ++s) {
+            const size_t rr = s * plane + rowi;
+            const float w = __builtin_amdgcn_exp2f(cj.part_ml[rr * 2] - mt);   // an empty split has m = -inf
+            lt += w * cj.part_ml[rr * 2 + 1];
+            const f32x4 a = *(const f32x4*)(cj.part_o + rr * D + 8 * x), b = *(const f32x4*)(cj.part_o + rr * D + 8 * x + 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { acc[e] += w * a[e]; acc[4 + e] += w * b[e]; }
+        }
+        const float inv = 1.0f / lt;
+        bf16x8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (__bf16)(acc[e] * inv);
+        *(bf16x8*)(out + rowi * D + 8 * x) = o;
+    }
+}
+
 __global__ void __launch_bounds__(TPB)
 select_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __restrict__ userI,
-              int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap, int Hkv, RecentCopy rc)
+              int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap, int Hkv, RecentCopy rc,
+              CombineJob cj, int ncomb)
 {
+    if ((int)blockIdx.x >= Hkv + rc.ncopy) { combine_partials(cj, Hkv + rc.ncopy, ncomb); return; }
     if ((int)blockIdx.x >= Hkv) { copy_recent(rc, Hkv, cnd, r, R, cap); return; }
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_prefix, s_remaining, s_ties;
@@ -184,8 +219,10 @@ select_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __
 template <int KPT>
 __global__ void __launch_bounds__(TPB)
 select_reg_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __restrict__ userI,
-                  int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap, int Hkv, RecentCopy rc)
+                  int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap, int Hkv, RecentCopy rc,
+                  CombineJob cj, int ncomb)
 {
+    if ((int)blockIdx.x >= Hkv + rc.ncopy) { combine_partials(cj, Hkv + rc.ncopy, ncomb); return; }
     if ((int)blockIdx.x >= Hkv) { copy_recent(rc, Hkv, cnd, r, R, cap); return; }
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_prefix, s_remaining, s_ties;
@@ -313,7 +350,7 @@ select_reg_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t
 
 hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, int32_t* user_I,
                          int32_t* user_count, const CacheView& src, const KeySource& ks, int64_t T,
-                         const CacheView& dst, hipStream_t st)
+                         const CacheView& dst, const CombineJob& cj, hipStream_t st)
 {
     const int cnd = n - g.R, r = g.B - g.R;
     RecentCopy rc;
@@ -325,9 +362,14 @@ hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, 
     const long vecs = (long)g.Hkv * g.R * rc.vpr;
     long want = (vecs + 4 * TPB - 1) / (4 * TPB);
     rc.ncopy = (int)(want > 448 ? 448 : want);
-    const dim3 grid(g.Hkv + rc.ncopy);
+    int ncomb = 0;
+    if (cj.nsplit > 1) {
+        const long cw = ((long)cj.L * cj.Hq * 16 + 2 * TPB - 1) / (2 * TPB);
+        ncomb = (int)(cw > 256 ? 256 : cw);
+    }
+    const dim3 grid(g.Hkv + rc.ncopy + ncomb);
 #define INFMLLM_SELECT(KERNEL)                                                                           \
-    hipLaunchKernelGGL(KERNEL, grid, dim3(TPB), 0, st, Wb, I, user_I, user_count, cnd, r, g.R, g.B, g.cap, g.Hkv, rc)
+    hipLaunchKernelGGL(KERNEL, grid, dim3(TPB), 0, st, Wb, I, user_I, user_count, cnd, r, g.R, g.B, g.cap, g.Hkv, rc, cj, ncomb)
     if (cnd <= 2 * TPB) INFMLLM_SELECT(select_reg_kernel<2>);
     else if (cnd <= 4 * TPB) INFMLLM_SELECT(select_reg_kernel<4>);
     else if (cnd <= 8 * TPB) INFMLLM_SELECT(select_reg_kernel<8>);
