@@ -45,6 +45,9 @@ def test_cfg1_tiny_fp32_stream(bias):
     (4, 2, 64, 96, 96, [32, 64, 50, 50]),                           # r = 0: pure window
     (2, 2, 64, 128, 0, [64, 64, 64, 64]),                           # R = 0: nothing pinned
     (4, 1, 128, 200, 150, [70, 70, 70, 70, 70]),                    # R > L
+    (6, 2, 128, 128, 40, [60, 60, 33, 60, 60]),                     # group of 3 query heads
+    (8, 1, 64, 96, 32, [48, 48, 48, 48]),                           # group of 8 query heads
+    (2, 2, 128, 300, 100, [300, 7, 300, 150]),                      # chunk as long as the budget
 ])
 def test_small_bf16_streams(impl, heads, kv, d, budget, recent, chunks):
     ls = pair(budget, recent, heads, kv, d, "bf16", 1e-3, max_chunk=max(chunks), impl=impl)
@@ -113,3 +116,50 @@ def test_late_steps_spot_check(name, skip, steps):
         print(name, "late step", step, flush=True)
         ls.step(*next(stream), check_state=(step == skip + steps - 1))
     print("%s late: max err %.3g swaps %d" % (name, ls.max_err, ls.swaps), flush=True)
+
+
+def test_more_candidates_than_fit_in_registers():
+    """c > 16384 candidates per head takes the selection kernel that keeps the scores in memory."""
+    heads, kv, d, budget, recent, L = 2, 1, 64, 17000, 200, 128
+    ls = pair(budget, recent, heads, kv, d, "bf16", 1e-3, max_chunk=budget)
+    g = torch.Generator().manual_seed(11)
+    K = torch.randn((kv, budget, d), generator=g).bfloat16()
+    V = torch.randn((kv, budget, d), generator=g).bfloat16()
+    pos = torch.arange(budget, dtype=torch.int32).repeat(kv, 1)
+    ls.gpu.load(K.cuda(), V.cuda(), pos.cuda().contiguous(), budget)
+    ls.oracle.load(K.double().numpy(), V.double().numpy(), pos.numpy(), budget)
+    for step in range(2):
+        q, k, v = random_chunk(20 + step, L, heads, kv, d, "bf16")
+        ls.step(q, k, v, check_state=True)
+    assert ls.gpu.last_scores().shape == (kv, budget + L - recent)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_fp32_streams_with_grouped_heads(d):
+    ls = pair(160, 48, 8, 2, d, "fp32", 1e-2, max_chunk=100)
+    for step, L in enumerate([100, 37, 64, 1, 77]):
+        q, k, v = random_chunk(300 + step, L, 8, 2, d, "fp32")
+        ls.step(q, k, v, check_state=True)
+
+
+def test_scores_reported_match_oracle_scores():
+    """W' itself (not only its ranking) against the fp64 scores, through infmllm_stream_last_scores."""
+    heads, kv, d, budget, recent, L = 8, 2, 128, 512, 128, 128
+    ls = pair(budget, recent, heads, kv, d, "bf16", 1e-3, max_chunk=L)
+    for step in range(6):
+        q, k, v = random_chunk(400 + step, L, heads, kv, d, "bf16")
+        dev = ls.gpu.device
+        t = len(ls.oracle)
+        ls.gpu.step(q.to(dev), k.to(dev), v.to(dev))
+        ls.oracle.attend(q.double().numpy(), k.double().numpy(), v.double().numpy())
+        sc = ls.oracle.scores()
+        w = ls.gpu.last_scores()
+        if sc is None:
+            assert w is None
+        else:
+            S, Wb = sc
+            err = np.abs(w.double().cpu().numpy() - Wb).max()
+            assert err <= 2e-6 * np.abs(S).max() + 1e-9, err
+        ls.oracle.commit(ls.oracle.select())
+    # the two sides selected independently here; they must still agree on the final cache
+    ls.check_state()
