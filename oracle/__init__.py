@@ -45,6 +45,7 @@ def _load():
             lib.oracle_streamed.argtypes = [P]
             lib.oracle_streamed.restype = ctypes.c_int64
             lib.oracle_attend.argtypes = [P, P, P, P, ctypes.c_int, P]
+            lib.oracle_decode.argtypes = [P, P, P, P, P]
             lib.oracle_candidates.argtypes = [P]
             lib.oracle_scores.argtypes = [P, P, P]
             lib.oracle_select.argtypes = [P, P]
@@ -145,6 +146,17 @@ class OracleStream:
         I = self.select() if force_retained is None else np.asarray(force_retained, dtype=np.int32)
         self.commit(I)
         return out, I
+
+    def decode(self, q, k, v):
+        """One decoding step: append the token's k, v ([1,Hkv,d]), attend with q ([1,Hq,d]); nothing
+        is evicted, the cache may exceed the budget until the next chunk arrives.  Returns out [1,Hq,d]."""
+        q, k, v = _f64(q), _f64(k), _f64(v)
+        assert q.shape == (1, self.heads, self.head_dim) and k.shape == v.shape == (1, self.kv_heads, self.head_dim)
+        out = np.empty_like(q)
+        n = _lib.oracle_decode(self._h, _ptr(q), _ptr(k), _ptr(v), _ptr(out))
+        if n < 0:
+            raise RuntimeError("oracle_decode failed: %d" % n)
+        return out
 
     # -- state ------------------------------------------------------------------------------
     def export(self):

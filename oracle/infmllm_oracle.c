@@ -244,6 +244,41 @@ int oracle_attend(oracle_stream *s, const double *q, const double *k, const doub
     return n;
 }
 
+/*
+ * One decoding step (Sec. 3.2, last paragraph: the eviction runs when a prompt arrives, not while
+ * tokens are decoded).  The new token's k, v ([1][Hkv][dh]) are appended, its query ([1][Hq][dh])
+ * attends all t + 1 keys, and nothing is evicted: the cache may grow past B until the next prompt.
+ * Returns the new cache length, or a negative value on error.
+ */
+int oracle_decode(oracle_stream *s, const double *q, const double *k, const double *v, double *out)
+{
+    if (!s || !q || !k || !v || !out || s->pending) return -1;
+    const int dh = s->dh, t = s->t, n = t + 1;
+    if (grow(s, n) != 0) return -2;
+    for (int h = 0; h < s->Hkv; ++h) {
+        memcpy(s->K + ((size_t)h * s->cap + t) * dh, k + (size_t)h * dh, dh * sizeof(double));
+        memcpy(s->V + ((size_t)h * s->cap + t) * dh, v + (size_t)h * dh, dh * sizeof(double));
+        s->pos[(size_t)h * s->cap + t] = s->T;
+    }
+    s->n = n;
+    int fail = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int g = 0; g < s->Hq; ++g) {
+        double *W = (double *)malloc((size_t)n * sizeof(double));      /* the 1 x n weight row */
+        if (!W) {
+#pragma omp atomic write
+            fail = 1;
+            continue;
+        }
+        attention_one_head(s, g, q, 1, W, out);
+        free(W);
+    }
+    if (fail) return -2;
+    s->T += 1;
+    s->t = n;
+    return n;
+}
+
 /* number of candidate columns c = n - R of the step in flight (0 if it does not evict) */
 int oracle_candidates(const oracle_stream *s)
 {

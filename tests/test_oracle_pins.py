@@ -366,3 +366,55 @@ def test_rejects_bad_arguments():
     s.attend(rand(rng, 3, 2, 4), rand(rng, 3, 2, 4), rand(rng, 3, 2, 4))
     with pytest.raises(RuntimeError):
         s.commit(np.array([[0, 0, 1], [0, 1, 2]], dtype=np.int32))   # not strictly ascending
+
+
+# ---------------------------------------------------------------------------------------
+# decoding steps (Sec. 3.2: no eviction while tokens are decoded)
+# ---------------------------------------------------------------------------------------
+def test_decode_tokens_between_chunks_equal_one_shot_causal_attention():
+    rng = np.random.default_rng(50)
+    Hq, Hkv, d = 4, 2, 16
+    plan = [("chunk", 6), ("decode", 3), ("chunk", 5), ("decode", 4)]
+    N = sum(n for _, n in plan)
+    q, k, v = rand(rng, N, Hq, d), rand(rng, N, Hkv, d), rand(rng, N, Hkv, d)
+    s = OracleStream(budget=N, recent=2, heads=Hq, kv_heads=Hkv, head_dim=d, scale=0.4)
+    outs, a = [], 0
+    for kind, cnt in plan:
+        if kind == "chunk":
+            outs.append(s.step(q[a:a + cnt], k[a:a + cnt], v[a:a + cnt])[0])
+            a += cnt
+        else:
+            for _ in range(cnt):
+                outs.append(s.decode(q[a:a + 1], k[a:a + 1], v[a:a + 1]))
+                a += 1
+        assert len(s) == a and s.streamed == a
+    np.testing.assert_allclose(np.concatenate(outs), sdpa_causal(q, k, v, 0.4), atol=1e-12)
+    assert (s.export()[2] == np.arange(N)).all()
+
+
+def test_decode_grows_past_the_budget_and_the_next_chunk_evicts_back():
+    rng = np.random.default_rng(51)
+    Hq, Hkv, d, B, R, L = 2, 2, 8, 12, 4, 5
+    s = OracleStream(B, R, Hq, Hkv, d, bias=1e-2)
+    fill(s, rng, B, Hq, Hkv, d)
+    for i in range(3):
+        out = s.decode(rand(rng, 1, Hq, d), rand(rng, 1, Hkv, d), rand(rng, 1, Hkv, d))
+        assert out.shape == (1, Hq, d) and len(s) == B + i + 1          # no eviction while decoding
+    K, V, pos = s.export()
+    assert (pos == np.arange(B + 3)).all()
+    _, I = s.step(rand(rng, L, Hq, d), rand(rng, L, Hkv, d), rand(rng, L, Hkv, d))
+    n = B + 3 + L
+    assert len(s) == B and I.shape == (Hkv, B)
+    assert (I[:, -R:] == np.arange(n - R, n)).all()                       # recent window of the new n
+    assert (np.diff(s.export()[2], axis=1) > 0).all()
+
+
+def test_decode_with_zero_query_returns_mean_of_all_values():
+    rng = np.random.default_rng(52)
+    s = OracleStream(8, 2, 2, 1, 4)
+    v0 = rand(rng, 5, 1, 4)
+    s.step(rand(rng, 5, 2, 4), rand(rng, 5, 1, 4), v0)
+    v1 = rand(rng, 1, 1, 4)
+    out = s.decode(np.zeros((1, 2, 4)), rand(rng, 1, 1, 4), v1)
+    mean = np.concatenate([v0, v1]).mean(axis=0)                          # [1, 4]
+    np.testing.assert_allclose(out[0], np.repeat(mean, 2, axis=0), atol=1e-14)
