@@ -80,6 +80,47 @@ def cpu_baseline(cfg, budget_seconds=12.0):
             "ms_per_step": 1e3 * spent / steps}
 
 
+def decode_leg(cfg, binding, chunks, dev, impl, ntok=64):
+    """Secondary figure: decoding steps (one token, no eviction) on the same layer with the cache full."""
+    import torch
+    L = cfg.chunk
+    s = binding.Stream(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, dtype=cfg.torch_dtype,
+                       bias=cfg.bias, max_chunk=cfg.max_chunk, impl=impl, max_decode=ntok, device=dev)
+    for i in range(-(-cfg.budget // L) + 1):
+        q, k, v = chunks[i % len(chunks)]
+        s.step(q, k, v, report=False)
+    toks = [(q[i:i + 1].contiguous(), k[i:i + 1].contiguous(), v[i:i + 1].contiguous())
+            for q, k, v in chunks[:2] for i in range(ntok // 2)]
+    out = torch.empty_like(toks[0][0])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for q, k, v in toks:
+        s.decode(q, k, v, out=out)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    # same tokens again on a fresh full cache, with events around the decode kernels
+    s2 = binding.Stream(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, dtype=cfg.torch_dtype,
+                        bias=cfg.bias, max_chunk=cfg.max_chunk, impl=impl, max_decode=ntok, device=dev)
+    for i in range(-(-cfg.budget // L) + 1):
+        q, k, v = chunks[i % len(chunks)]
+        s2.step(q, k, v, report=False)
+    s2.profile(ntok)
+    for q, k, v in toks:
+        s2.decode(q, k, v, out=out)
+    torch.cuda.synchronize()
+    ms, cnt = s2.profile_read()["decode"]
+    s2.profile(0)
+    us = 1e3 * ms / cnt
+    elt = 2 if cfg.dtype == "bf16" else 4
+    n_avg = cfg.budget + (ntok + 1) / 2.0
+    nbytes = 2 * n_avg * cfg.kv_heads * cfg.head_dim * elt          # every K and V row once
+    gbs = nbytes / (us * 1e-6) / 1e9
+    return {"tokens_per_s": round(ntok / elapsed, 1), "us_per_token": round(1e6 * elapsed / ntok, 3),
+            "kernels_us": round(us, 3), "launches": cnt,
+            "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": round(gbs / PEAK_HBM_GBS, 4), "algorithmic_bytes_per_token": nbytes}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -206,6 +247,7 @@ def main():
         "evict_roofline": evict,
         "kernels": kernels,
     }
+    result["decode"] = decode_leg(cfg, binding, chunks, dev, args.impl)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(result))

@@ -52,6 +52,9 @@ enum {
     INFMLLM_PARAM_SCALE = 1,     /* softmax scale on q.k; default 1/sqrt(head_dim)           */
     INFMLLM_PARAM_MAX_CHUNK = 2, /* largest chunk_len a step may carry; default = budget.
                                     Fixes the cache capacity at budget + max_chunk rows      */
+    INFMLLM_PARAM_MAX_DECODE = 4,/* tokens that may be decoded (infmllm_decode) between two chunk
+                                    steps; default 0.  The cache may then hold up to budget +
+                                    max_decode rows and its capacity grows by as much              */
     INFMLLM_PARAM_IMPL = 3       /* debug/test: 0 (default) = bf16 streams run attention and
                                     scoring on the matrix cores; 1 = every dtype runs the
                                     plain fp32-arithmetic kernels (fp32 streams always do)   */
@@ -73,9 +76,10 @@ int infmllm_stream_create(int budget, int recent, int heads, int kv_heads, int h
                           int dtype, infmllm_stream_t** out);
 
 /*
- * Sets b, the softmax scale, max_chunk or the kernel family (Alg. 1 input b; Sec. 3.3).
- * Only before infmllm_stream_attach (ESTATE afterwards).  EINVAL for an unknown parameter,
- * a non-finite value, bias < 0, scale <= 0, max_chunk < 1 or impl outside {0, 1}.
+ * Sets b, the softmax scale, max_chunk, max_decode or the kernel family (Alg. 1 input b;
+ * Sec. 3.3).  Only before infmllm_stream_attach (ESTATE afterwards).  EINVAL for an unknown
+ * parameter, a non-finite value, bias < 0, scale <= 0, max_chunk < 1, max_decode < 0 or impl
+ * outside {0, 1}.
  */
 int infmllm_stream_set_param(infmllm_stream_t* s, int which, double value);
 
@@ -118,15 +122,33 @@ int infmllm_stream_attach(infmllm_stream_t* s, void* dev_workspace, size_t bytes
 int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* v, int chunk_len,
                  void* out, int32_t* retained, int32_t* n_retained);
 
-/* Tokens now cached (host bookkeeping: min(tokens streamed, budget)); -1 if s is null. */
+/*
+ * One decoding step (Sec. 3.2, last paragraph: the eviction runs when a prompt arrives, not
+ * while tokens are decoded), enqueued on the attached HIP stream: the token's k, v become cache
+ * row t (stream position T), out = softmax_j(scale * q.K[j]) V[j] over all t + 1 keys, nothing
+ * is evicted.  The cache may so grow to budget + max_decode rows; the next infmllm_step brings
+ * it back to the budget.
+ *   q      device, [1, heads, head_dim];  k, v  device, [1, kv_heads, head_dim];  read-only
+ *   out    device, [1, heads, head_dim], written
+ * Errors: EINVAL (null pointer), ECAPACITY (the cache already holds budget + max_decode rows),
+ * ESTATE (not attached), EHIP.
+ */
+int infmllm_decode(infmllm_stream_t* s, const void* q, const void* k, const void* v, void* out);
+
+/* Tokens now cached (host bookkeeping; at most budget after a step, up to budget + max_decode
+ * after decoding steps); -1 if s is null. */
 int infmllm_stream_len(const infmllm_stream_t* s);
+
+/* Most rows the cache can hold between two steps: budget + max_decode; -1 if s is null. */
+int infmllm_stream_max_len(const infmllm_stream_t* s);
 
 /* Tokens streamed so far, i.e. the stream position the next chunk starts at; -1 if null. */
 int64_t infmllm_stream_streamed(const infmllm_stream_t* s);
 
 /*
- * Copies the stream position of every cached row to pos (device, int32 [kv_heads, budget];
- * the first infmllm_stream_len entries of each row are written).  These are Alg. 1's I
+ * Copies the stream position of every cached row to pos (device, int32 [kv_heads, max_len] with
+ * max_len = infmllm_stream_max_len(s), i.e. [kv_heads, budget] unless max_decode was set; the
+ * first infmllm_stream_len entries of each row are written).  These are Alg. 1's I
  * expressed as positions in the whole stream.  Errors: EINVAL, ESTATE, EHIP.
  */
 int infmllm_stream_positions(infmllm_stream_t* s, int32_t* pos);
@@ -142,7 +164,7 @@ int infmllm_stream_export(infmllm_stream_t* s, void* K, void* V, int32_t* pos, f
 /*
  * Debug/test: replaces the cache by len rows per kv-head (layouts as for export; pos must
  * be strictly ascending per head) and sets the number of tokens streamed so far.  Scores
- * are set to +inf.  Errors: EINVAL (len outside 0..budget, null pointers with len > 0),
+ * are set to +inf.  Errors: EINVAL (len outside 0..max_len, null pointers with len > 0),
  * ESTATE (not attached), EHIP.
  */
 int infmllm_stream_import(infmllm_stream_t* s, const void* K, const void* V, const int32_t* pos,
@@ -162,7 +184,8 @@ enum {
     INFMLLM_K_SCORE = 2,
     INFMLLM_K_SELECT = 3,
     INFMLLM_K_COMPACT = 4,
-    INFMLLM_K_COUNT = 5
+    INFMLLM_K_DECODE = 5,
+    INFMLLM_K_COUNT = 6
 };
 
 /*

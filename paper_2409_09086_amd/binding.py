@@ -14,16 +14,16 @@ LIB_PATH = os.path.join(_HERE, "libinfmllm.so")
 
 BF16, FP32 = 0, 1
 OK, EINVAL, ENOMEM, ECAPACITY, ESTATE, EHIP = 0, -1, -2, -3, -4, -5
-PARAM_BIAS, PARAM_SCALE, PARAM_MAX_CHUNK, PARAM_IMPL = 0, 1, 2, 3
+PARAM_BIAS, PARAM_SCALE, PARAM_MAX_CHUNK, PARAM_IMPL, PARAM_MAX_DECODE = 0, 1, 2, 3, 4
 
 EXPORTS = [
     "infmllm_stream_create", "infmllm_stream_set_param", "infmllm_stream_workspace_bytes",
     "infmllm_stream_attach", "infmllm_step", "infmllm_stream_len", "infmllm_stream_streamed",
     "infmllm_stream_positions", "infmllm_stream_export", "infmllm_stream_import",
     "infmllm_stream_last_scores", "infmllm_last_error", "infmllm_stream_destroy",
-    "infmllm_stream_profile", "infmllm_stream_profile_read",
+    "infmllm_stream_profile", "infmllm_stream_profile_read", "infmllm_decode", "infmllm_stream_max_len",
 ]
-KERNELS = ["append", "attn", "score", "select", "compact"]
+KERNELS = ["append", "attn", "score", "select", "compact", "decode"]
 
 _lib = None
 
@@ -48,6 +48,8 @@ def lib():
         L.infmllm_stream_workspace_bytes.restype = ctypes.c_size_t
         L.infmllm_stream_attach.argtypes = [P, P, ctypes.c_size_t, P]
         L.infmllm_step.argtypes = [P, P, P, P, I, P, P, P]
+        L.infmllm_decode.argtypes = [P, P, P, P, P]
+        L.infmllm_stream_max_len.argtypes = [P]
         L.infmllm_stream_len.argtypes = [P]
         L.infmllm_stream_streamed.argtypes = [P]
         L.infmllm_stream_streamed.restype = ctypes.c_int64
@@ -89,7 +91,7 @@ class Stream:
     """infmllm_stream_t with its workspace: one layer of one sequence on one GPU."""
 
     def __init__(self, budget, recent, heads, kv_heads, head_dim, dtype=torch.bfloat16, bias=None, scale=None,
-                 max_chunk=None, impl=None, device="cuda:0", hip_stream=None):
+                 max_chunk=None, impl=None, max_decode=None, device="cuda:0", hip_stream=None):
         L = lib()
         self.dtype = dtype
         code = {torch.bfloat16: BF16, torch.float32: FP32}.get(dtype)
@@ -99,7 +101,8 @@ class Stream:
         _check(L.infmllm_stream_create(budget, recent, heads, kv_heads, head_dim, code, ctypes.byref(h)))
         self._h = h
         self.budget, self.recent, self.heads, self.kv_heads, self.head_dim = budget, recent, heads, kv_heads, head_dim
-        for which, val in ((PARAM_BIAS, bias), (PARAM_SCALE, scale), (PARAM_MAX_CHUNK, max_chunk), (PARAM_IMPL, impl)):
+        for which, val in ((PARAM_BIAS, bias), (PARAM_SCALE, scale), (PARAM_MAX_CHUNK, max_chunk), (PARAM_IMPL, impl),
+                           (PARAM_MAX_DECODE, max_decode)):
             if val is not None:
                 _check(L.infmllm_stream_set_param(self._h, which, float(val)))
         self.device = torch.device(device)
@@ -142,8 +145,23 @@ class Stream:
                                   _dev_ptr(n_retained, torch.int32, None, "n_retained")))
         return out, retained, n_retained
 
+    def decode(self, q, k, v, out=None):
+        """infmllm_decode: q [1,heads,d], k/v [1,kv_heads,d].  Returns out [1,heads,d]."""
+        _dev_ptr(q, self.dtype, (1, self.heads, self.head_dim), "q")
+        _dev_ptr(k, self.dtype, (1, self.kv_heads, self.head_dim), "k")
+        _dev_ptr(v, self.dtype, (1, self.kv_heads, self.head_dim), "v")
+        if out is None:
+            out = torch.empty_like(q)
+        _check(lib().infmllm_decode(self._h, _dev_ptr(q), _dev_ptr(k), _dev_ptr(v),
+                                    _dev_ptr(out, self.dtype, q.shape, "out")))
+        return out
+
+    @property
+    def max_len(self):
+        return lib().infmllm_stream_max_len(self._h)
+
     def positions(self):
-        pos = torch.empty((self.kv_heads, self.budget), dtype=torch.int32, device=self.device)
+        pos = torch.empty((self.kv_heads, self.max_len), dtype=torch.int32, device=self.device)
         _check(lib().infmllm_stream_positions(self._h, _dev_ptr(pos)))
         return pos[:, : len(self)]
 

@@ -55,6 +55,7 @@ struct infmllm_stream {
     float* Wb;           // [Hkv][cap]
     int32_t* I;          // [Hkv][B]
     FwdScratch fwd;      // key-split partials of the matrix-core attention
+    float* dec_part;     // partials of the decoding step
     // optional per-kernel timing: one event pair per kernel per step, up to prof_cap steps
     std::vector<hipEvent_t> prof_ev;   // [prof_cap][INFMLLM_K_COUNT][2]
     std::vector<char> prof_used;       // [prof_cap][INFMLLM_K_COUNT]
@@ -73,7 +74,7 @@ struct infmllm_stream {
     }
 
     struct Layout {
-        size_t K[2], V[2], pos[2], score[2], lse, Wb, I, part_o, part_ml, total;
+        size_t K[2], V[2], pos[2], score[2], lse, Wb, I, part_o, part_ml, dec_part, total;
         size_t part_rows;
     };
     Layout layout() const
@@ -96,6 +97,7 @@ struct infmllm_stream {
         L.part_rows = (g.elt == 2 && g.d == 128) ? (size_t)4 * (g.max_chunk < 4096 ? g.max_chunk : 4096) : 0;
         L.part_o = off; off += up(L.part_rows * g.Hq * g.d * 4);
         L.part_ml = off; off += up(L.part_rows * g.Hq * 2 * 4);
+        L.dec_part = off; off += up(g.max_decode > 0 ? (size_t)g.Hq * DECODE_MAX_SPLIT * (g.d + 2) * 4 : 0);
         L.total = off;
         return L;
     }
@@ -124,7 +126,7 @@ int infmllm_stream_create(int budget, int recent, int heads, int kv_heads, int h
     infmllm_stream* s = new (std::nothrow) infmllm_stream();
     if (!s) return fail(INFMLLM_ENOMEM, "create: out of host memory");
     s->g.B = budget; s->g.R = recent; s->g.Hq = heads; s->g.Hkv = kv_heads; s->g.G = heads / kv_heads;
-    s->g.d = head_dim; s->g.max_chunk = budget; s->g.cap = 2 * budget;
+    s->g.d = head_dim; s->g.max_chunk = budget; s->g.max_decode = 0; s->g.cap = 2 * budget;
     s->g.elt = dtype == INFMLLM_BF16 ? 2 : 4;
     s->g.scale = (float)(1.0 / std::sqrt((double)head_dim));
     s->g.bias = 1e-4f;
@@ -159,7 +161,13 @@ int infmllm_stream_set_param(infmllm_stream_t* s, int which, double value)
             if (value < 1 || value > (double)(1 << 24) || value != std::floor(value))
                 return fail(INFMLLM_EINVAL, "set_param: max_chunk must be an integer in 1..2^24");
             s->g.max_chunk = (int)value;
-            s->g.cap = s->g.B + s->g.max_chunk;
+            s->g.cap = s->g.B + s->g.max_decode + s->g.max_chunk;
+            return INFMLLM_OK;
+        case INFMLLM_PARAM_MAX_DECODE:
+            if (value < 0 || value > (double)(1 << 24) || value != std::floor(value))
+                return fail(INFMLLM_EINVAL, "set_param: max_decode must be an integer in 0..2^24");
+            s->g.max_decode = (int)value;
+            s->g.cap = s->g.B + s->g.max_decode + s->g.max_chunk;
             return INFMLLM_OK;
         case INFMLLM_PARAM_IMPL:
             if (value != 0 && value != 1) return fail(INFMLLM_EINVAL, "set_param: impl must be 0 or 1");
@@ -202,6 +210,7 @@ int infmllm_stream_attach(infmllm_stream_t* s, void* ws, size_t bytes, void* hip
     s->fwd.part_o = (float*)(base + L.part_o);
     s->fwd.part_ml = (float*)(base + L.part_ml);
     s->fwd.part_rows = L.part_rows;
+    s->dec_part = (float*)(base + L.dec_part);
     s->st = (hipStream_t)hip_stream;
     s->cur = 0; s->len = 0; s->streamed = 0; s->last_cnd = 0;
     s->attached = true;
@@ -311,7 +320,31 @@ int infmllm_stream_profile_read(infmllm_stream_t* s, float* ms, int* launches)
     return INFMLLM_OK;
 }
 
+int infmllm_decode(infmllm_stream_t* s, const void* q, const void* k, const void* v, void* out)
+{
+    if (!s) return fail(INFMLLM_EINVAL, "decode: stream is null");
+    if (!s->attached) return fail(INFMLLM_ESTATE, "decode: stream has no workspace attached");
+    if (!q || !k || !v || !out) return fail(INFMLLM_EINVAL, "decode: q, k, v and out must not be null");
+    if (s->len >= s->g.B + s->g.max_decode)
+        return fail(INFMLLM_ECAPACITY, "decode: the cache already holds budget + max_decode = %d rows",
+                    s->g.B + s->g.max_decode);
+    if (s->streamed + 1 > (int64_t)INT32_MAX)
+        return fail(INFMLLM_ECAPACITY, "decode: stream positions would exceed 2^31-1");
+    s->mark(INFMLLM_K_DECODE, 0);
+    hipError_t e = launch_decode(s->g, s->cache[s->cur], q, k, v, s->len, s->streamed, out, s->dec_part,
+                                 DECODE_MAX_SPLIT, s->st);
+    if (e != hipSuccess) return fail_hip(e, "decode");
+    s->mark(INFMLLM_K_DECODE, 1);
+    s->len += 1;
+    s->streamed += 1;
+    s->last_cnd = 0;
+    if (s->prof_steps < s->prof_cap) ++s->prof_steps;
+    return INFMLLM_OK;
+}
+
 int infmllm_stream_len(const infmllm_stream_t* s) { return s ? s->len : -1; }
+
+int infmllm_stream_max_len(const infmllm_stream_t* s) { return s ? s->g.B + s->g.max_decode : -1; }
 
 int64_t infmllm_stream_streamed(const infmllm_stream_t* s) { return s ? s->streamed : -1; }
 
@@ -327,7 +360,7 @@ int infmllm_stream_positions(infmllm_stream_t* s, int32_t* pos)
 {
     if (!s || !pos) return fail(INFMLLM_EINVAL, "positions: null argument");
     if (!s->attached) return fail(INFMLLM_ESTATE, "positions: stream has no workspace attached");
-    return copy_rows(s, pos, (size_t)s->g.B * 4, s->cache[s->cur].pos, (size_t)s->g.cap * 4, (size_t)s->len * 4,
+    return copy_rows(s, pos, (size_t)(s->g.B + s->g.max_decode) * 4, s->cache[s->cur].pos, (size_t)s->g.cap * 4, (size_t)s->len * 4,
                      "positions: copy");
 }
 
@@ -353,7 +386,8 @@ int infmllm_stream_import(infmllm_stream_t* s, const void* K, const void* V, con
 {
     if (!s) return fail(INFMLLM_EINVAL, "import: stream is null");
     if (!s->attached) return fail(INFMLLM_ESTATE, "import: stream has no workspace attached");
-    if (len < 0 || len > s->g.B) return fail(INFMLLM_EINVAL, "import: len must lie in 0..budget (got %d)", len);
+    if (len < 0 || len > s->g.B + s->g.max_decode)
+        return fail(INFMLLM_EINVAL, "import: len must lie in 0..budget + max_decode (got %d)", len);
     if (len > 0 && (!K || !V || !pos)) return fail(INFMLLM_EINVAL, "import: K, V and pos must not be null");
     if (streamed < len || streamed > (int64_t)INT32_MAX) return fail(INFMLLM_EINVAL, "import: bad streamed count");
     const Geometry& g = s->g;

@@ -21,6 +21,7 @@ struct Geometry {
     int d;        // head_dim (64 or 128)
     int cap;      // cache rows per kv-head = B + max_chunk
     int max_chunk;
+    int max_decode;
     int elt;      // bytes per element (2 = bf16, 4 = fp32)
     float scale;  // softmax scale
     float bias;   // b of Alg. 1
@@ -94,6 +95,12 @@ hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, 
 
 // warm-up: I[h][j] = j for j < n.
 hipError_t launch_iota(const Geometry& g, int n, int32_t* user_I, int32_t* user_count, hipStream_t st);
+
+// Decoding step: appends the token's k, v as cache row t and attends all t + 1 keys with q (one
+// row per query head).  part is scratch of [Hq][max_split][d + 2] floats.
+constexpr int DECODE_MAX_SPLIT = 64;
+hipError_t launch_decode(const Geometry& g, const CacheView& c, const void* q, const void* k, const void* v, int t,
+                         int64_t T, void* out, float* part, int max_split, hipStream_t st);
 
 // score[h][0..len) <- +inf (used when a cache is imported).
 hipError_t launch_fill_inf(const Geometry& g, float* score, int len, hipStream_t st);

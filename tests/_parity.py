@@ -70,6 +70,17 @@ class LockStep:
         self.steps += 1
         return out_g, I_g
 
+    def decode(self, q, k, v):
+        """One decoding step on both sides (q [1,Hq,d], k/v [1,Hkv,d]); compares the outputs."""
+        dev = self.gpu.device
+        out_g = self.gpu.decode(q.to(dev), k.to(dev), v.to(dev))
+        out_o = self.oracle.decode(q.double().numpy(), k.double().numpy(), v.double().numpy())
+        err = float(np.abs(out_g.double().cpu().numpy() - out_o).max())
+        self.max_err = max(self.max_err, err)
+        assert np.isfinite(err) and err <= OUT_TOL[self.gpu.dtype], "decode step: attention output off by %g" % err
+        assert len(self.gpu) == len(self.oracle) and self.gpu.streamed == self.oracle.streamed
+        return out_g
+
     def adopt_gpu_state(self):
         """Spot-check protocol for late steps: the oracle takes over the GPU's exported cache."""
         K, V, pos, _ = self.gpu.export()

@@ -17,8 +17,9 @@ pytestmark = pytest.mark.gpu
 DT = {"fp32": torch.float32, "bf16": torch.bfloat16}
 
 
-def pair(budget, recent, heads, kv, d, dtype, bias, max_chunk=None, impl=None, scale=None):
-    gpu = B.Stream(budget, recent, heads, kv, d, dtype=DT[dtype], bias=bias, max_chunk=max_chunk, impl=impl, scale=scale)
+def pair(budget, recent, heads, kv, d, dtype, bias, max_chunk=None, impl=None, scale=None, max_decode=None):
+    gpu = B.Stream(budget, recent, heads, kv, d, dtype=DT[dtype], bias=bias, max_chunk=max_chunk, impl=impl, scale=scale,
+                   max_decode=max_decode)
     orc = OracleStream(budget, recent, heads, kv, d, bias=float(np.float32(bias)),
                        scale=None if scale is None else float(np.float32(scale)))
     if scale is None:
@@ -163,3 +164,54 @@ def test_scores_reported_match_oracle_scores():
         ls.oracle.commit(ls.oracle.select())
     # the two sides selected independently here; they must still agree on the final cache
     ls.check_state()
+
+
+# ---------------------------------------------------------------------------------------
+# decoding steps (Sec. 3.2: no eviction while tokens are decoded)
+# ---------------------------------------------------------------------------------------
+@pytest.mark.parametrize("heads,kv,d,dtype", [(4, 4, 128, "bf16"), (8, 2, 128, "bf16"), (8, 1, 64, "bf16"),
+                                              (4, 2, 64, "fp32"), (6, 1, 128, "fp32")])
+def test_decode_steps_between_chunks(heads, kv, d, dtype):
+    budget, recent, L, nd = 192, 48, 64, 9
+    ls = pair(budget, recent, heads, kv, d, dtype, 1e-3, max_chunk=L, max_decode=nd)
+    key = 0
+    for rnd in range(5):                                         # rounds of (prompt chunk, a few decoded tokens)
+        q, k, v = random_chunk(500 + rnd, L, heads, kv, d, dtype)
+        ls.step(q, k, v, check_state=True)
+        for i in range(nd if rnd % 2 == 0 else 3):
+            key += 1
+            q1, k1, v1 = random_chunk(600 + key, 1, heads, kv, d, dtype)
+            ls.decode(q1, k1, v1)
+        ls.check_state()                                         # the cache may exceed the budget here
+    assert len(ls.gpu) <= ls.gpu.max_len == budget + nd
+    assert len(ls.gpu) == budget + nd                            # the last round decoded max_decode tokens
+    q1, k1, v1 = [x.cuda() for x in random_chunk(1, 1, heads, kv, d, dtype)]
+    with pytest.raises(B.InfMLLMError) as e:                     # budget + max_decode rows are cached
+        ls.gpu.decode(q1, k1, v1)
+    assert e.value.code == B.ECAPACITY
+
+
+def test_decode_at_full_shape_cfg2():
+    """cfg2's layer shape with the cache full: 16 decoded tokens, then the next prompt evicts."""
+    cfg = CONFIGS["cfg2"]
+    ls = pair(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, cfg.dtype, cfg.bias,
+              max_chunk=cfg.max_chunk, max_decode=16)
+    stream = ChunkStream(cfg)
+    for step in range(5):
+        ls.step(*next(stream))
+    for i in range(16):
+        q1, k1, v1 = random_chunk(700 + i, 1, cfg.heads, cfg.kv_heads, cfg.head_dim, "bf16", sigma=0.5)
+        ls.decode(q1, k1, v1)
+    assert len(ls.gpu) == cfg.budget + 16
+    ls.step(*next(stream), check_state=True)
+    assert len(ls.gpu) == cfg.budget
+    print("decode cfg2: max err %.3g swaps %d" % (ls.max_err, ls.swaps), flush=True)
+
+
+def test_decode_without_max_decode_is_refused():
+    s = B.Stream(64, 16, 2, 2, 64, dtype=torch.bfloat16, max_chunk=64)
+    q, k, v = [x.cuda() for x in random_chunk(1, 64, 2, 2, 64, "bf16")]
+    s.step(q, k, v)
+    with pytest.raises(B.InfMLLMError) as e:
+        s.decode(q[:1].contiguous(), k[:1].contiguous(), v[:1].contiguous())
+    assert e.value.code == B.ECAPACITY and len(s) == 64
