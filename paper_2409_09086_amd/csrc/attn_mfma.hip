@@ -57,6 +57,83 @@ struct FwdCfg {
     static_assert(TILE <= FWD_MAX_TILE, "workspace padding assumes smaller tiles");
 };
 
+// Tail shared by the attention kernels: merge the key ways of a query block through LDS, then
+// normalise and store (or store the un-normalised partial of a key split).
+template <int D, int RB, int KW>
+__device__ __forceinline__ void fwd_finish(char* smem, bool sync_first, f32x16 (&o)[D / 32], float m_ref, float lsum,
+                                           int rb, int kw, int lane, int hh, int my_row, int g, int sp, int L, int Hq,
+                                           int max_chunk, int nsplit, float* __restrict__ part_o,
+                                           float* __restrict__ part_ml, uint16_t* __restrict__ out,
+                                           float* __restrict__ lse2)
+{
+    constexpr int OREG = D / 2;
+    // ---- merge the key ways of a query block ---------------------------------------------------
+    if (KW > 1) {
+        if (sync_first) __syncthreads();
+        float* mg = (float*)smem;
+        if (kw > 0) {
+            float* w = mg + (size_t)((kw - 1) * RB + rb) * 64 * (OREG + 2);
+            w[lane] = m_ref;
+            w[64 + lane] = lsum;
+#pragma unroll
+            for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) w[(2 + b * 16 + i) * 64 + lane] = o[b][i];
+        }
+        __syncthreads();
+        if (kw == 0) {
+            for (int k2 = 1; k2 < KW; ++k2) {
+                const float* w = mg + (size_t)((k2 - 1) * RB + rb) * 64 * (OREG + 2);
+                const float m2 = w[lane], l2 = w[64 + lane];
+                const float mt = fmaxf(m_ref, m2);
+                const float mu = (mt == -__builtin_inff()) ? 0.f : mt;
+                const float a1 = fast_exp2(m_ref - mu), a2 = fast_exp2(m2 - mu);
+                lsum = lsum * a1 + l2 * a2;
+#pragma unroll
+                for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o[b][i] = o[b][i] * a1 + w[(2 + b * 16 + i) * 64 + lane] * a2;
+                m_ref = mt;
+            }
+        }
+    }
+    if (kw != 0 || my_row >= L) return;
+
+    // ---- normalise and store: lane (row l32, half hh) holds O[row][32b + 8(i/4) + 4hh + i%4] -----
+    const float ltot = lsum + xhalf(lsum);
+    if (nsplit > 1) {
+        // un-normalised partial of this key split: [split][row][head][D] fp32, (m, l) beside it
+        const size_t rowi = ((size_t)sp * L + my_row) * Hq + g;
+        float* pp = part_o + rowi * D;
+#pragma unroll
+        for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                f32x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = o[b][4 * a + e];
+                *(f32x4*)(pp + 32 * b + 8 * a + 4 * hh) = w;
+            }
+        if (hh == 0) {
+            part_ml[rowi * 2] = m_ref;
+            part_ml[rowi * 2 + 1] = ltot;
+        }
+        return;
+    }
+    const float inv = 1.0f / ltot;
+    uint16_t* op = out + ((size_t)my_row * Hq + g) * D;
+#pragma unroll
+    for (int b = 0; b < D / 32; ++b)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            bf16x4 w;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[b][4 * a + e] * inv);
+            *(bf16x4*)(op + 32 * b + 8 * a + 4 * hh) = w;
+        }
+    if (hh == 0) lse2[(size_t)g * max_chunk + my_row] = m_ref + __builtin_log2f(ltot);
+}
+
 template <int D, int RB, int KW, int KVB>
 __global__ void __launch_bounds__(64 * RB * KW)
 attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
@@ -219,6 +296,9 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
 #pragma unroll
                 for (int s = 0; s < D / 16; ++s)
                     acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], acc[kb], 0, 0, 0);
+                // all K fragments of the block are requested before the first MFMA waits for one
+                __builtin_amdgcn_sched_group_barrier(0x100, D / 16, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, D / 16, 0);
             }
             // ---- causal mask on tiles that reach past the first row's limit --------------------
             if (sub0 + C::SUB - 1 > t + row0) {
@@ -284,71 +364,8 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
         }
     }
 
-    // ---- merge the key ways of a query block ---------------------------------------------------
-    if (KW > 1) {
-        if (C::NBUF == 1) __syncthreads();
-        float* mg = (float*)smem;
-        if (kw > 0) {
-            float* w = mg + (size_t)((kw - 1) * RB + rb) * 64 * (C::OREG + 2);
-            w[lane] = m_ref;
-            w[64 + lane] = lsum;
-#pragma unroll
-            for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) w[(2 + b * 16 + i) * 64 + lane] = o[b][i];
-        }
-        __syncthreads();
-        if (kw == 0) {
-            for (int k2 = 1; k2 < KW; ++k2) {
-                const float* w = mg + (size_t)((k2 - 1) * RB + rb) * 64 * (C::OREG + 2);
-                const float m2 = w[lane], l2 = w[64 + lane];
-                const float mt = fmaxf(m_ref, m2);
-                const float mu = (mt == -__builtin_inff()) ? 0.f : mt;
-                const float a1 = fast_exp2(m_ref - mu), a2 = fast_exp2(m2 - mu);
-                lsum = lsum * a1 + l2 * a2;
-#pragma unroll
-                for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) o[b][i] = o[b][i] * a1 + w[(2 + b * 16 + i) * 64 + lane] * a2;
-                m_ref = mt;
-            }
-        }
-    }
-    if (kw != 0 || my_row >= L) return;
-
-    // ---- normalise and store: lane (row l32, half hh) holds O[row][32b + 8(i/4) + 4hh + i%4] -----
-    const float ltot = lsum + xhalf(lsum);
-    if (nsplit > 1) {
-        // un-normalised partial of this key split: [split][row][head][D] fp32, (m, l) beside it
-        const size_t rowi = ((size_t)sp * L + my_row) * Hq + g;
-        float* pp = part_o + rowi * D;
-#pragma unroll
-        for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                f32x4 w;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = o[b][4 * a + e];
-                *(f32x4*)(pp + 32 * b + 8 * a + 4 * hh) = w;
-            }
-        if (hh == 0) {
-            part_ml[rowi * 2] = m_ref;
-            part_ml[rowi * 2 + 1] = ltot;
-        }
-        return;
-    }
-    const float inv = 1.0f / ltot;
-    uint16_t* op = out + ((size_t)my_row * Hq + g) * D;
-#pragma unroll
-    for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            bf16x4 w;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[b][4 * a + e] * inv);
-            *(bf16x4*)(op + 32 * b + 8 * a + 4 * hh) = w;
-        }
-    if (hh == 0) lse2[(size_t)g * max_chunk + my_row] = m_ref + __builtin_log2f(ltot);
+    fwd_finish<D, RB, KW>(smem, C::NBUF == 1, o, m_ref, lsum, rb, kw, lane, hh, my_row, g, sp, L, Hq, max_chunk, nsplit,
+                          part_o, part_ml, out, lse2);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -459,7 +476,7 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
         }
         if (tid < 64) {
             const bool second = tid >= 32;
-            const int g = h * G + (second ? gB : gA), i = L - lq + 32 * (second ? bB : bA) + (tid & 31);
+            const int i = L - lq + 32 * (second ? bB : bA) + (tid & 31);
             stl = __builtin_inff();                           // +inf: weight 0
             stl_idx = -1;
             if ((!second || okB) && i < L) {
@@ -589,10 +606,10 @@ hipError_t launch_fwd_cfg(const Geometry& g, const CacheView& c, const KeySource
     const int rbph = RB / hpw;
     const int ntile = (L + 32 * rbph - 1) / (32 * rbph), ny = g.Hkv * (g.G / hpw);
     if (D != 128 || (nsplit > 1 && (size_t)nsplit * L > sc.part_rows)) nsplit = 1;   // no scratch: no split
-    hipLaunchKernelGGL((attn_fwd_kernel<D, RB, KW, KVB>), dim3(ntile * ny * nsplit), dim3(64 * RB * KW), 0, st,
-                       (const uint16_t*)q, (const uint16_t*)c.K, (const uint16_t*)c.V, (const uint16_t*)ks.k,
-                       (const uint16_t*)ks.v, ks.rows, (uint16_t*)out, lse, t, L, g.Hq, g.G, g.cap, g.max_chunk,
-                       hpw, ntile, ny, nsplit, sc.part_o, sc.part_ml, g.scale * LOG2E);
+    const dim3 grid(ntile * ny * nsplit), block(64 * RB * KW);
+    hipLaunchKernelGGL((attn_fwd_kernel<D, RB, KW, KVB>), grid, block, 0, st, (const uint16_t*)q, (const uint16_t*)c.K, (const uint16_t*)c.V,
+                       (const uint16_t*)ks.k, (const uint16_t*)ks.v, ks.rows, (uint16_t*)out, lse, t, L, g.Hq, g.G,
+                       g.cap, g.max_chunk, hpw, ntile, ny, nsplit, sc.part_o, sc.part_ml, g.scale * LOG2E);
     hipError_t e = hipGetLastError();
     *nsplit_out = (defer_combine && e == hipSuccess) ? nsplit : 1;
     if (e != hipSuccess || nsplit == 1 || defer_combine) return e;
