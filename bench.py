@@ -122,6 +122,54 @@ def decode_leg(cfg, binding, chunks, dev, impl, ntok=64):
                          "frac": round(gbs / PEAK_HBM_GBS, 4), "algorithmic_bytes_per_token": nbytes}}
 
 
+def layer_batched_leg(cfg, binding, chunks, dev, impl, n_layers, steps):
+    """Secondary figure: n_layers streams of the workload's shape (the layers of a model) fed the same
+    chunk per step, once with infmllm_step per layer and once with infmllm_step_attend per layer plus one
+    infmllm_evict_batched per step.  Both in steady state (caches full); time per layer-step."""
+    import torch
+    L = cfg.chunk
+    lib = binding.lib()
+    P = ctypes.c_void_p
+    cargs = [(P(q.data_ptr()), P(k.data_ptr()), P(v.data_ptr())) for q, k, v in chunks]
+    outs = torch.empty((n_layers,) + tuple(chunks[0][0].shape), dtype=chunks[0][0].dtype, device=dev)
+    po = [P(outs[i].data_ptr()) for i in range(n_layers)]
+    fill = -(-cfg.budget // L) + 1
+    res = {}
+    for mode in ("per_layer", "batched"):
+        ss = [binding.Stream(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, dtype=cfg.torch_dtype,
+                             bias=cfg.bias, max_chunk=cfg.max_chunk, impl=impl, device=dev) for _ in range(n_layers)]
+        hs = [s._h for s in ss]
+        harr = (P * n_layers)(*hs)
+
+        def run(count, first):
+            for i in range(count):
+                for li in range(n_layers):
+                    a = cargs[(first + i + li) % len(cargs)]
+                    if mode == "per_layer":
+                        rc = lib.infmllm_step(hs[li], a[0], a[1], a[2], L, po[li], None, None)
+                    else:
+                        rc = lib.infmllm_step_attend(hs[li], a[0], a[1], a[2], L, po[li], None, None)
+                    if rc != 0:
+                        raise RuntimeError(binding.last_error())
+                if mode == "batched" and lib.infmllm_stream_pending(hs[0]) == 1:
+                    if lib.infmllm_evict_batched(harr, n_layers, None, None) != 0:
+                        raise RuntimeError(binding.last_error())
+
+        run(fill + 2, 0)
+        torch.cuda.synchronize()
+        assert all(len(s) == cfg.budget for s in ss)
+        t0 = time.perf_counter()
+        run(steps, fill + 2)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        res[mode] = {"us_per_layer_step": round(1e6 * el / (steps * n_layers), 3),
+                     "tokens_per_s": round(L * steps * n_layers / el, 1)}
+        del ss
+    res["layers"] = n_layers
+    res["steps"] = steps
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -131,6 +179,7 @@ def main():
     ap.add_argument("--chunks", type=int, default=32, help="distinct chunks kept in HBM and cycled through")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--impl", type=int, default=None, help="debug: 1 = plain-arithmetic kernels")
+    ap.add_argument("--layers", type=int, default=16, help="streams in the layer-batched eviction leg (0 = skip)")
     ap.add_argument("--copy-calib", type=int, default=0, metavar="MIB",
                     help="also run an elementwise copy of this many MiB (reads MIB, writes MIB) three times, as "
                          "the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -249,6 +298,10 @@ def main():
         "kernels": kernels,
     }
     result["decode"] = decode_leg(cfg, binding, chunks, dev, args.impl)
+    if args.layers > 0:
+        del s
+        result["layer_batched"] = layer_batched_leg(cfg, binding, chunks, dev, args.impl, args.layers,
+                                                    max(4, min(args.steps, 2000 // args.layers)))
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(result))

@@ -135,6 +135,42 @@ int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* 
  */
 int infmllm_decode(infmllm_stream_t* s, const void* q, const void* k, const void* v, void* out);
 
+/*
+ * Layer-batched eviction (Alg. 1, note under "Input": the method treats the caches of all
+ * layers at once).  A model's layers attend one after the other, but their evictions do not
+ * depend on each other, so they can share launches:
+ *
+ * infmllm_step_attend does what infmllm_step does up to and including the scores (append or
+ * in-place read of the chunk, chunk attention, S and the attention bias).  If the chunk fits
+ * into the budget the step is complete, exactly as with infmllm_step (retained / n_retained are
+ * written).  Otherwise the eviction is left pending: retained / n_retained are not touched, the
+ * stream accepts no call other than infmllm_evict_batched, infmllm_stream_pending,
+ * infmllm_stream_len / _streamed / _max_len and infmllm_stream_destroy (ESTATE), and q, k, v must
+ * stay valid and unchanged until the kernels of that infmllm_evict_batched have run (the chunk's
+ * rows are gathered from k and v in place).  Arguments and errors as for infmllm_step.
+ */
+int infmllm_step_attend(infmllm_stream_t* s, const void* q, const void* k, const void* v, int chunk_len,
+                        void* out, int32_t* retained, int32_t* n_retained);
+
+/* 1 if an eviction is pending on s, 0 if not, -1 if s is null. */
+int infmllm_stream_pending(const infmllm_stream_t* s);
+
+/*
+ * Selection, recent-window move and gather (Alg. 1 l.5-8) of `count` streams with a pending
+ * eviction, as one selection launch and one gather launch per 16 streams, enqueued on their
+ * common HIP stream.  The result for every stream is the one infmllm_step would have produced.
+ *   streams     host array of `count` distinct streams that have the same budget, recent, heads,
+ *               kv_heads, head_dim, dtype, max_chunk and max_decode and are attached to the same
+ *               HIP stream (their chunk lengths and cached lengths may differ)
+ *   retained    host array of `count` device pointers, each int32 [kv_heads, budget] as in
+ *               infmllm_step, or null; the array itself may be null
+ *   n_retained  host array of `count` device pointers to an int32, or null entries / null array
+ * Errors: EINVAL (null or repeated stream, differing geometry or HIP stream), ESTATE (a stream
+ * with no eviction pending; nothing is launched then), EHIP.
+ */
+int infmllm_evict_batched(infmllm_stream_t* const* streams, int count, int32_t* const* retained,
+                          int32_t* const* n_retained);
+
 /* Tokens now cached (host bookkeeping; at most budget after a step, up to budget + max_decode
  * after decoding steps); -1 if s is null. */
 int infmllm_stream_len(const infmllm_stream_t* s);

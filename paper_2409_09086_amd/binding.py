@@ -22,6 +22,7 @@ EXPORTS = [
     "infmllm_stream_positions", "infmllm_stream_export", "infmllm_stream_import",
     "infmllm_stream_last_scores", "infmllm_last_error", "infmllm_stream_destroy",
     "infmllm_stream_profile", "infmllm_stream_profile_read", "infmllm_decode", "infmllm_stream_max_len",
+    "infmllm_step_attend", "infmllm_stream_pending", "infmllm_evict_batched",
 ]
 KERNELS = ["append", "attn", "score", "select", "compact", "decode"]
 
@@ -49,6 +50,9 @@ def lib():
         L.infmllm_stream_attach.argtypes = [P, P, ctypes.c_size_t, P]
         L.infmllm_step.argtypes = [P, P, P, P, I, P, P, P]
         L.infmllm_decode.argtypes = [P, P, P, P, P]
+        L.infmllm_step_attend.argtypes = [P, P, P, P, I, P, P, P]
+        L.infmllm_stream_pending.argtypes = [P]
+        L.infmllm_evict_batched.argtypes = [ctypes.POINTER(P), I, ctypes.POINTER(P), ctypes.POINTER(P)]
         L.infmllm_stream_max_len.argtypes = [P]
         L.infmllm_stream_len.argtypes = [P]
         L.infmllm_stream_streamed.argtypes = [P]
@@ -145,6 +149,32 @@ class Stream:
                                   _dev_ptr(n_retained, torch.int32, None, "n_retained")))
         return out, retained, n_retained
 
+    def step_attend(self, q, k, v, out=None, retained=None, n_retained=None, report=True):
+        """infmllm_step_attend: the step up to the scores.  If the chunk fits into the budget the step
+        is complete and (out, retained, n_retained) are as from step(); otherwise the eviction is
+        left pending (self.pending) for evict_batched(), retained / n_retained are returned unwritten,
+        and q, k, v are kept alive here until that call."""
+        Lc = q.shape[0]
+        _dev_ptr(q, self.dtype, (Lc, self.heads, self.head_dim), "q")
+        _dev_ptr(k, self.dtype, (Lc, self.kv_heads, self.head_dim), "k")
+        _dev_ptr(v, self.dtype, (Lc, self.kv_heads, self.head_dim), "v")
+        if out is None:
+            out = torch.empty_like(q)
+        if report and retained is None:
+            retained = torch.empty((self.kv_heads, self.budget), dtype=torch.int32, device=q.device)
+        if report and n_retained is None:
+            n_retained = torch.empty((1,), dtype=torch.int32, device=q.device)
+        _check(lib().infmllm_step_attend(self._h, _dev_ptr(q), _dev_ptr(k), _dev_ptr(v), Lc,
+                                         _dev_ptr(out, self.dtype, q.shape, "out"),
+                                         _dev_ptr(retained, torch.int32, (self.kv_heads, self.budget), "retained"),
+                                         _dev_ptr(n_retained, torch.int32, None, "n_retained")))
+        self._held = (q, k, v, retained, n_retained) if self.pending else None
+        return out, retained, n_retained
+
+    @property
+    def pending(self):
+        return lib().infmllm_stream_pending(self._h) == 1
+
     def decode(self, q, k, v, out=None):
         """infmllm_decode: q [1,heads,d], k/v [1,kv_heads,d].  Returns out [1,heads,d]."""
         _dev_ptr(q, self.dtype, (1, self.heads, self.head_dim), "q")
@@ -205,3 +235,19 @@ class Stream:
         w = torch.empty((self.kv_heads, c.value), dtype=torch.float32, device=self.device)
         _check(lib().infmllm_stream_last_scores(self._h, _dev_ptr(w), ctypes.byref(c)))
         return w
+
+
+def evict_batched(streams):
+    """infmllm_evict_batched over Stream objects that all have an eviction pending (the layers of a
+    model after step_attend).  The retained / n_retained tensors handed to (or made by) each
+    stream's step_attend receive the result.  Nothing is synchronised."""
+    n = len(streams)
+    P = ctypes.c_void_p
+    hs = (P * n)(*[s._h for s in streams])
+    held = [getattr(s, "_held", None) for s in streams]
+    ret = (P * n)(*[(h[3].data_ptr() if h is not None and h[3] is not None else None) for h in held])
+    cnt = (P * n)(*[(h[4].data_ptr() if h is not None and h[4] is not None else None) for h in held])
+    _check(lib().infmllm_evict_batched(hs, n, ret, cnt))
+    # the gather is enqueued: torch's stream-ordered allocator may now recycle the chunk tensors
+    for s in streams:
+        s._held = None

@@ -51,6 +51,10 @@ struct infmllm_stream {
     int len;             // rows cached
     int64_t streamed;    // tokens streamed so far
     int last_cnd;        // candidates of the most recent evicting step (0 = none)
+    // eviction left pending by infmllm_step_attend: scores are in Wb, the chunk is still read in place
+    bool pending = false;
+    KeySource pend_ks{0, nullptr, nullptr};
+    int pend_n = 0, pend_L = 0;
     float* lse;          // [Hq][max_chunk]
     float* Wb;           // [Hkv][cap]
     int32_t* I;          // [Hkv][B]
@@ -217,17 +221,26 @@ int infmllm_stream_attach(infmllm_stream_t* s, void* ws, size_t bytes, void* hip
     return INFMLLM_OK;
 }
 
-int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* v, int L, void* out,
-                 int32_t* retained, int32_t* n_retained)
+}  // extern "C"
+
+namespace {
+
+// a1-a4 of a step: append (unless the chunk is read in place), attention, and either the warm-up
+// index list or the scores.  On return *evict says whether a5-a7 are still to run; the stream's
+// counters are advanced only when they are not.
+int step_front(infmllm_stream* s, const void* q, const void* k, const void* v, int L, void* out, int32_t* retained,
+               int32_t* n_retained, bool merge_in_select, bool* evict, KeySource* ks_out, int* nsplit_out,
+               const char* who)
 {
-    if (!s) return fail(INFMLLM_EINVAL, "step: stream is null");
-    if (!s->attached) return fail(INFMLLM_ESTATE, "step: stream has no workspace attached");
-    if (!q || !k || !v || !out) return fail(INFMLLM_EINVAL, "step: q, k, v and out must not be null");
-    if (L < 1) return fail(INFMLLM_EINVAL, "step: chunk_len must be >= 1 (got %d)", L);
+    if (!s) return fail(INFMLLM_EINVAL, "%s: stream is null", who);
+    if (!s->attached) return fail(INFMLLM_ESTATE, "%s: stream has no workspace attached", who);
+    if (s->pending) return fail(INFMLLM_ESTATE, "%s: an eviction is pending on this stream", who);
+    if (!q || !k || !v || !out) return fail(INFMLLM_EINVAL, "%s: q, k, v and out must not be null", who);
+    if (L < 1) return fail(INFMLLM_EINVAL, "%s: chunk_len must be >= 1 (got %d)", who, L);
     if (L > s->g.max_chunk)
-        return fail(INFMLLM_ECAPACITY, "step: chunk_len %d exceeds max_chunk %d", L, s->g.max_chunk);
+        return fail(INFMLLM_ECAPACITY, "%s: chunk_len %d exceeds max_chunk %d", who, L, s->g.max_chunk);
     if (s->streamed + L > (int64_t)INT32_MAX)
-        return fail(INFMLLM_ECAPACITY, "step: stream positions would exceed 2^31-1");
+        return fail(INFMLLM_ECAPACITY, "%s: stream positions would exceed 2^31-1", who);
 
     const Geometry& g = s->g;
     const CacheView& cur = s->cache[s->cur];
@@ -241,42 +254,133 @@ int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* 
     const KeySource ks = in_place ? KeySource{t, k, v} : KeySource{n, nullptr, nullptr};
     if (!in_place) {
         s->mark(INFMLLM_K_APPEND, 0);
-        if ((e = launch_append(g, cur, k, v, t, L, s->streamed, s->st)) != hipSuccess) return fail_hip(e, "step: append");
+        if ((e = launch_append(g, cur, k, v, t, L, s->streamed, s->st)) != hipSuccess) return fail_hip(e, "append");
         s->mark(INFMLLM_K_APPEND, 1);
     }
     s->mark(INFMLLM_K_ATTN, 0);
     int nsplit = 1;     // > 1: the attention left key-split partials that the select launch merges into out
-    e = mfma ? launch_attn_mfma(g, cur, ks, q, t, L, out, s->lse, s->fwd, /*defer_combine=*/n > g.B, &nsplit, s->st)
+    e = mfma ? launch_attn_mfma(g, cur, ks, q, t, L, out, s->lse, s->fwd, /*defer_combine=*/merge_in_select && n > g.B,
+                                &nsplit, s->st)
              : launch_attn_simple(g, cur, q, t, L, out, s->lse, s->st);
-    if (e != hipSuccess) return fail_hip(e, "step: attention");
+    if (e != hipSuccess) return fail_hip(e, "attention");
     s->mark(INFMLLM_K_ATTN, 1);
 
+    *evict = n > g.B;
+    *ks_out = ks;
+    *nsplit_out = nsplit;
     if (n <= g.B) {
         // the chunk fits: nothing is evicted
-        if ((e = launch_iota(g, n, retained, n_retained, s->st)) != hipSuccess) return fail_hip(e, "step: index list");
+        if ((e = launch_iota(g, n, retained, n_retained, s->st)) != hipSuccess) return fail_hip(e, "index list");
         s->len = n;
         s->last_cnd = 0;
-    } else {
-        s->mark(INFMLLM_K_SCORE, 0);
-        e = mfma ? launch_score_mfma(g, cur, ks, q, s->lse, s->fwd, nsplit, t, L, s->Wb, s->st)
-                 : launch_score_simple(g, cur, q, s->lse, t, L, s->Wb, s->st);
-        if (e != hipSuccess) return fail_hip(e, "step: score");
-        s->mark(INFMLLM_K_SCORE, 1);
-        s->mark(INFMLLM_K_SELECT, 0);
-        const CacheView& nxt = s->cache[s->cur ^ 1];
-        const CombineJob cj{s->fwd.part_o, s->fwd.part_ml, out, L, g.Hq, nsplit};
-        if ((e = launch_select(g, s->Wb, n, s->I, retained, n_retained, cur, ks, s->streamed, nxt, cj, s->st)) != hipSuccess)
-            return fail_hip(e, "step: select");
-        s->mark(INFMLLM_K_SELECT, 1);
-        s->mark(INFMLLM_K_COMPACT, 0);
-        if ((e = launch_compact(g, cur, ks, s->streamed, nxt, s->I, s->Wb, n, s->st)) != hipSuccess) return fail_hip(e, "step: compact");
-        s->mark(INFMLLM_K_COMPACT, 1);
-        s->cur ^= 1;
-        s->len = g.B;
-        s->last_cnd = n - g.R;
+        s->streamed += L;
+        if (s->prof_steps < s->prof_cap) ++s->prof_steps;
+        return INFMLLM_OK;
     }
+    s->mark(INFMLLM_K_SCORE, 0);
+    e = mfma ? launch_score_mfma(g, cur, ks, q, s->lse, s->fwd, nsplit, t, L, s->Wb, s->st)
+             : launch_score_simple(g, cur, q, s->lse, t, L, s->Wb, s->st);
+    if (e != hipSuccess) return fail_hip(e, "score");
+    s->mark(INFMLLM_K_SCORE, 1);
+    return INFMLLM_OK;
+}
+
+// host bookkeeping once a5-a7 of a step of L tokens (n keys before eviction) have been launched
+void step_done(infmllm_stream* s, int n, int L)
+{
+    s->cur ^= 1;
+    s->len = s->g.B;
+    s->last_cnd = n - s->g.R;
     s->streamed += L;
+    s->pending = false;
     if (s->prof_steps < s->prof_cap) ++s->prof_steps;
+}
+
+}  // namespace
+
+extern "C" {
+
+int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* v, int L, void* out,
+                 int32_t* retained, int32_t* n_retained)
+{
+    bool evict = false;
+    KeySource ks{0, nullptr, nullptr};
+    int nsplit = 1;
+    const int rc = step_front(s, q, k, v, L, out, retained, n_retained, true, &evict, &ks, &nsplit, "step");
+    if (rc != INFMLLM_OK || !evict) return rc;
+    const Geometry& g = s->g;
+    const CacheView& cur = s->cache[s->cur];
+    const CacheView& nxt = s->cache[s->cur ^ 1];
+    const int n = s->len + L;
+    hipError_t e;
+    s->mark(INFMLLM_K_SELECT, 0);
+    const CombineJob cj{s->fwd.part_o, s->fwd.part_ml, out, L, g.Hq, nsplit};
+    if ((e = launch_select(g, s->Wb, n, s->I, retained, n_retained, cur, ks, s->streamed, nxt, cj, s->st)) != hipSuccess)
+        return fail_hip(e, "step: select");
+    s->mark(INFMLLM_K_SELECT, 1);
+    s->mark(INFMLLM_K_COMPACT, 0);
+    if ((e = launch_compact(g, cur, ks, s->streamed, nxt, s->I, s->Wb, n, s->st)) != hipSuccess) return fail_hip(e, "step: compact");
+    s->mark(INFMLLM_K_COMPACT, 1);
+    step_done(s, n, L);
+    return INFMLLM_OK;
+}
+
+int infmllm_step_attend(infmllm_stream_t* s, const void* q, const void* k, const void* v, int L, void* out,
+                        int32_t* retained, int32_t* n_retained)
+{
+    bool evict = false;
+    KeySource ks{0, nullptr, nullptr};
+    int nsplit = 1;
+    const int rc = step_front(s, q, k, v, L, out, retained, n_retained, false, &evict, &ks, &nsplit, "step_attend");
+    if (rc != INFMLLM_OK || !evict) return rc;
+    s->pending = true;
+    s->pend_ks = ks;
+    s->pend_n = s->len + L;
+    s->pend_L = L;
+    return INFMLLM_OK;
+}
+
+int infmllm_stream_pending(const infmllm_stream_t* s) { return s ? (s->pending ? 1 : 0) : -1; }
+
+int infmllm_evict_batched(infmllm_stream_t* const* streams, int count, int32_t* const* retained,
+                          int32_t* const* n_retained)
+{
+    if (!streams || count < 1) return fail(INFMLLM_EINVAL, "evict_batched: no streams");
+    const infmllm_stream* s0 = streams[0];
+    for (int i = 0; i < count; ++i) {
+        const infmllm_stream* s = streams[i];
+        if (!s) return fail(INFMLLM_EINVAL, "evict_batched: stream %d is null", i);
+        if (!s->attached || !s->pending) return fail(INFMLLM_ESTATE, "evict_batched: stream %d has no eviction pending", i);
+        for (int j = 0; j < i; ++j)
+            if (streams[j] == s) return fail(INFMLLM_EINVAL, "evict_batched: stream %d appears twice", i);
+        const Geometry &a = s->g, &b = s0->g;
+        if (a.B != b.B || a.R != b.R || a.Hq != b.Hq || a.Hkv != b.Hkv || a.d != b.d || a.cap != b.cap ||
+            a.elt != b.elt || s->st != s0->st)
+            return fail(INFMLLM_EINVAL, "evict_batched: stream %d differs from stream 0 in geometry or HIP stream", i);
+    }
+    infmllm_stream* lead = streams[0];
+    for (int base = 0; base < count; base += EVICT_MAX_JOBS) {
+        EvictBatch eb{};
+        eb.count = count - base < EVICT_MAX_JOBS ? count - base : EVICT_MAX_JOBS;
+        for (int j = 0; j < eb.count; ++j) {
+            infmllm_stream* s = streams[base + j];
+            EvictJob& job = eb.job[j];
+            job.Wb = s->Wb; job.I = s->I;
+            job.user_I = retained ? retained[base + j] : nullptr;
+            job.user_count = n_retained ? n_retained[base + j] : nullptr;
+            job.src = s->cache[s->cur]; job.dst = s->cache[s->cur ^ 1];
+            job.kc = s->pend_ks.k; job.vc = s->pend_ks.v;
+            job.tc = s->pend_ks.rows; job.pos0 = (int)s->streamed; job.n = s->pend_n;
+        }
+        hipError_t e;
+        lead->mark(INFMLLM_K_SELECT, 0);
+        if ((e = launch_select_batch(lead->g, eb, lead->st)) != hipSuccess) return fail_hip(e, "evict_batched: select");
+        lead->mark(INFMLLM_K_SELECT, 1);
+        lead->mark(INFMLLM_K_COMPACT, 0);
+        if ((e = launch_compact_batch(lead->g, eb, lead->st)) != hipSuccess) return fail_hip(e, "evict_batched: compact");
+        lead->mark(INFMLLM_K_COMPACT, 1);
+        for (int j = 0; j < eb.count; ++j) step_done(streams[base + j], streams[base + j]->pend_n, streams[base + j]->pend_L);
+    }
     return INFMLLM_OK;
 }
 
@@ -324,6 +428,7 @@ int infmllm_decode(infmllm_stream_t* s, const void* q, const void* k, const void
 {
     if (!s) return fail(INFMLLM_EINVAL, "decode: stream is null");
     if (!s->attached) return fail(INFMLLM_ESTATE, "decode: stream has no workspace attached");
+    if (s->pending) return fail(INFMLLM_ESTATE, "decode: an eviction is pending on this stream");
     if (!q || !k || !v || !out) return fail(INFMLLM_EINVAL, "decode: q, k, v and out must not be null");
     if (s->len >= s->g.B + s->g.max_decode)
         return fail(INFMLLM_ECAPACITY, "decode: the cache already holds budget + max_decode = %d rows",
@@ -360,6 +465,7 @@ int infmllm_stream_positions(infmllm_stream_t* s, int32_t* pos)
 {
     if (!s || !pos) return fail(INFMLLM_EINVAL, "positions: null argument");
     if (!s->attached) return fail(INFMLLM_ESTATE, "positions: stream has no workspace attached");
+    if (s->pending) return fail(INFMLLM_ESTATE, "positions: an eviction is pending on this stream");
     return copy_rows(s, pos, (size_t)(s->g.B + s->g.max_decode) * 4, s->cache[s->cur].pos, (size_t)s->g.cap * 4, (size_t)s->len * 4,
                      "positions: copy");
 }
@@ -368,6 +474,7 @@ int infmllm_stream_export(infmllm_stream_t* s, void* K, void* V, int32_t* pos, f
 {
     if (!s) return fail(INFMLLM_EINVAL, "export: stream is null");
     if (!s->attached) return fail(INFMLLM_ESTATE, "export: stream has no workspace attached");
+    if (s->pending) return fail(INFMLLM_ESTATE, "export: an eviction is pending on this stream");
     const Geometry& g = s->g;
     const CacheView& c = s->cache[s->cur];
     const size_t row = (size_t)g.d * g.elt;
@@ -386,6 +493,7 @@ int infmllm_stream_import(infmllm_stream_t* s, const void* K, const void* V, con
 {
     if (!s) return fail(INFMLLM_EINVAL, "import: stream is null");
     if (!s->attached) return fail(INFMLLM_ESTATE, "import: stream has no workspace attached");
+    if (s->pending) return fail(INFMLLM_ESTATE, "import: an eviction is pending on this stream");
     if (len < 0 || len > s->g.B + s->g.max_decode)
         return fail(INFMLLM_EINVAL, "import: len must lie in 0..budget + max_decode (got %d)", len);
     if (len > 0 && (!K || !V || !pos)) return fail(INFMLLM_EINVAL, "import: K, V and pos must not be null");
@@ -414,6 +522,7 @@ int infmllm_stream_last_scores(infmllm_stream_t* s, float* w, int* n_candidates)
 {
     if (!s || !n_candidates) return fail(INFMLLM_EINVAL, "last_scores: null argument");
     if (!s->attached) return fail(INFMLLM_ESTATE, "last_scores: stream has no workspace attached");
+    if (s->pending) return fail(INFMLLM_ESTATE, "last_scores: an eviction is pending on this stream");
     *n_candidates = s->last_cnd;
     if (s->last_cnd == 0 || !w) return INFMLLM_OK;
     return copy_rows(s, w, (size_t)s->last_cnd * 4, s->Wb, (size_t)s->g.cap * 4, (size_t)s->last_cnd * 4,

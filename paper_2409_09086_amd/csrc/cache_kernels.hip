@@ -56,13 +56,14 @@ fill_inf_kernel(float* __restrict__ score, int len, int Hkv, int cap)
 
 // dst[h][x] <- src[h][I[h][x]] for x < rows (the relevant rows; I has row stride B).  One thread per
 // 16-byte vector of a row of K and V.
-template <int VPR>   // vectors per row
-__global__ void __launch_bounds__(256)
-compact_kernel(const u32x4* __restrict__ Ks, const u32x4* __restrict__ Vs, const int32_t* __restrict__ ps,
-               const u32x4* __restrict__ kc, const u32x4* __restrict__ vc, int tc, int pos0, int Hkv,
-               u32x4* __restrict__ Kd, u32x4* __restrict__ Vd, int32_t* __restrict__ pd,
-               float* __restrict__ sd, const int32_t* __restrict__ I, const float* __restrict__ Wb,
-               int B, int rows, int cap)
+template <int VPR>
+__device__ __forceinline__ void compact_body(const u32x4* __restrict__ Ks, const u32x4* __restrict__ Vs,
+                                             const int32_t* __restrict__ ps, const u32x4* __restrict__ kc,
+                                             const u32x4* __restrict__ vc, int tc, int pos0, int Hkv,
+                                             u32x4* __restrict__ Kd, u32x4* __restrict__ Vd,
+                                             int32_t* __restrict__ pd, float* __restrict__ sd,
+                                             const int32_t* __restrict__ I, const float* __restrict__ Wb, int B,
+                                             int rows, int cap)
 {
     constexpr int ROWS = 256 / VPR;               // rows per block pass
     const int h = blockIdx.y;
@@ -98,6 +99,28 @@ compact_kernel(const u32x4* __restrict__ Ks, const u32x4* __restrict__ Vs, const
             }
         }
     }
+}
+
+template <int VPR>
+__global__ void __launch_bounds__(256)
+compact_kernel(const u32x4* __restrict__ Ks, const u32x4* __restrict__ Vs, const int32_t* __restrict__ ps,
+               const u32x4* __restrict__ kc, const u32x4* __restrict__ vc, int tc, int pos0, int Hkv,
+               u32x4* __restrict__ Kd, u32x4* __restrict__ Vd, int32_t* __restrict__ pd,
+               float* __restrict__ sd, const int32_t* __restrict__ I, const float* __restrict__ Wb,
+               int B, int rows, int cap)
+{
+    compact_body<VPR>(Ks, Vs, ps, kc, vc, tc, pos0, Hkv, Kd, Vd, pd, sd, I, Wb, B, rows, cap);
+}
+
+// blockIdx.z = stream of the batch
+template <int VPR>
+__global__ void __launch_bounds__(256)
+compact_batch_kernel(EvictBatch eb, int Hkv, int B, int rows, int cap)
+{
+    const EvictJob& j = eb.job[blockIdx.z];
+    compact_body<VPR>((const u32x4*)j.src.K, (const u32x4*)j.src.V, j.src.pos, (const u32x4*)j.kc, (const u32x4*)j.vc,
+                      j.tc, j.pos0, Hkv, (u32x4*)j.dst.K, (u32x4*)j.dst.V, j.dst.pos, j.dst.score, j.I, j.Wb, B, rows,
+                      cap);
 }
 
 }  // namespace
@@ -153,6 +176,23 @@ hipError_t launch_compact(const Geometry& g, const CacheView& src, const KeySour
         default: return hipErrorInvalidValue;
     }
 #undef INFMLLM_COMPACT
+    return hipGetLastError();
+}
+
+hipError_t launch_compact_batch(const Geometry& g, const EvictBatch& eb, hipStream_t st)
+{
+    if (eb.count < 1 || eb.count > EVICT_MAX_JOBS) return hipErrorInvalidValue;
+    const int vpr = g.d * g.elt / 16;
+    const int rows_per_pass = (256 / vpr) * 4;
+    const int rows = g.B - g.R;
+    if (rows <= 0) return hipSuccess;
+    const dim3 grid((rows + rows_per_pass - 1) / rows_per_pass, g.Hkv, eb.count), block(256);
+    switch (vpr) {
+        case 8: hipLaunchKernelGGL(compact_batch_kernel<8>, grid, block, 0, st, eb, g.Hkv, g.B, rows, g.cap); break;
+        case 16: hipLaunchKernelGGL(compact_batch_kernel<16>, grid, block, 0, st, eb, g.Hkv, g.B, rows, g.cap); break;
+        case 32: hipLaunchKernelGGL(compact_batch_kernel<32>, grid, block, 0, st, eb, g.Hkv, g.B, rows, g.cap); break;
+        default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

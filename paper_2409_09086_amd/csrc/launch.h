@@ -93,6 +93,26 @@ hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, 
                          int32_t* user_count, const CacheView& src, const KeySource& ks, int64_t T,
                          const CacheView& dst, const CombineJob& cj, hipStream_t st);
 
+// One stream's share of a batched eviction (a5-a7 for the layers of a model in one launch each,
+// Alg. 1 Input note).  All streams of a batch have the same geometry.
+struct EvictJob {
+    const float* Wb;          // [Hkv][cap] biased scores of this stream
+    int32_t* I;               // [Hkv][B] index list (stream scratch)
+    int32_t* user_I;          // [Hkv][B] or null
+    int32_t* user_count;      // one int or null
+    CacheView src, dst;       // live half, other half
+    const void* kc;           // chunk tensors, rows >= tc of the key axis
+    const void* vc;
+    int tc, pos0, n, pad_;
+};
+constexpr int EVICT_MAX_JOBS = 16;
+struct EvictBatch {
+    int count, pad_;
+    EvictJob job[EVICT_MAX_JOBS];
+};
+hipError_t launch_select_batch(const Geometry& g, const EvictBatch& eb, hipStream_t st);
+hipError_t launch_compact_batch(const Geometry& g, const EvictBatch& eb, hipStream_t st);
+
 // warm-up: I[h][j] = j for j < n.
 hipError_t launch_iota(const Geometry& g, int n, int32_t* user_I, int32_t* user_count, hipStream_t st);
 

@@ -50,10 +50,9 @@ struct RecentCopy {
     int tc, pos0, vpr, ncopy;                                 // vpr = 16-byte vectors per row
 };
 
-__device__ __forceinline__ void copy_recent(const RecentCopy& rc, int Hkv, int cnd, int r, int R, int cap)
+__device__ __forceinline__ void copy_recent(const RecentCopy& rc, int wg, int Hkv, int cnd, int r, int R, int cap)
 {
     const long total = (long)Hkv * R * rc.vpr;
-    const int wg = blockIdx.x - Hkv;
     for (long idx = (long)wg * TPB + threadIdx.x; idx < total; idx += (long)rc.ncopy * TPB) {
         const int x = (int)(idx % rc.vpr);
         const long hr = idx / rc.vpr;
@@ -106,19 +105,16 @@ __device__ __forceinline__ void combine_partials(const CombineJob& cj, int first
     }
 }
 
-__global__ void __launch_bounds__(TPB)
-select_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __restrict__ userI,
-              int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap, int Hkv, RecentCopy rc,
-              CombineJob cj, int ncomb)
+// Selection of kv-head h by one workgroup, candidates re-read from memory in every pass.
+__device__ __forceinline__ void select_mem_body(const float* __restrict__ Wb, int32_t* __restrict__ I,
+                                                int32_t* __restrict__ userI, int32_t* __restrict__ user_count,
+                                                int h, int cnd, int r, int R, int B, int cap)
 {
-    if ((int)blockIdx.x >= Hkv + rc.ncopy) { combine_partials(cj, Hkv + rc.ncopy, ncomb); return; }
-    if ((int)blockIdx.x >= Hkv) { copy_recent(rc, Hkv, cnd, r, R, cap); return; }
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_prefix, s_remaining, s_ties;
     __shared__ uint32_t wave_eq[NW], wave_keep[NW];
     __shared__ uint32_t run_eq, run_keep;
 
-    const int h = blockIdx.x;
     const float* W = Wb + (size_t)h * cap;
     int32_t* Ih = I + (size_t)h * B;
     int32_t* Uh = userI ? userI + (size_t)h * B : nullptr;
@@ -217,18 +213,15 @@ select_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __
 // exponent bits, a handful of distinct values) is counted through ballots, the later digits
 // (spread evenly) through plain LDS atomics, and the ordered write needs four barriers in all.
 template <int KPT>
-__global__ void __launch_bounds__(TPB)
-select_reg_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __restrict__ userI,
-                  int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap, int Hkv, RecentCopy rc,
-                  CombineJob cj, int ncomb)
+__device__ __forceinline__ void select_reg_body(const float* __restrict__ Wb, int32_t* __restrict__ I,
+                                                int32_t* __restrict__ userI, int32_t* __restrict__ user_count,
+                                                int h, int cnd, int r, int R, int B, int cap)
 {
-    if ((int)blockIdx.x >= Hkv + rc.ncopy) { combine_partials(cj, Hkv + rc.ncopy, ncomb); return; }
-    if ((int)blockIdx.x >= Hkv) { copy_recent(rc, Hkv, cnd, r, R, cap); return; }
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_prefix, s_remaining, s_ties;
     __shared__ uint32_t tab_eq[KPT * NW], tab_keep[KPT * NW];
 
-    const int h = blockIdx.x, tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
     const float* W = Wb + (size_t)h * cap;
     int32_t* Ih = I + (size_t)h * B;
     int32_t* Uh = userI ? userI + (size_t)h * B : nullptr;
@@ -346,6 +339,50 @@ select_reg_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t
     if (user_count && h == 0 && tid == 0) *user_count = B;
 }
 
+// KPT = 0: candidates stay in memory.
+template <int KPT>
+__device__ __forceinline__ void select_body(const float* Wb, int32_t* I, int32_t* userI, int32_t* user_count, int h,
+                                            int cnd, int r, int R, int B, int cap)
+{
+    if constexpr (KPT == 0) select_mem_body(Wb, I, userI, user_count, h, cnd, r, R, B, cap);
+    else select_reg_body<KPT>(Wb, I, userI, user_count, h, cnd, r, R, B, cap);
+}
+
+// One stream: workgroups [0, Hkv) select, the next rc.ncopy move the recent window, the rest
+// merge attention partials.
+template <int KPT>
+__global__ void __launch_bounds__(TPB)
+select_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __restrict__ userI,
+              int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap, int Hkv, RecentCopy rc,
+              CombineJob cj, int ncomb)
+{
+    if ((int)blockIdx.x >= Hkv + rc.ncopy) { combine_partials(cj, Hkv + rc.ncopy, ncomb); return; }
+    if ((int)blockIdx.x >= Hkv) { copy_recent(rc, blockIdx.x - Hkv, Hkv, cnd, r, R, cap); return; }
+    select_body<KPT>(Wb, I, userI, user_count, blockIdx.x, cnd, r, R, B, cap);
+}
+
+// Several streams of one geometry (the layers of a model, Alg. 1 Input note): stream j owns
+// workgroups [j * (Hkv + ncopy), (j + 1) * (Hkv + ncopy)) with the same split into selecting
+// and copying workgroups.
+template <int KPT>
+__global__ void __launch_bounds__(TPB)
+select_batch_kernel(EvictBatch eb, int r, int R, int B, int cap, int Hkv, int vpr, int ncopy)
+{
+    const int per = Hkv + ncopy, j = blockIdx.x / per, b = blockIdx.x % per;
+    const EvictJob& job = eb.job[j];
+    const int cnd = job.n - R;
+    if (b >= Hkv) {
+        RecentCopy rc;
+        rc.Ks = (const u32x4*)job.src.K; rc.Vs = (const u32x4*)job.src.V; rc.ps = job.src.pos;
+        rc.kc = (const u32x4*)job.kc; rc.vc = (const u32x4*)job.vc;
+        rc.Kd = (u32x4*)job.dst.K; rc.Vd = (u32x4*)job.dst.V; rc.pd = job.dst.pos; rc.sd = job.dst.score;
+        rc.tc = job.tc; rc.pos0 = job.pos0; rc.vpr = vpr; rc.ncopy = ncopy;
+        copy_recent(rc, b - Hkv, Hkv, cnd, r, R, cap);
+        return;
+    }
+    select_body<KPT>(job.Wb, job.I, job.user_I, job.user_count, b, cnd, r, R, B, cap);
+}
+
 }  // namespace
 
 hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, int32_t* user_I,
@@ -368,13 +405,35 @@ hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, 
         ncomb = (int)(cw > 256 ? 256 : cw);
     }
     const dim3 grid(g.Hkv + rc.ncopy + ncomb);
-#define INFMLLM_SELECT(KERNEL)                                                                           \
-    hipLaunchKernelGGL(KERNEL, grid, dim3(TPB), 0, st, Wb, I, user_I, user_count, cnd, r, g.R, g.B, g.cap, g.Hkv, rc, cj, ncomb)
-    if (cnd <= 2 * TPB) INFMLLM_SELECT(select_reg_kernel<2>);
-    else if (cnd <= 4 * TPB) INFMLLM_SELECT(select_reg_kernel<4>);
-    else if (cnd <= 8 * TPB) INFMLLM_SELECT(select_reg_kernel<8>);
-    else if (cnd <= 16 * TPB) INFMLLM_SELECT(select_reg_kernel<16>);
-    else INFMLLM_SELECT(select_kernel);                      // candidates stay in memory
+#define INFMLLM_SELECT(KPT)                                                                                \
+    hipLaunchKernelGGL(select_kernel<KPT>, grid, dim3(TPB), 0, st, Wb, I, user_I, user_count, cnd, r, g.R, g.B, g.cap, \
+                       g.Hkv, rc, cj, ncomb)
+    if (cnd <= 2 * TPB) INFMLLM_SELECT(2);
+    else if (cnd <= 4 * TPB) INFMLLM_SELECT(4);
+    else if (cnd <= 8 * TPB) INFMLLM_SELECT(8);
+    else if (cnd <= 16 * TPB) INFMLLM_SELECT(16);
+    else INFMLLM_SELECT(0);                                  // candidates stay in memory
+#undef INFMLLM_SELECT
+    return hipGetLastError();
+}
+
+hipError_t launch_select_batch(const Geometry& g, const EvictBatch& eb, hipStream_t st)
+{
+    if (eb.count < 1 || eb.count > EVICT_MAX_JOBS) return hipErrorInvalidValue;
+    const int r = g.B - g.R, vpr = g.d * g.elt / 16;
+    int cnd = 0;
+    for (int j = 0; j < eb.count; ++j) cnd = eb.job[j].n - g.R > cnd ? eb.job[j].n - g.R : cnd;
+    const long vecs = (long)g.Hkv * g.R * vpr;
+    long want = (vecs + 4 * TPB - 1) / (4 * TPB);
+    const int ncopy = (int)(want > 448 ? 448 : want);
+    const dim3 grid((g.Hkv + ncopy) * eb.count);
+#define INFMLLM_SELECT(KPT) \
+    hipLaunchKernelGGL(select_batch_kernel<KPT>, grid, dim3(TPB), 0, st, eb, r, g.R, g.B, g.cap, g.Hkv, vpr, ncopy)
+    if (cnd <= 2 * TPB) INFMLLM_SELECT(2);
+    else if (cnd <= 4 * TPB) INFMLLM_SELECT(4);
+    else if (cnd <= 8 * TPB) INFMLLM_SELECT(8);
+    else if (cnd <= 16 * TPB) INFMLLM_SELECT(16);
+    else INFMLLM_SELECT(0);
 #undef INFMLLM_SELECT
     return hipGetLastError();
 }

@@ -70,6 +70,36 @@ class LockStep:
         self.steps += 1
         return out_g, I_g
 
+    def attend(self, q, k, v):
+        """First half of a layer-batched step: step_attend on the GPU, attend on the oracle, outputs
+        compared.  If nothing is pending afterwards the step is finished here; otherwise finish()
+        must follow the batched eviction."""
+        dev = self.gpu.device
+        self._t = len(self.oracle)
+        out_g, self._ret, self._cnt = self.gpu.step_attend(q.to(dev), k.to(dev), v.to(dev))
+        out_o = self.oracle.attend(q.double().numpy(), k.double().numpy(), v.double().numpy())
+        self._n = self._t + q.shape[0]
+        err = float(np.abs(out_g.double().cpu().numpy() - out_o).max())
+        self.max_err = max(self.max_err, err)
+        assert np.isfinite(err) and err <= OUT_TOL[self.gpu.dtype], "step %d: attention output off by %g" % (self.steps, err)
+        assert self.gpu.pending == (self._n > self.gpu.budget)
+        if not self.gpu.pending:
+            self.finish()
+        return out_g
+
+    def finish(self):
+        """Second half: the retained lists (written by step_attend or by the batched eviction)."""
+        n = self._n
+        count = int(self._cnt.item())
+        assert count == min(n, self.gpu.budget) == len(self.gpu)
+        sc = self.oracle.scores()
+        I_o = self.oracle.select()
+        I_g = self._ret.cpu().numpy()[:, :count]
+        self.swaps += check_retained(I_g, I_o, None if sc is None else sc[1], n, self.gpu.budget, self.gpu.recent)
+        self.oracle.commit(I_g)
+        self.steps += 1
+        return I_g
+
     def decode(self, q, k, v):
         """One decoding step on both sides (q [1,Hq,d], k/v [1,Hkv,d]); compares the outputs."""
         dev = self.gpu.device
