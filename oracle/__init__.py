@@ -47,6 +47,8 @@ def _load():
             lib.oracle_attend.argtypes = [P, P, P, P, ctypes.c_int, P]
             lib.oracle_decode.argtypes = [P, P, P, P, P]
             lib.oracle_candidates.argtypes = [P]
+            lib.oracle_set_policy.argtypes = [P, ctypes.c_int]
+            lib.oracle_accumulated.argtypes = [P, P]
             lib.oracle_scores.argtypes = [P, P, P]
             lib.oracle_select.argtypes = [P, P]
             lib.oracle_commit.argtypes = [P, P, ctypes.c_int]
@@ -76,7 +78,9 @@ class OracleStream:
     scale (default 1/sqrt(head_dim)).
     """
 
-    def __init__(self, budget, recent, heads, kv_heads, head_dim, bias=1e-4, scale=None):
+    POLICIES = {"infmllm": 0, "window": 1, "initial_recent": 2, "cumulative": 3}
+
+    def __init__(self, budget, recent, heads, kv_heads, head_dim, bias=1e-4, scale=None, policy="infmllm"):
         lib = _load()
         if scale is None:
             scale = 1.0 / np.sqrt(head_dim)
@@ -85,6 +89,9 @@ class OracleStream:
             raise ValueError("oracle_create: invalid arguments")
         self.budget, self.recent, self.heads, self.kv_heads, self.head_dim = budget, recent, heads, kv_heads, head_dim
         self.bias, self.scale = float(bias), float(scale)
+        self.policy = policy
+        if lib.oracle_set_policy(self._h, self.POLICIES[policy]) != 0:
+            raise ValueError("oracle_set_policy failed")
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
@@ -157,6 +164,12 @@ class OracleStream:
         if n < 0:
             raise RuntimeError("oracle_decode failed: %d" % n)
         return out
+
+    def accumulated(self):
+        """[Hkv, t] accumulated scores of the cached rows (cumulative policy; zeros otherwise)."""
+        A = np.empty((self.kv_heads, len(self)), dtype=np.float64)
+        _lib.oracle_accumulated(self._h, _ptr(A))
+        return A
 
     # -- state ------------------------------------------------------------------------------
     def export(self):

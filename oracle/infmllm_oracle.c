@@ -36,6 +36,17 @@
  *   - while n <= B nothing is evicted.
  *   - the chunk's attention output uses the cache before eviction.
  *
+ * Comparison policies (Sec. 2 "KV cache eviction", Sec. 4.1 baselines), selectable with
+ * oracle_set_policy; each only replaces the score W' that Alg. 1 l.5 ranks:
+ *   1 window          : W'[j] = j            -> the cache is the newest B tokens
+ *   2 initial + recent: W'[j] = -j           -> the r oldest cached tokens and the R newest
+ *   3 cumulative      : W'[j] = A[j] + S[j]  -> A[j] = sum of S over the earlier steps in which
+ *                       row j was a candidate (0 for a row never scored); no attention bias;
+ *                       the retained rows carry W' on as their A.
+ *   Reading: the paper names these methods without formulas; the three rules above are the
+ *   plain statements of "keep recent", "keep initial and recent" and "keep the heaviest by
+ *   accumulated attention" inside this step's (r, R) frame.
+ *
  * All arithmetic is IEEE double.  Inputs are taken as exact values (a bf16 or fp32
  * input converts to double without rounding).
  *
@@ -80,6 +91,8 @@ typedef struct oracle_stream {
     int evict;    /* n > B                                                */
     double *S;    /* [Hkv][cap] column mean, first c = n - R entries used */
     double *Wb;   /* [Hkv][cap] biased score                              */
+    int policy;   /* 0 Alg. 1, 1 window, 2 initial + recent, 3 cumulative */
+    double *A;    /* [Hkv][cap] accumulated score of each cached row      */
 } oracle_stream;
 
 static int grow(oracle_stream *s, int need)
@@ -92,8 +105,9 @@ static int grow(oracle_stream *s, int need)
     int64_t *pos = (int64_t *)calloc((size_t)s->Hkv * ncap, sizeof(int64_t));
     double *S = (double *)calloc((size_t)s->Hkv * ncap, sizeof(double));
     double *Wb = (double *)calloc((size_t)s->Hkv * ncap, sizeof(double));
-    if (!K || !V || !pos || !S || !Wb) {
-        free(K); free(V); free(pos); free(S); free(Wb);
+    double *A = (double *)calloc((size_t)s->Hkv * ncap, sizeof(double));
+    if (!K || !V || !pos || !S || !Wb || !A) {
+        free(K); free(V); free(pos); free(S); free(Wb); free(A);
         return -1;
     }
     for (int h = 0; h < s->Hkv; ++h) {
@@ -101,10 +115,11 @@ static int grow(oracle_stream *s, int need)
             memcpy(K + (size_t)h * ncap * row, s->K + (size_t)h * s->cap * row, (size_t)s->t * row * sizeof(double));
             memcpy(V + (size_t)h * ncap * row, s->V + (size_t)h * s->cap * row, (size_t)s->t * row * sizeof(double));
             memcpy(pos + (size_t)h * ncap, s->pos + (size_t)h * s->cap, (size_t)s->t * sizeof(int64_t));
+            memcpy(A + (size_t)h * ncap, s->A + (size_t)h * s->cap, (size_t)s->t * sizeof(double));
         }
     }
-    free(s->K); free(s->V); free(s->pos); free(s->S); free(s->Wb);
-    s->K = K; s->V = V; s->pos = pos; s->S = S; s->Wb = Wb; s->cap = ncap;
+    free(s->K); free(s->V); free(s->pos); free(s->S); free(s->Wb); free(s->A);
+    s->K = K; s->V = V; s->pos = pos; s->S = S; s->Wb = Wb; s->A = A; s->cap = ncap;
     return 0;
 }
 
@@ -124,8 +139,16 @@ oracle_stream *oracle_create(int budget, int recent, int heads, int kv_heads, in
 void oracle_destroy(oracle_stream *s)
 {
     if (!s) return;
-    free(s->K); free(s->V); free(s->pos); free(s->S); free(s->Wb);
+    free(s->K); free(s->V); free(s->pos); free(s->S); free(s->Wb); free(s->A);
     free(s);
+}
+
+/* selects the score that Alg. 1 l.5 ranks (see the header); only between steps */
+int oracle_set_policy(oracle_stream *s, int policy)
+{
+    if (!s || s->pending || policy < 0 || policy > 3) return -1;
+    s->policy = policy;
+    return 0;
 }
 
 int oracle_len(const oracle_stream *s) { return s->t; }
@@ -189,6 +212,7 @@ int oracle_attend(oracle_stream *s, const double *q, const double *k, const doub
             memcpy(s->K + ((size_t)h * s->cap + t + i) * dh, k + ((size_t)i * s->Hkv + h) * dh, dh * sizeof(double));
             memcpy(s->V + ((size_t)h * s->cap + t + i) * dh, v + ((size_t)i * s->Hkv + h) * dh, dh * sizeof(double));
             s->pos[(size_t)h * s->cap + t + i] = s->T + i;
+            s->A[(size_t)h * s->cap + t + i] = 0.0;
         }
     }
     s->n = n; s->L = L; s->evict = (n > s->B);
@@ -234,6 +258,9 @@ int oracle_attend(oracle_stream *s, const double *q, const double *k, const doub
                 S[j] = acc / (double)G;
                 const double D = -(double)(c - 1 - j) * d;   /* Alg. 1 l.3 */
                 Wb[j] = S[j] + D;                            /* Alg. 1 l.4 */
+                if (s->policy == 1) Wb[j] = (double)j;                            /* newest first */
+                if (s->policy == 2) Wb[j] = -(double)j;                           /* oldest first */
+                if (s->policy == 3) Wb[j] = s->A[(size_t)h * s->cap + j] + S[j];  /* heaviest first */
             }
         }
         free(Sg);
@@ -259,6 +286,7 @@ int oracle_decode(oracle_stream *s, const double *q, const double *k, const doub
         memcpy(s->K + ((size_t)h * s->cap + t) * dh, k + (size_t)h * dh, dh * sizeof(double));
         memcpy(s->V + ((size_t)h * s->cap + t) * dh, v + (size_t)h * dh, dh * sizeof(double));
         s->pos[(size_t)h * s->cap + t] = s->T;
+        s->A[(size_t)h * s->cap + t] = 0.0;
     }
     s->n = n;
     int fail = 0;
@@ -362,6 +390,9 @@ int oracle_commit(oracle_stream *s, const int32_t *I, int count)
         double *K = s->K + (size_t)h * s->cap * dh;
         double *V = s->V + (size_t)h * s->cap * dh;
         int64_t *pos = s->pos + (size_t)h * s->cap;
+        double *A = s->A + (size_t)h * s->cap;
+        const double *Wb = s->Wb + (size_t)h * s->cap;
+        const int c = s->n - s->R;
         for (int x = 0; x < count; ++x) {          /* ascending and I[x] >= x: a forward move is safe */
             const int src = Ih[x];
             if (src != x) {
@@ -369,11 +400,22 @@ int oracle_commit(oracle_stream *s, const int32_t *I, int count)
                 memmove(V + (size_t)x * dh, V + (size_t)src * dh, dh * sizeof(double));
                 pos[x] = pos[src];
             }
+            /* cumulative policy: a row that was ranked carries its new total, the others keep theirs */
+            if (s->policy == 3 && s->evict) A[x] = (src < c) ? Wb[src] : A[src];
+            else A[x] = A[src];
         }
     }
     s->t = count;
     s->pending = 0;
     return 0;
+}
+
+/* accumulated scores of the cached rows, [Hkv][t] (cumulative policy; all zero otherwise) */
+int oracle_accumulated(const oracle_stream *s, double *A)
+{
+    for (int h = 0; h < s->Hkv; ++h)
+        memcpy(A + (size_t)h * s->t, s->A + (size_t)h * s->cap, (size_t)s->t * sizeof(double));
+    return s->t;
 }
 
 /* copies the cache out: K, V are [Hkv][t][dh], pos is [Hkv][t]; any may be NULL */
@@ -400,6 +442,7 @@ int oracle_import(oracle_stream *s, const double *K, const double *V, const int6
         memcpy(s->K + (size_t)h * s->cap * dh, K + (size_t)h * len * dh, (size_t)len * dh * sizeof(double));
         memcpy(s->V + (size_t)h * s->cap * dh, V + (size_t)h * len * dh, (size_t)len * dh * sizeof(double));
         memcpy(s->pos + (size_t)h * s->cap, pos + (size_t)h * len, (size_t)len * sizeof(int64_t));
+        memset(s->A + (size_t)h * s->cap, 0, (size_t)len * sizeof(double));
     }
     s->t = len;
     s->T = streamed;
