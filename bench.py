@@ -54,12 +54,13 @@ def read_traffic(name):
     return None
 
 
-def cpu_baseline(cfg, budget_seconds=12.0):
+def cpu_baseline(cfg, budget_seconds=12.0, policy="infmllm"):
     """The oracle as it stands, timed on steady-state steps of the same workload."""
     import numpy as np
     import oracle
     from paper_2409_09086_amd.workloads import ChunkStream
-    orc = oracle.OracleStream(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, bias=cfg.bias)
+    orc = oracle.OracleStream(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, bias=cfg.bias,
+                              policy=policy)
     rng = np.random.default_rng(cfg.seed)
     K = rng.standard_normal((cfg.kv_heads, cfg.budget, cfg.head_dim)) * cfg.sigma
     V = rng.standard_normal((cfg.kv_heads, cfg.budget, cfg.head_dim)) * cfg.sigma
@@ -179,6 +180,8 @@ def main():
     ap.add_argument("--chunks", type=int, default=32, help="distinct chunks kept in HBM and cycled through")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--impl", type=int, default=None, help="debug: 1 = plain-arithmetic kernels")
+    ap.add_argument("--policy", default="infmllm", choices=["infmllm", "window", "initial_recent", "cumulative"],
+                    help="score the selection ranks (comparison policies); the default is the paper's method")
     ap.add_argument("--layers", type=int, default=16, help="streams in the layer-batched eviction leg (0 = skip)")
     ap.add_argument("--copy-calib", type=int, default=0, metavar="MIB",
                     help="also run an elementwise copy of this many MiB (reads MIB, writes MIB) three times, as "
@@ -213,7 +216,7 @@ def main():
     n_ret = torch.empty((1,), dtype=torch.int32, device=dev)
 
     s = binding.Stream(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, dtype=cfg.torch_dtype,
-                       bias=cfg.bias, max_chunk=cfg.max_chunk, impl=args.impl, device=dev)
+                       bias=cfg.bias, max_chunk=cfg.max_chunk, impl=args.impl, policy=args.policy, device=dev)
     lib = binding.lib()
     P = ctypes.c_void_p
     cargs = [(P(q.data_ptr()), P(k.data_ptr()), P(v.data_ptr())) for q, k, v in chunks]
@@ -291,7 +294,7 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": "%s: %d q-heads / %d kv-heads x %d, budget %d (recent %d), chunk %d, steady state n = %d"
                    % (cfg.name, cfg.heads, cfg.kv_heads, cfg.head_dim, cfg.budget, cfg.recent, L, cfg.budget + L),
-                   "bias": cfg.bias, "seed": cfg.seed, "chunks_in_hbm": nchunks,
+                   "bias": cfg.bias, "seed": cfg.seed, "chunks_in_hbm": nchunks, "policy": args.policy,
                    "kernels": "mfma" if mfma else "plain"},
         "roofline": roofline,
         "evict_roofline": evict,
@@ -303,7 +306,7 @@ def main():
         result["layer_batched"] = layer_batched_leg(cfg, binding, chunks, dev, args.impl, args.layers,
                                                     max(4, min(args.steps, 2000 // args.layers)))
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(cfg)
+        result["cpu_baseline"] = cpu_baseline(cfg, policy=args.policy)
     print(json.dumps(result))
 
 

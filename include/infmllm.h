@@ -55,6 +55,15 @@ enum {
     INFMLLM_PARAM_MAX_DECODE = 4,/* tokens that may be decoded (infmllm_decode) between two chunk
                                     steps; default 0.  The cache may then hold up to budget +
                                     max_decode rows and its capacity grows by as much              */
+    INFMLLM_PARAM_POLICY = 5,    /* which score the selection (Alg. 1 l.5) ranks; the methods Inf-MLLM is
+                                    compared with (Sec. 2, Sec. 4.1) as modes of the same kernels:
+                                    0 (default) W' = S + D of Alg. 1;
+                                    1 window: W'[j] = j, the cache is the newest `budget` tokens;
+                                    2 initial + recent: W'[j] = -j, the budget - recent oldest cached
+                                      tokens and the `recent` newest;
+                                    3 cumulative: W'[j] = A[j] + S[j], A = the W' a row was retained
+                                      with in earlier steps (0 if never ranked); b is not applied.
+                                    Modes 1 and 2 launch no scoring kernel                         */
     INFMLLM_PARAM_IMPL = 3       /* debug/test: 0 (default) = bf16 streams run attention and
                                     scoring on the matrix cores; 1 = every dtype runs the
                                     plain fp32-arithmetic kernels (fp32 streams always do)   */

@@ -134,6 +134,7 @@ int infmllm_stream_create(int budget, int recent, int heads, int kv_heads, int h
     s->g.elt = dtype == INFMLLM_BF16 ? 2 : 4;
     s->g.scale = (float)(1.0 / std::sqrt((double)head_dim));
     s->g.bias = 1e-4f;
+    s->g.policy = POLICY_INFMLLM;
     s->dtype = dtype; s->impl = 0; s->attached = false; s->st = nullptr; s->cur = 0; s->len = 0;
     s->streamed = 0; s->last_cnd = 0; s->lse = nullptr; s->Wb = nullptr; s->I = nullptr;
     *out = s;
@@ -172,6 +173,11 @@ int infmllm_stream_set_param(infmllm_stream_t* s, int which, double value)
                 return fail(INFMLLM_EINVAL, "set_param: max_decode must be an integer in 0..2^24");
             s->g.max_decode = (int)value;
             s->g.cap = s->g.B + s->g.max_decode + s->g.max_chunk;
+            return INFMLLM_OK;
+        case INFMLLM_PARAM_POLICY:
+            if (value != 0 && value != 1 && value != 2 && value != 3)
+                return fail(INFMLLM_EINVAL, "set_param: policy must be 0, 1, 2 or 3");
+            s->g.policy = (int)value;
             return INFMLLM_OK;
         case INFMLLM_PARAM_IMPL:
             if (value != 0 && value != 1) return fail(INFMLLM_EINVAL, "set_param: impl must be 0 or 1");
@@ -278,8 +284,11 @@ int step_front(infmllm_stream* s, const void* q, const void* k, const void* v, i
         return INFMLLM_OK;
     }
     s->mark(INFMLLM_K_SCORE, 0);
-    e = mfma ? launch_score_mfma(g, cur, ks, q, s->lse, s->fwd, nsplit, t, L, s->Wb, s->st)
-             : launch_score_simple(g, cur, q, s->lse, t, L, s->Wb, s->st);
+    if (g.policy == POLICY_WINDOW || g.policy == POLICY_INITIAL_RECENT)
+        e = launch_rank_scores(g, s->Wb, n - g.R, g.policy == POLICY_WINDOW ? 1.f : -1.f, s->st);
+    else
+        e = mfma ? launch_score_mfma(g, cur, ks, q, s->lse, s->fwd, nsplit, t, L, s->Wb, s->st)
+                 : launch_score_simple(g, cur, q, s->lse, t, L, s->Wb, s->st);
     if (e != hipSuccess) return fail_hip(e, "score");
     s->mark(INFMLLM_K_SCORE, 1);
     return INFMLLM_OK;

@@ -380,7 +380,7 @@ template <int D, int CB>
 __global__ void __launch_bounds__(512)
 score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ kc, int tc,
              const float* __restrict__ lse2, const float* __restrict__ part_ml, int nsplit,
-             float* __restrict__ Wb, int L, int lq, int Hq, int Hkv, int G, int cap, int max_chunk, int cnd,
+             const float* __restrict__ carry, float* __restrict__ Wb, int L, int lq, int Hq, int Hkv, int G, int cap, int max_chunk, int cnd,
              int nxb, float c, float bias)
 {
     constexpr int QP = D * 2 + 16;                            // pitch of a staged query row
@@ -553,7 +553,14 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
             const int col = col0 + 32 * cb + l32;
             if (col < cnd) {
                 const float tot = sum[cb] + s_part[(cg * CB + cb) * 32 + l32];
-                Wb[(size_t)h * cap + col] = tot * norm - (float)(cnd - 1 - col) * dstep;   // Alg. 1 l.1, l.3-4
+                float w = tot * norm - (float)(cnd - 1 - col) * dstep;                     // Alg. 1 l.1, l.3-4
+                if (carry) {
+                    // cumulative policy: this step's S on top of what the row has gathered, no bias; the
+                    // chunk's own rows (read in place, col >= tc) and rows never ranked (+inf) carry nothing
+                    const float a = col < tc ? carry[(size_t)h * cap + col] : 0.f;
+                    w = tot * norm + (a < __builtin_inff() ? a : 0.f);
+                }
+                Wb[(size_t)h * cap + col] = w;
             }
         }
     }
@@ -660,7 +667,8 @@ hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySou
     const dim3 grid(nxb * g.Hkv), block(512);
 #define INFMLLM_SCORE(DD, CB)                                                                              \
     hipLaunchKernelGGL((score_kernel<DD, CB>), grid, block, 0, st, (const uint16_t*)q, (const uint16_t*)c.K, \
-                       (const uint16_t*)ks.k, ks.rows, lse, sc.part_ml, nsplit, Wb, L, lq, g.Hq, g.Hkv, g.G, g.cap, \
+                       (const uint16_t*)ks.k, ks.rows, lse, sc.part_ml, nsplit,                              \
+                       g.policy == POLICY_CUMULATIVE ? c.score : nullptr, Wb, L, lq, g.Hq, g.Hkv, g.G, g.cap, \
                        g.max_chunk,                                                                          \
                        cnd, nxb, cc, g.bias)
     if (g.d == 128 && wide) INFMLLM_SCORE(128, 2);

@@ -118,8 +118,8 @@ attn_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const T* __
 template <typename T, int D>
 __global__ void __launch_bounds__(128)
 score_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const float* __restrict__ lse,
-                    float* __restrict__ Wb, int L, int lq, int Hq, int G, int cap, int max_chunk, int cnd,
-                    float scale, float bias)
+                    const float* __restrict__ carry, float* __restrict__ Wb, int L, int lq, int Hq, int G, int cap,
+                    int max_chunk, int cnd, float scale, float bias)
 {
     constexpr int RT = 16;                       // query rows staged per round
     __shared__ float qs[RT][D];
@@ -157,7 +157,12 @@ score_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const floa
     if (live) {
         const float S = (lq > 0) ? acc / (float)(G * lq) : 0.f;        // Alg. 1 l.1, pooled over the group
         const float dstep = bias / (float)cnd;                         // Alg. 1 l.2
-        Wb[(size_t)h * cap + j] = S - (float)(cnd - 1 - j) * dstep;    // Alg. 1 l.3-4
+        float w = S - (float)(cnd - 1 - j) * dstep;                    // Alg. 1 l.3-4
+        if (carry) {                                                   // cumulative policy: total so far, no bias
+            const float a = carry[(size_t)h * cap + j];
+            w = S + (a < __builtin_inff() ? a : 0.f);                  // +inf marks a row never ranked
+        }
+        Wb[(size_t)h * cap + j] = w;
     }
 }
 
@@ -196,7 +201,8 @@ hipError_t launch_score_simple(const Geometry& g, const CacheView& c, const void
     const dim3 grid((cnd + 127) / 128, g.Hkv), block(128);
 #define INFMLLM_SCORE(TT, DD)                                                                           \
     hipLaunchKernelGGL((score_simple_kernel<TT, DD>), grid, block, 0, st, (const TT*)q, (const TT*)c.K, \
-                       lse, Wb, L, lq, g.Hq, g.G, g.cap, g.max_chunk, cnd, g.scale, g.bias)
+                       lse, g.policy == POLICY_CUMULATIVE ? c.score : nullptr, Wb, L, lq, g.Hq, g.G, g.cap,     \
+                       g.max_chunk, cnd, g.scale, g.bias)
     if (g.elt == 4 && g.d == 64) INFMLLM_SCORE(float, 64);
     else if (g.elt == 4 && g.d == 128) INFMLLM_SCORE(float, 128);
     else if (g.elt == 2 && g.d == 64) INFMLLM_SCORE(uint16_t, 64);

@@ -45,6 +45,16 @@ iota_kernel(int32_t* __restrict__ I, int32_t* __restrict__ count, int n, int Hkv
 }
 
 __global__ void __launch_bounds__(256)
+rank_score_kernel(float* __restrict__ Wb, int cnd, int Hkv, int cap, float sign)
+{
+    const int total = cnd * Hkv;
+    for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += gridDim.x * blockDim.x) {
+        const int h = idx / cnd, j = idx - h * cnd;
+        Wb[(long)h * cap + j] = sign * (float)j;
+    }
+}
+
+__global__ void __launch_bounds__(256)
 fill_inf_kernel(float* __restrict__ score, int len, int Hkv, int cap)
 {
     const int total = len * Hkv;
@@ -143,6 +153,15 @@ hipError_t launch_iota(const Geometry& g, int n, int32_t* user_I, int32_t* user_
     int blocks = (n * g.Hkv + 255) / 256;
     if (blocks > 1024) blocks = 1024;
     hipLaunchKernelGGL(iota_kernel, dim3(blocks), dim3(256), 0, st, user_I, user_count, n, g.Hkv, g.B);
+    return hipGetLastError();
+}
+
+hipError_t launch_rank_scores(const Geometry& g, float* Wb, int cnd, float sign, hipStream_t st)
+{
+    if (cnd <= 0) return hipSuccess;
+    int blocks = (cnd * g.Hkv + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(rank_score_kernel, dim3(blocks), dim3(256), 0, st, Wb, cnd, g.Hkv, g.cap, sign);
     return hipGetLastError();
 }
 

@@ -25,7 +25,9 @@ struct Geometry {
     int elt;      // bytes per element (2 = bf16, 4 = fp32)
     float scale;  // softmax scale
     float bias;   // b of Alg. 1
+    int policy;   // score ranked by the selection: 0 Alg. 1, 1 window, 2 initial + recent, 3 cumulative
 };
+enum { POLICY_INFMLLM = 0, POLICY_WINDOW = 1, POLICY_INITIAL_RECENT = 2, POLICY_CUMULATIVE = 3 };
 
 // One side of the double-buffered cache.
 struct CacheView {
@@ -44,6 +46,8 @@ hipError_t launch_attn_simple(const Geometry& g, const CacheView& c, const void*
                               void* out, float* lse, hipStream_t st);
 
 // a3+a4 (plain fp32 arithmetic, any dtype): W'[h][j] for j < cnd = n - R.
+// With g.policy == POLICY_CUMULATIVE the score is S plus the score the row carries in c.score
+// (a row never ranked carries +inf there and counts as 0) and no bias is applied.
 hipError_t launch_score_simple(const Geometry& g, const CacheView& c, const void* q, const float* lse,
                                int t, int L, float* Wb, hipStream_t st);
 
@@ -112,6 +116,10 @@ struct EvictBatch {
 };
 hipError_t launch_select_batch(const Geometry& g, const EvictBatch& eb, hipStream_t st);
 hipError_t launch_compact_batch(const Geometry& g, const EvictBatch& eb, hipStream_t st);
+
+// Comparison policies that rank by age: W'[h][j] = sign * j for j < cnd (sign +1 keeps the newest,
+// -1 the oldest).
+hipError_t launch_rank_scores(const Geometry& g, float* Wb, int cnd, float sign, hipStream_t st);
 
 // warm-up: I[h][j] = j for j < n.
 hipError_t launch_iota(const Geometry& g, int n, int32_t* user_I, int32_t* user_count, hipStream_t st);
