@@ -385,15 +385,17 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
 {
     constexpr int QP = D * 2 + 16;                            // pitch of a staged query row
     constexpr int CPR = D / 8;
-    constexpr int NLD = 64 * CPR / 512;                       // 16-byte chunks per thread per pair of blocks
-    constexpr int QBYTES = 64 * QP;
-    constexpr int BUF = QBYTES + 64 * 4;                      // rows + their log-sum-exp
+    constexpr int TROWS = 128;                                // rows staged per iteration: four 32-row blocks
+    constexpr int NLD = TROWS * CPR / 512;                    // 16-byte chunks per thread per iteration
+    constexpr int QBYTES = TROWS * QP;
+    constexpr int BUF = QBYTES + TROWS * 4;                   // rows + their log-sum-exp
     constexpr int LSE_ROWS = 4096;                            // scored rows whose log-sum-exp is kept in LDS
     __shared__ __attribute__((aligned(16))) char smem[2 * BUF];
     __shared__ float s_part[4 * CB * 32];
     __shared__ float s_lse[LSE_ROWS];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: what depends on it stays scalar
     const int cg = wave & 3, rg = wave >> 2;                  // column group, row group
     // all column blocks of a kv-head get workgroup ids of one residue class mod 8, i.e. one XCD,
     // so that the head's scored queries are fetched into one L2 only
@@ -411,21 +413,6 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
     }
     const int col0 = bx * (128 * CB) + cg * (32 * CB);
 
-    // key fragments: B operand of S = Q.K^T, lane (column l32, half hh) holds K[col][16s + 8hh .. +8)
-    bf16x8 kf[CB][D / 16];
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb) {
-        const int col = col0 + 32 * cb + l32;
-        const bool ok = col < cnd;
-        const int cc = ok ? col : 0;
-        const uint16_t* kp = (cc < tc ? K + ((size_t)h * cap + cc) * D : kc + ((size_t)(cc - tc) * Hkv + h) * D) + 8 * hh;
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-            u32x4 v = *(const u32x4*)(kp + 16 * s);
-            if (!ok) v = u32x4{0u, 0u, 0u, 0u};
-            kf[cb][s] = as_bf16x8(v);
-        }
-    }
     f32x16 part[CB];
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
@@ -433,8 +420,8 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
         for (int i = 0; i < 16; ++i) part[cb][i] = 0.f;
 
     const int nblk = (lq + 31) / 32;                          // 32-row blocks per query head
-    const int total = G * nblk;                               // blocks to sweep, two per iteration
-    const int niter = (total + 1) / 2;
+    const int total = G * nblk;                               // blocks to sweep, four per iteration
+    const int niter = (total + 3) / 4;
     // Row log-sum-exp of every scored row of the group, once per workgroup: row (gg, i) -> s_lse[gg*lq + i].
     // After a key-split attention launch it is derived from the partials: max m + log2(sum_s l_s 2^(m_s - max m)).
     auto row_lse = [&](int g, int i) -> float {
@@ -452,37 +439,49 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
     if (lse_in_lds)
         for (int x = tid; x < G * lq; x += 512) s_lse[x] = row_lse(h * G + x / lq, L - lq + x % lq);
 
+    // Staging of the next four blocks.  Chunk u of a thread is row rr[u] of block slot sl[u] (the slot is
+    // uniform over a wavefront), so the block's address is scalar and only toff[u] is per lane.
     u32x4 st[NLD];
     float stl = 0.f;                                          // log-sum-exp of the staged row, or ...
     int stl_idx = -1;                                         // ... its index in s_lse (looked up when it is staged)
-    // (head, block-in-head) of the next pair of blocks to fetch: kept as running scalars so that
-    // the fetch needs no per-thread division
-    int fg = 0, fb = 0;
-    auto fetch = [&](int it) {
-        const int gA = fg, bA = fb;
-        int gB = fg, bB = fb + 1;
-        if (bB >= nblk) { bB = 0; ++gB; }
-        fb = bB + 1; fg = gB;
-        if (fb >= nblk) { fb = 0; ++fg; }
-        const bool okB = 2 * it + 1 < total;
+    int sl[NLD], rr[NLD];
+    uint32_t toff[NLD];
+#pragma unroll
+    for (int u = 0; u < NLD; ++u) {
+        const int ch = tid + u * 512, r = ch / CPR;           // r in 0..127
+        sl[u] = __builtin_amdgcn_readfirstlane(r >> 5);
+        rr[u] = r & 31;
+        toff[u] = (uint32_t)(rr[u] * Hq * D + (ch % CPR) * 8);
+    }
+    int fg = 0, fb = 0;                                       // (head in group, block in head) of the next block
+    auto fetch = [&]() {
+        int gk[4], bk[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {                         // past the last block: fg == G
+            gk[k] = fg; bk[k] = fb;
+            if (fg < G && ++fb >= nblk) { fb = 0; ++fg; }
+        }
 #pragma unroll
         for (int u = 0; u < NLD; ++u) {
-            const int ch = tid + u * 512, r = ch / CPR, cc = ch % CPR;        // r in 0..63
-            const bool second = r >= 32;
-            const int g = h * G + (second ? gB : gA), i = L - lq + 32 * (second ? bB : bA) + (r & 31);
+            const int g1 = gk[sl[u]], b1 = bk[sl[u]];
+            const int i0 = L - lq + 32 * b1;
             u32x4 v = {0u, 0u, 0u, 0u};
-            if ((!second || okB) && i < L) v = *(const u32x4*)(q + ((size_t)i * Hq + g) * D + cc * 8);
+            if (g1 < G) {
+                const uint16_t* base = q + ((size_t)i0 * Hq + h * G + g1) * D;
+                if (i0 + rr[u] < L) v = *(const u32x4*)(base + toff[u]);
+            }
             st[u] = v;
         }
-        if (tid < 64) {
-            const bool second = tid >= 32;
-            const int i = L - lq + 32 * (second ? bB : bA) + (tid & 31);
+        if (tid < TROWS) {
+            const int k = tid >> 5;                           // block slot of the row whose lse this thread stages
+            const int g1 = k == 0 ? gk[0] : k == 1 ? gk[1] : k == 2 ? gk[2] : gk[3];
+            const int b1 = k == 0 ? bk[0] : k == 1 ? bk[1] : k == 2 ? bk[2] : bk[3];
+            const int i = L - lq + 32 * b1 + (tid & 31);
             stl = __builtin_inff();                           // +inf: weight 0
             stl_idx = -1;
-            if ((!second || okB) && i < L) {
-                const int gg = second ? gB : gA;
-                if (lse_in_lds) stl_idx = gg * lq + (i - (L - lq));
-                else stl = row_lse(h * G + gg, i);
+            if (g1 < G && i < L) {
+                if (lse_in_lds) stl_idx = g1 * lq + (i - (L - lq));
+                else stl = row_lse(h * G + g1, i);
             }
         }
     };
@@ -490,48 +489,73 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
         char* base = smem + buf * BUF;
 #pragma unroll
         for (int u = 0; u < NLD; ++u) {
-            const int ch = tid + u * 512, r = ch / CPR, cc = ch % CPR;
-            *(u32x4*)(base + r * QP + cc * 16) = st[u];
+            const int ch = tid + u * 512;
+            *(u32x4*)(base + (ch / CPR) * QP + (ch % CPR) * 16) = st[u];
         }
-        if (tid < 64) *(float*)(base + QBYTES + tid * 4) = (stl_idx >= 0) ? s_lse[stl_idx] : stl;
+        if (tid < TROWS) *(float*)(base + QBYTES + tid * 4) = (stl_idx >= 0) ? s_lse[stl_idx] : stl;
     };
-    if (niter > 0) fetch(0);                                  // in flight while s_lse is being completed
+    if (niter > 0) fetch();
+    // The key fragments are requested last: loads return in order, so the small loads above (log-sum-exp,
+    // first query rows) can be waited for and staged while the 64 KB of keys are still on their way.
+    // key fragments: B operand of S = Q.K^T, lane (column l32, half hh) holds K[col][16s + 8hh .. +8)
+    bf16x8 kf[CB][D / 16];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+        const int col = col0 + 32 * cb + l32;
+        const bool ok = col < cnd;
+        const int cc = ok ? col : 0;
+        const uint16_t* kp = (cc < tc ? K + ((size_t)h * cap + cc) * D : kc + ((size_t)(cc - tc) * Hkv + h) * D) + 8 * hh;
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+            u32x4 v = *(const u32x4*)(kp + 16 * s);
+            if (!ok) v = u32x4{0u, 0u, 0u, 0u};
+            kf[cb][s] = as_bf16x8(v);
+        }
+    }
     __syncthreads();                                          // s_lse is complete
     if (niter > 0) {
         stash(0);
-        if (niter > 1) fetch(1);
+        if (niter > 1) fetch();
     }
     __syncthreads();
     for (int it = 0; it < niter; ++it) {
         const char* base = smem + (it & 1) * BUF;
-        const char* qp = base + (32 * rg + l32) * QP + 16 * hh;
-        const float* sl = (const float*)(base + QBYTES) + 32 * rg;
-        f32x16 acc[CB];
+        // a row group takes two of the four blocks; the MFMAs of the second run under the exponentials of
+        // the first
+        f32x16 acc[2][CB];
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
-        bf16x8 qf[D / 16];
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) qf[s] = as_bf16x8(*(const u32x4*)(qp + 32 * s));
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s)
+        for (int k = 0; k < 2; ++k) {
+            const char* qp = base + (64 * rg + 32 * k + l32) * QP + 16 * hh;
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
-                acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[s], kf[cb][s], acc[cb], 0, 0, 0);
-        // lane (column, half hh) holds rows 8a + 4hh + e of the block in register 4a + e
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            const f32x4 ls = *(const f32x4*)(sl + 8 * a + 4 * hh);
+                for (int i = 0; i < 16; ++i) acc[k][cb][i] = 0.f;
+            bf16x8 qf[D / 16];
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
+            for (int s = 0; s < D / 16; ++s) qf[s] = as_bf16x8(*(const u32x4*)(qp + 32 * s));
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s)
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb)
-                    part[cb][4 * a + e] += fast_exp2(__builtin_fmaf(acc[cb][4 * a + e], c, -ls[e]));
+                    acc[k][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[s], kf[cb][s], acc[k][cb], 0, 0, 0);
+        }
+        // lane (column, half hh) holds rows 8a + 4hh + e of a block in register 4a + e
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const float* lp = (const float*)(base + QBYTES) + 64 * rg + 32 * k;
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const f32x4 ls = *(const f32x4*)(lp + 8 * a + 4 * hh);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb)
+                        part[cb][4 * a + e] += fast_exp2(__builtin_fmaf(acc[k][cb][4 * a + e], c, -ls[e]));
+            }
         }
         // the other buffer was last read one iteration ago, before the barrier that ended it
         if (it + 1 < niter) stash((it + 1) & 1);
-        if (it + 2 < niter) fetch(it + 2);
+        if (it + 2 < niter) fetch();
         __syncthreads();
     }
     // column sums: 16 registers, the two half-waves, then the two row groups (fixed order)
