@@ -51,14 +51,17 @@ struct FwdCfg {
     static constexpr int KBYTES = TILE * KP, VBYTES = TILE * VP, BUF = KBYTES + VBYTES;
     static constexpr int NBUF = (2 * BUF <= 160 * 1024) ? 2 : 1;
     static constexpr int OREG = D / 2;                 // fp32 accumulators of O^T per lane
-    static constexpr int MERGE = (KW - 1) * RB * 64 * (OREG + 2) * 4;
+    static constexpr int MERGE = (KW > 1 ? KW : 0) * RB * 64 * (OREG + 2) * 4;
     static constexpr int LDS = (NBUF * BUF) > MERGE ? (NBUF * BUF) : MERGE;
     static_assert(TILE * CPR % NT == 0 && NT % CPR == 0, "tile must split evenly over the threads");
     static_assert(TILE <= FWD_MAX_TILE, "workspace padding assumes smaller tiles");
 };
 
-// Tail shared by the attention kernels: merge the key ways of a query block through LDS, then
-// normalise and store (or store the un-normalised partial of a key split).
+// Tail of the attention kernel: merge the key ways of a query block through LDS, then normalise and
+// store (or store the un-normalised partial of a key split).  Every wavefront leaves its (m, l, O) in
+// LDS; the KW wavefronts of a query block then each merge and store their own D / KW output columns,
+// so the tail's LDS reads, arithmetic and stores are spread over the whole workgroup.
+// Lane (row l32, half hh) holds O[row][32b + 8(i/4) + 4hh + i%4] in o[b][i].
 template <int D, int RB, int KW>
 __device__ __forceinline__ void fwd_finish(char* smem, bool sync_first, f32x16 (&o)[D / 32], float m_ref, float lsum,
                                            int rb, int kw, int lane, int hh, int my_row, int g, int sp, int L, int Hq,
@@ -66,72 +69,85 @@ __device__ __forceinline__ void fwd_finish(char* smem, bool sync_first, f32x16 (
                                            float* __restrict__ part_ml, uint16_t* __restrict__ out,
                                            float* __restrict__ lse2)
 {
-    constexpr int OREG = D / 2;
-    // ---- merge the key ways of a query block ---------------------------------------------------
+    constexpr int OREG = D / 2, NB = D / 32;
+    static_assert(NB % KW == 0, "the output column blocks must split evenly over the key ways");
+    constexpr int BPW = NB / KW;                              // column blocks stored by one wavefront
+    float a[KW];
+    const float* slot[KW];
     if (KW > 1) {
         if (sync_first) __syncthreads();
         float* mg = (float*)smem;
-        if (kw > 0) {
-            float* w = mg + (size_t)((kw - 1) * RB + rb) * 64 * (OREG + 2);
-            w[lane] = m_ref;
-            w[64 + lane] = lsum;
+        float* w = mg + (size_t)(kw * RB + rb) * 64 * (OREG + 2);
+        w[lane] = m_ref;
+        w[64 + lane] = lsum;
 #pragma unroll
-            for (int b = 0; b < D / 32; ++b)
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) w[(2 + b * 16 + i) * 64 + lane] = o[b][i];
-        }
+            for (int i = 0; i < 16; ++i) w[(2 + b * 16 + i) * 64 + lane] = o[b][i];
         __syncthreads();
-        if (kw == 0) {
-            for (int k2 = 1; k2 < KW; ++k2) {
-                const float* w = mg + (size_t)((k2 - 1) * RB + rb) * 64 * (OREG + 2);
-                const float m2 = w[lane], l2 = w[64 + lane];
-                const float mt = fmaxf(m_ref, m2);
-                const float mu = (mt == -__builtin_inff()) ? 0.f : mt;
-                const float a1 = fast_exp2(m_ref - mu), a2 = fast_exp2(m2 - mu);
-                lsum = lsum * a1 + l2 * a2;
+        if (my_row >= L) return;
+        float mk[KW], mt = -__builtin_inff();
 #pragma unroll
-                for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) o[b][i] = o[b][i] * a1 + w[(2 + b * 16 + i) * 64 + lane] * a2;
-                m_ref = mt;
-            }
+        for (int k = 0; k < KW; ++k) {
+            slot[k] = mg + (size_t)(k * RB + rb) * 64 * (OREG + 2);
+            mk[k] = slot[k][lane];
+            mt = fmaxf(mt, mk[k]);
         }
+        const float mu = (mt == -__builtin_inff()) ? 0.f : mt;
+        lsum = 0.f;
+#pragma unroll
+        for (int k = 0; k < KW; ++k) {
+            a[k] = fast_exp2(mk[k] - mu);                     // a way that saw no key has m = -inf, weight 0
+            lsum += slot[k][64 + lane] * a[k];
+        }
+        m_ref = mt;
+    } else {
+        if (my_row >= L) return;
     }
-    if (kw != 0 || my_row >= L) return;
-
-    // ---- normalise and store: lane (row l32, half hh) holds O[row][32b + 8(i/4) + 4hh + i%4] -----
     const float ltot = lsum + xhalf(lsum);
-    if (nsplit > 1) {
-        // un-normalised partial of this key split: [split][row][head][D] fp32, (m, l) beside it
-        const size_t rowi = ((size_t)sp * L + my_row) * Hq + g;
-        float* pp = part_o + rowi * D;
-#pragma unroll
-        for (int b = 0; b < D / 32; ++b)
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                f32x4 w;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = o[b][4 * a + e];
-                *(f32x4*)(pp + 32 * b + 8 * a + 4 * hh) = w;
-            }
-        if (hh == 0) {
-            part_ml[rowi * 2] = m_ref;
-            part_ml[rowi * 2 + 1] = ltot;
-        }
-        return;
-    }
     const float inv = 1.0f / ltot;
+    const size_t rowi = ((size_t)sp * L + my_row) * Hq + g;   // row of the key-split partials
     uint16_t* op = out + ((size_t)my_row * Hq + g) * D;
 #pragma unroll
-    for (int b = 0; b < D / 32; ++b)
+    for (int bb = 0; bb < BPW; ++bb) {
+        const int b = kw * BPW + bb;
+        float v[16];
+        if (KW > 1) {
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            bf16x4 w;
+            for (int i = 0; i < 16; ++i) {
+                float t = 0.f;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[b][4 * a + e] * inv);
-            *(bf16x4*)(op + 32 * b + 8 * a + 4 * hh) = w;
+                for (int k = 0; k < KW; ++k) t += a[k] * slot[k][(2 + b * 16 + i) * 64 + lane];
+                v[i] = t;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[i] = o[bb][i];
         }
-    if (hh == 0) lse2[(size_t)g * max_chunk + my_row] = m_ref + __builtin_log2f(ltot);
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            if (nsplit > 1) {
+                // un-normalised partial of this key split: [split][row][head][D] fp32, (m, l) beside it
+                f32x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = v[4 * q4 + e];
+                *(f32x4*)(part_o + rowi * D + 32 * b + 8 * q4 + 4 * hh) = w;
+            } else {
+                bf16x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = (__bf16)(v[4 * q4 + e] * inv);
+                *(bf16x4*)(op + 32 * b + 8 * q4 + 4 * hh) = w;
+            }
+        }
+    }
+    if (kw == 0 && hh == 0) {
+        if (nsplit > 1) {
+            part_ml[rowi * 2] = m_ref;
+            part_ml[rowi * 2 + 1] = ltot;
+        } else {
+            lse2[(size_t)g * max_chunk + my_row] = m_ref + __builtin_log2f(ltot);
+        }
+    }
 }
 
 template <int D, int RB, int KW, int KVB>
