@@ -48,6 +48,7 @@ def _load():
             lib.oracle_decode.argtypes = [P, P, P, P, P]
             lib.oracle_candidates.argtypes = [P]
             lib.oracle_set_policy.argtypes = [P, ctypes.c_int]
+            lib.oracle_set_rope.argtypes = [P, ctypes.c_double, ctypes.c_int]
             lib.oracle_accumulated.argtypes = [P, P]
             lib.oracle_scores.argtypes = [P, P, P]
             lib.oracle_select.argtypes = [P, P]
@@ -80,7 +81,10 @@ class OracleStream:
 
     POLICIES = {"infmllm": 0, "window": 1, "initial_recent": 2, "cumulative": 3}
 
-    def __init__(self, budget, recent, heads, kv_heads, head_dim, bias=1e-4, scale=None, policy="infmllm"):
+    ROUND = {None: 0, "bf16": 1, "fp32": 2}
+
+    def __init__(self, budget, recent, heads, kv_heads, head_dim, bias=1e-4, scale=None, policy="infmllm",
+                 rope_base=0.0, rope_round=None):
         lib = _load()
         if scale is None:
             scale = 1.0 / np.sqrt(head_dim)
@@ -92,6 +96,8 @@ class OracleStream:
         self.policy = policy
         if lib.oracle_set_policy(self._h, self.POLICIES[policy]) != 0:
             raise ValueError("oracle_set_policy failed")
+        if lib.oracle_set_rope(self._h, float(rope_base), self.ROUND[rope_round]) != 0:
+            raise ValueError("oracle_set_rope failed")
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None

@@ -47,6 +47,17 @@
  *   plain statements of "keep recent", "keep initial and recent" and "keep the heaviest by
  *   accumulated attention" inside this step's (r, R) frame.
  *
+ * Cache-relative position encoding (Sec. 3.4 "length extrapolation", Sec. 4.1: the models use
+ * rotary position embeddings), selectable with oracle_set_rope; off by default:
+ *   Reading: the paper states no formula.  Taken here: keys and values are cached as given
+ *   (unrotated); whenever attention is computed, the key in cache row j is rotated by the angle
+ *   of position j and the query of chunk row i by that of position t + i (the row its own key
+ *   occupies), so that relative distances are distances inside the cache and never exceed its
+ *   size.  Rotation: pairs (x[i], x[i + d/2]), angle p * base^(-2i/d), i < d/2 (the half-split
+ *   form of rotary embeddings).  The rotated values are rounded to the stream's element type
+ *   (bf16 or fp32) before the dot products, because that is the precision in which the HIP
+ *   path hands them to its attention kernels and the rounding decides retained sets.
+ *
  * All arithmetic is IEEE double.  Inputs are taken as exact values (a bf16 or fp32
  * input converts to double without rounding).
  *
@@ -92,6 +103,8 @@ typedef struct oracle_stream {
     double *S;    /* [Hkv][cap] column mean, first c = n - R entries used */
     double *Wb;   /* [Hkv][cap] biased score                              */
     int policy;   /* 0 Alg. 1, 1 window, 2 initial + recent, 3 cumulative */
+    double rope_base;   /* 0 = no position encoding                        */
+    int rope_round;     /* rotated values rounded to: 0 nothing, 1 bf16, 2 fp32 */
     double *A;    /* [Hkv][cap] accumulated score of each cached row      */
 } oracle_stream;
 
@@ -151,6 +164,40 @@ int oracle_set_policy(oracle_stream *s, int policy)
     return 0;
 }
 
+/* cache-relative rotary encoding (see the header); round_to: 0 none, 1 bf16, 2 fp32; only between steps */
+int oracle_set_rope(oracle_stream *s, double base, int round_to)
+{
+    if (!s || s->pending || !(base == 0.0 || base > 1.0) || round_to < 0 || round_to > 2 || (s->dh & 1)) return -1;
+    s->rope_base = base;
+    s->rope_round = round_to;
+    return 0;
+}
+
+static double round_to_type(double v, int round_to)
+{
+    if (round_to == 0) return v;
+    float f = (float)v;                            /* IEEE round to nearest even */
+    if (round_to == 2) return (double)f;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u += 0x7fffu + ((u >> 16) & 1u);               /* bf16: nearest even on the upper 16 bits */
+    u &= 0xffff0000u;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+/* y = x rotated to position p: (x[i], x[i + d/2]) turned by p * base^(-2i/d), then rounded */
+static void rotate_row(const oracle_stream *s, const double *x, int p, double *y)
+{
+    const int half = s->dh / 2;
+    for (int i = 0; i < half; ++i) {
+        const double ang = (double)p * pow(s->rope_base, -2.0 * (double)i / (double)s->dh);
+        const double c = cos(ang), sn = sin(ang);
+        y[i] = round_to_type(x[i] * c - x[i + half] * sn, s->rope_round);
+        y[i + half] = round_to_type(x[i + half] * c + x[i] * sn, s->rope_round);
+    }
+}
+
 int oracle_len(const oracle_stream *s) { return s->t; }
 int64_t oracle_streamed(const oracle_stream *s) { return s->T; }
 
@@ -167,8 +214,16 @@ static void attention_one_head(const oracle_stream *s, int g, const double *q, i
     const int h = g / (s->Hq / s->Hkv);
     const double *K = s->K + (size_t)h * s->cap * dh;
     const double *V = s->V + (size_t)h * s->cap * dh;
+    double *Kr = NULL, *qr = NULL;                 /* rotated copies when the position encoding is on */
+    if (s->rope_base > 0.0) {
+        Kr = (double *)malloc((size_t)n * dh * sizeof(double));
+        qr = (double *)malloc((size_t)dh * sizeof(double));
+        for (int j = 0; j < n; ++j) rotate_row(s, K + (size_t)j * dh, j, Kr + (size_t)j * dh);
+        K = Kr;
+    }
     for (int i = 0; i < L; ++i) {
         const double *qi = q + ((size_t)i * s->Hq + g) * dh;
+        if (qr) { rotate_row(s, qi, t + i, qr); qi = qr; }
         double *Wi = W + (size_t)i * n;
         const int vis = t + i + 1;                 /* visible columns 0 .. t+i */
         double mx = -INFINITY;
@@ -191,6 +246,8 @@ static void attention_one_head(const oracle_stream *s, int g, const double *q, i
             for (int x = 0; x < dh; ++x) oi[x] += w * vj[x];
         }
     }
+    free(Kr);
+    free(qr);
 }
 
 /*
