@@ -167,7 +167,8 @@ int oracle_set_policy(oracle_stream *s, int policy)
 /* cache-relative rotary encoding (see the header); round_to: 0 none, 1 bf16, 2 fp32; only between steps */
 int oracle_set_rope(oracle_stream *s, double base, int round_to)
 {
-    if (!s || s->pending || !(base == 0.0 || base > 1.0) || round_to < 0 || round_to > 2 || (s->dh & 1)) return -1;
+    if (!s || s->pending || !(base == 0.0 || base > 1.0) || round_to < 0 || round_to > 2) return -1;
+    if (base > 0.0 && (s->dh & 1)) return -1;     /* the rotation pairs x[i] with x[i + d/2] */
     s->rope_base = base;
     s->rope_round = round_to;
     return 0;
