@@ -39,6 +39,8 @@ def algorithmic_work(cfg, L, t):
         # the select launch also moves the R recent rows (always kept) on workgroups of its own
         "select": {"bytes": 4 * c * Hkv + 4 * B * Hkv + row * R * Hkv},
         "compact": {"bytes": row * r * Hkv},
+        # position-encoding pre-pass: every cached key, the chunk's keys and the queries read and written once
+        "rope": {"bytes": 2 * elt * d * (n * Hkv + L * Hq)},
     }
 
 
@@ -54,13 +56,13 @@ def read_traffic(name):
     return None
 
 
-def cpu_baseline(cfg, budget_seconds=12.0, policy="infmllm"):
+def cpu_baseline(cfg, budget_seconds=12.0, policy="infmllm", rope_base=0.0):
     """The oracle as it stands, timed on steady-state steps of the same workload."""
     import numpy as np
     import oracle
     from paper_2409_09086_amd.workloads import ChunkStream
     orc = oracle.OracleStream(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, bias=cfg.bias,
-                              policy=policy)
+                              policy=policy, rope_base=rope_base, rope_round=cfg.dtype if rope_base else None)
     rng = np.random.default_rng(cfg.seed)
     K = rng.standard_normal((cfg.kv_heads, cfg.budget, cfg.head_dim)) * cfg.sigma
     V = rng.standard_normal((cfg.kv_heads, cfg.budget, cfg.head_dim)) * cfg.sigma
@@ -182,6 +184,8 @@ def main():
     ap.add_argument("--impl", type=int, default=None, help="debug: 1 = plain-arithmetic kernels")
     ap.add_argument("--policy", default="infmllm", choices=["infmllm", "window", "initial_recent", "cumulative"],
                     help="score the selection ranks (comparison policies); the default is the paper's method")
+    ap.add_argument("--rope", type=float, default=0.0, metavar="BASE",
+                    help="cache-relative rotary position encoding with this base (0 = off, the default)")
     ap.add_argument("--layers", type=int, default=16, help="streams in the layer-batched eviction leg (0 = skip)")
     ap.add_argument("--copy-calib", type=int, default=0, metavar="MIB",
                     help="also run an elementwise copy of this many MiB (reads MIB, writes MIB) three times, as "
@@ -216,7 +220,8 @@ def main():
     n_ret = torch.empty((1,), dtype=torch.int32, device=dev)
 
     s = binding.Stream(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, dtype=cfg.torch_dtype,
-                       bias=cfg.bias, max_chunk=cfg.max_chunk, impl=args.impl, policy=args.policy, device=dev)
+                       bias=cfg.bias, max_chunk=cfg.max_chunk, impl=args.impl, policy=args.policy,
+                       rope_base=args.rope or None, device=dev)
     lib = binding.lib()
     P = ctypes.c_void_p
     cargs = [(P(q.data_ptr()), P(k.data_ptr()), P(v.data_ptr())) for q, k, v in chunks]
@@ -265,7 +270,10 @@ def main():
             continue
         us = 1e3 * ms / cnt
         e = {"us": round(us, 3), "launches": cnt}
-        w = work[name]
+        w = work.get(name)
+        if w is None:
+            kernels[name] = e
+            continue
         if "flops" in w:
             e["tflops"] = round(w["flops"] / (us * 1e-6) / 1e12, 2)
         e["gbs"] = round(w["bytes"] / (us * 1e-6) / 1e9, 1)
@@ -294,7 +302,7 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": "%s: %d q-heads / %d kv-heads x %d, budget %d (recent %d), chunk %d, steady state n = %d"
                    % (cfg.name, cfg.heads, cfg.kv_heads, cfg.head_dim, cfg.budget, cfg.recent, L, cfg.budget + L),
-                   "bias": cfg.bias, "seed": cfg.seed, "chunks_in_hbm": nchunks, "policy": args.policy,
+                   "bias": cfg.bias, "seed": cfg.seed, "chunks_in_hbm": nchunks, "policy": args.policy, "rope_base": args.rope,
                    "kernels": "mfma" if mfma else "plain"},
         "roofline": roofline,
         "evict_roofline": evict,
@@ -306,7 +314,7 @@ def main():
         result["layer_batched"] = layer_batched_leg(cfg, binding, chunks, dev, args.impl, args.layers,
                                                     max(4, min(args.steps, 2000 // args.layers)))
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(cfg, policy=args.policy)
+        result["cpu_baseline"] = cpu_baseline(cfg, policy=args.policy, rope_base=args.rope)
     print(json.dumps(result))
 
 

@@ -64,6 +64,13 @@ enum {
                                     3 cumulative: W'[j] = A[j] + S[j], A = the W' a row was retained
                                       with in earlier steps (0 if never ranked); b is not applied.
                                     Modes 1 and 2 launch no scoring kernel                         */
+    INFMLLM_PARAM_ROPE_BASE = 6, /* cache-relative rotary position encoding (Sec. 3.4, length extrapolation):
+                                    0 (default) off; a value > 1 is the base of the rotary angles.  q and k
+                                    are then passed unrotated; for every attention the key in cache row j is
+                                    turned to position j and the query of chunk row i to position t + i
+                                    (pairs (x[i], x[i + head_dim/2]), angle p * base^(-2i/head_dim)), so
+                                    relative distances never exceed the cache size.  Costs one extra pass over
+                                    the cached keys per step and workspace for the turned copies     */
     INFMLLM_PARAM_IMPL = 3       /* debug/test: 0 (default) = bf16 streams run attention and
                                     scoring on the matrix cores; 1 = every dtype runs the
                                     plain fp32-arithmetic kernels (fp32 streams always do)   */
@@ -230,7 +237,8 @@ enum {
     INFMLLM_K_SELECT = 3,
     INFMLLM_K_COMPACT = 4,
     INFMLLM_K_DECODE = 5,
-    INFMLLM_K_COUNT = 6
+    INFMLLM_K_ROPE = 6,
+    INFMLLM_K_COUNT = 7
 };
 
 /*

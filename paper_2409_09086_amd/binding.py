@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libinfmllm.so")
 
 BF16, FP32 = 0, 1
 OK, EINVAL, ENOMEM, ECAPACITY, ESTATE, EHIP = 0, -1, -2, -3, -4, -5
-PARAM_BIAS, PARAM_SCALE, PARAM_MAX_CHUNK, PARAM_IMPL, PARAM_MAX_DECODE, PARAM_POLICY = 0, 1, 2, 3, 4, 5
+PARAM_BIAS, PARAM_SCALE, PARAM_MAX_CHUNK, PARAM_IMPL, PARAM_MAX_DECODE, PARAM_POLICY, PARAM_ROPE_BASE = 0, 1, 2, 3, 4, 5, 6
 POLICIES = {"infmllm": 0, "window": 1, "initial_recent": 2, "cumulative": 3}
 
 EXPORTS = [
@@ -25,7 +25,7 @@ EXPORTS = [
     "infmllm_stream_profile", "infmllm_stream_profile_read", "infmllm_decode", "infmllm_stream_max_len",
     "infmllm_step_attend", "infmllm_stream_pending", "infmllm_evict_batched",
 ]
-KERNELS = ["append", "attn", "score", "select", "compact", "decode"]
+KERNELS = ["append", "attn", "score", "select", "compact", "decode", "rope"]
 
 _lib = None
 
@@ -96,7 +96,8 @@ class Stream:
     """infmllm_stream_t with its workspace: one layer of one sequence on one GPU."""
 
     def __init__(self, budget, recent, heads, kv_heads, head_dim, dtype=torch.bfloat16, bias=None, scale=None,
-                 max_chunk=None, impl=None, max_decode=None, policy=None, device="cuda:0", hip_stream=None):
+                 max_chunk=None, impl=None, max_decode=None, policy=None, rope_base=None, device="cuda:0",
+                 hip_stream=None):
         L = lib()
         self.dtype = dtype
         code = {torch.bfloat16: BF16, torch.float32: FP32}.get(dtype)
@@ -108,7 +109,8 @@ class Stream:
         self.budget, self.recent, self.heads, self.kv_heads, self.head_dim = budget, recent, heads, kv_heads, head_dim
         for which, val in ((PARAM_BIAS, bias), (PARAM_SCALE, scale), (PARAM_MAX_CHUNK, max_chunk), (PARAM_IMPL, impl),
                            (PARAM_MAX_DECODE, max_decode),
-                           (PARAM_POLICY, None if policy is None else POLICIES[policy])):
+                           (PARAM_POLICY, None if policy is None else POLICIES[policy]),
+                           (PARAM_ROPE_BASE, rope_base)):
             if val is not None:
                 _check(L.infmllm_stream_set_param(self._h, which, float(val)))
         self.device = torch.device(device)

@@ -51,6 +51,13 @@ struct infmllm_stream {
     int len;             // rows cached
     int64_t streamed;    // tokens streamed so far
     int last_cnd;        // candidates of the most recent evicting step (0 = none)
+    // cache-relative rotary encoding (off while rope_base == 0): turned copies that attention and scoring read
+    double rope_base = 0.0;
+    void* K_rot = nullptr;      // [Hkv][cap (+pad)][d]
+    void* kc_rot = nullptr;     // [max_chunk][Hkv][d]
+    void* q_rot = nullptr;      // [max_chunk][Hq][d]
+    double* rope_tab = nullptr; // [cap][d/2] (cos, sin)
+    int rot_rows = 0;           // leading rows of the live cache whose K_rot entry is current
     // eviction left pending by infmllm_step_attend: scores are in Wb, the chunk is still read in place
     bool pending = false;
     KeySource pend_ks{0, nullptr, nullptr};
@@ -78,7 +85,7 @@ struct infmllm_stream {
     }
 
     struct Layout {
-        size_t K[2], V[2], pos[2], score[2], lse, Wb, I, part_o, part_ml, dec_part, total;
+        size_t K[2], V[2], pos[2], score[2], lse, Wb, I, part_o, part_ml, dec_part, K_rot, kc_rot, q_rot, rope_tab, total;
         size_t part_rows;
     };
     Layout layout() const
@@ -102,6 +109,11 @@ struct infmllm_stream {
         L.part_o = off; off += up(L.part_rows * g.Hq * g.d * 4);
         L.part_ml = off; off += up(L.part_rows * g.Hq * 2 * 4);
         L.dec_part = off; off += up(g.max_decode > 0 ? (size_t)g.Hq * DECODE_MAX_SPLIT * (g.d + 2) * 4 : 0);
+        const bool rope = rope_base > 0.0;
+        L.K_rot = off; off += rope ? kv : 0;
+        L.kc_rot = off; off += up(rope ? (size_t)g.max_chunk * g.Hkv * g.d * g.elt : 0);
+        L.q_rot = off; off += up(rope ? (size_t)g.max_chunk * g.Hq * g.d * g.elt : 0);
+        L.rope_tab = off; off += up(rope ? (size_t)g.cap * (g.d / 2) * 2 * sizeof(double) : 0);
         L.total = off;
         return L;
     }
@@ -179,6 +191,10 @@ int infmllm_stream_set_param(infmllm_stream_t* s, int which, double value)
                 return fail(INFMLLM_EINVAL, "set_param: policy must be 0, 1, 2 or 3");
             s->g.policy = (int)value;
             return INFMLLM_OK;
+        case INFMLLM_PARAM_ROPE_BASE:
+            if (value != 0 && !(value > 1)) return fail(INFMLLM_EINVAL, "set_param: rope_base must be 0 (off) or > 1");
+            s->rope_base = value;
+            return INFMLLM_OK;
         case INFMLLM_PARAM_IMPL:
             if (value != 0 && value != 1) return fail(INFMLLM_EINVAL, "set_param: impl must be 0 or 1");
             s->impl = (int)value;
@@ -221,6 +237,29 @@ int infmllm_stream_attach(infmllm_stream_t* s, void* ws, size_t bytes, void* hip
     s->fwd.part_ml = (float*)(base + L.part_ml);
     s->fwd.part_rows = L.part_rows;
     s->dec_part = (float*)(base + L.dec_part);
+    s->K_rot = base + L.K_rot;
+    s->kc_rot = base + L.kc_rot;
+    s->q_rot = base + L.q_rot;
+    s->rope_tab = (double*)(base + L.rope_tab);
+    s->rot_rows = 0;
+    if (s->rope_base > 0.0) {
+        // (cos, sin) of p * base^(-2i/d) in fp64 for every cache position p and pair i; the copy is finished
+        // before this function returns (the host buffer is pageable and goes out of scope)
+        const int half = s->g.d / 2;
+        std::vector<double> tab((size_t)s->g.cap * half * 2);
+        for (int i = 0; i < half; ++i) {
+            const double inv = std::pow(s->rope_base, -2.0 * (double)i / (double)s->g.d);
+            for (int p = 0; p < s->g.cap; ++p) {
+                const double ang = (double)p * inv;
+                tab[((size_t)p * half + i) * 2] = std::cos(ang);
+                tab[((size_t)p * half + i) * 2 + 1] = std::sin(ang);
+            }
+        }
+        hipError_t e = hipMemcpyAsync(s->rope_tab, tab.data(), tab.size() * sizeof(double), hipMemcpyHostToDevice,
+                                      (hipStream_t)hip_stream);
+        if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)hip_stream);
+        if (e != hipSuccess) return fail_hip(e, "attach: position table");
+    }
     s->st = (hipStream_t)hip_stream;
     s->cur = 0; s->len = 0; s->streamed = 0; s->last_cnd = 0;
     s->attached = true;
@@ -263,11 +302,28 @@ int step_front(infmllm_stream* s, const void* q, const void* k, const void* v, i
         if ((e = launch_append(g, cur, k, v, t, L, s->streamed, s->st)) != hipSuccess) return fail_hip(e, "append");
         s->mark(INFMLLM_K_APPEND, 1);
     }
+    // With the position encoding on, attention and scoring read turned copies of the keys and queries;
+    // selection and compaction go on working with the rows as given (ks).
+    CacheView att = cur;
+    KeySource ks_att = ks;
+    const void* q_att = q;
+    if (s->rope_base > 0.0) {
+        s->mark(INFMLLM_K_ROPE, 0);
+        const int have = s->rot_rows < t ? s->rot_rows : t;
+        e = launch_rope(g, cur.K, s->K_rot, have, in_place ? t : n, in_place ? k : nullptr, s->kc_rot, q, s->q_rot, t, L,
+                        s->rope_tab, s->st);
+        if (e != hipSuccess) return fail_hip(e, "position encoding");
+        s->mark(INFMLLM_K_ROPE, 1);
+        att.K = s->K_rot;
+        if (in_place) ks_att.k = s->kc_rot;
+        q_att = s->q_rot;
+        s->rot_rows = in_place ? t : n;
+    }
     s->mark(INFMLLM_K_ATTN, 0);
     int nsplit = 1;     // > 1: the attention left key-split partials that the select launch merges into out
-    e = mfma ? launch_attn_mfma(g, cur, ks, q, t, L, out, s->lse, s->fwd, /*defer_combine=*/merge_in_select && n > g.B,
-                                &nsplit, s->st)
-             : launch_attn_simple(g, cur, q, t, L, out, s->lse, s->st);
+    e = mfma ? launch_attn_mfma(g, att, ks_att, q_att, t, L, out, s->lse, s->fwd,
+                                /*defer_combine=*/merge_in_select && n > g.B, &nsplit, s->st)
+             : launch_attn_simple(g, att, q_att, t, L, out, s->lse, s->st);
     if (e != hipSuccess) return fail_hip(e, "attention");
     s->mark(INFMLLM_K_ATTN, 1);
 
@@ -287,8 +343,8 @@ int step_front(infmllm_stream* s, const void* q, const void* k, const void* v, i
     if (g.policy == POLICY_WINDOW || g.policy == POLICY_INITIAL_RECENT)
         e = launch_rank_scores(g, s->Wb, n - g.R, g.policy == POLICY_WINDOW ? 1.f : -1.f, s->st);
     else
-        e = mfma ? launch_score_mfma(g, cur, ks, q, s->lse, s->fwd, nsplit, t, L, s->Wb, s->st)
-                 : launch_score_simple(g, cur, q, s->lse, t, L, s->Wb, s->st);
+        e = mfma ? launch_score_mfma(g, att, ks_att, q_att, s->lse, s->fwd, nsplit, t, L, s->Wb, s->st)
+                 : launch_score_simple(g, att, q_att, s->lse, t, L, s->Wb, s->st);
     if (e != hipSuccess) return fail_hip(e, "score");
     s->mark(INFMLLM_K_SCORE, 1);
     return INFMLLM_OK;
@@ -302,6 +358,7 @@ void step_done(infmllm_stream* s, int n, int L)
     s->last_cnd = n - s->g.R;
     s->streamed += L;
     s->pending = false;
+    s->rot_rows = 0;                                          // the rows have moved: their turned copies are stale
     if (s->prof_steps < s->prof_cap) ++s->prof_steps;
 }
 
@@ -445,8 +502,23 @@ int infmllm_decode(infmllm_stream_t* s, const void* q, const void* k, const void
     if (s->streamed + 1 > (int64_t)INT32_MAX)
         return fail(INFMLLM_ECAPACITY, "decode: stream positions would exceed 2^31-1");
     s->mark(INFMLLM_K_DECODE, 0);
-    hipError_t e = launch_decode(s->g, s->cache[s->cur], q, k, v, s->len, s->streamed, out, s->dec_part,
-                                 DECODE_MAX_SPLIT, s->st);
+    hipError_t e;
+    if (s->rope_base > 0.0) {
+        // the token's row enters the cache as given; the decoding kernels see the turned copies (and put the
+        // turned key at row t of K_rot themselves)
+        const CacheView& cur = s->cache[s->cur];
+        const int t = s->len;
+        if ((e = launch_append(s->g, cur, k, v, t, 1, s->streamed, s->st)) != hipSuccess) return fail_hip(e, "decode: append");
+        e = launch_rope(s->g, cur.K, s->K_rot, s->rot_rows < t ? s->rot_rows : t, t, k, s->kc_rot, q, s->q_rot, t, 1,
+                        s->rope_tab, s->st);
+        if (e != hipSuccess) return fail_hip(e, "decode: position encoding");
+        CacheView att = cur;
+        att.K = s->K_rot;
+        e = launch_decode(s->g, att, s->q_rot, s->kc_rot, v, t, s->streamed, out, s->dec_part, DECODE_MAX_SPLIT, s->st);
+        s->rot_rows = t + 1;
+    } else {
+        e = launch_decode(s->g, s->cache[s->cur], q, k, v, s->len, s->streamed, out, s->dec_part, DECODE_MAX_SPLIT, s->st);
+    }
     if (e != hipSuccess) return fail_hip(e, "decode");
     s->mark(INFMLLM_K_DECODE, 1);
     s->len += 1;
@@ -524,6 +596,7 @@ int infmllm_stream_import(infmllm_stream_t* s, const void* K, const void* V, con
     s->len = len;
     s->streamed = streamed;
     s->last_cnd = 0;
+    s->rot_rows = 0;
     return INFMLLM_OK;
 }
 

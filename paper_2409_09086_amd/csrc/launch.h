@@ -121,6 +121,12 @@ hipError_t launch_compact_batch(const Geometry& g, const EvictBatch& eb, hipStre
 // -1 the oldest).
 hipError_t launch_rank_scores(const Geometry& g, float* Wb, int cnd, float sign, hipStream_t st);
 
+// Cache-relative rotary encoding pre-pass: Krot[h][j] <- K[h][j] turned to position j for j in [j0, j1);
+// kcrot[i][h] <- kc[i][h] and qrot[i][h] <- q[i][h] turned to position t + i for i < L (kc and q may each
+// be null).  tab = [cap][d/2] pairs (cos, sin) of doubles.
+hipError_t launch_rope(const Geometry& g, const void* K, void* Krot, int j0, int j1, const void* kc, void* kcrot,
+                       const void* q, void* qrot, int t, int L, const double* tab, hipStream_t st);
+
 // warm-up: I[h][j] = j for j < n.
 hipError_t launch_iota(const Geometry& g, int n, int32_t* user_I, int32_t* user_count, hipStream_t st);
 

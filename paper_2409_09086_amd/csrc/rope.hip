@@ -1,0 +1,125 @@
+// Cache-relative rotary position encoding for gfx950 (Sec. 3.4: length extrapolation; Sec. 4.1: the
+// models use rotary embeddings).  Keys are cached as given; before attention is computed the key in
+// cache row j is turned to position j and the query of chunk row i to position t + i, so relative
+// distances are distances inside the cache.  This pre-pass writes the turned copies (K_rot in the cache
+// layout, the chunk's keys and the queries token-major) which the attention and scoring kernels then read
+// in place of the originals; selection and compaction keep working on the unrotated rows.
+//
+// Pair (x[i], x[i + d/2]) is turned by p * base^(-2i/d).  The arithmetic is fp64 on a (cos, sin) table
+// computed on the host in fp64, and the result is rounded once to the stream type: retained sets are
+// decided by these values, so they are produced in a way a plain fp64 restatement reproduces bit for bit
+// (HBM-bound pass; the fp64 work hides behind the loads).
+#include "launch.h"
+
+namespace infmllm {
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int ROPE_HPT = 4;                                   // heads per thread
+
+template <typename T> struct Oct;                             // eight consecutive elements of a row
+template <> struct Oct<uint16_t> {
+    u32x4 raw;
+    __device__ __forceinline__ void load(const uint16_t* p) { raw = *(const u32x4*)p; }
+    __device__ __forceinline__ void store(uint16_t* p) const { *(u32x4*)p = raw; }
+    __device__ __forceinline__ double get(int e) const
+    {
+        const uint32_t w = raw[e >> 1];
+        return (double)__uint_as_float((e & 1) ? (w & 0xffff0000u) : (w << 16));
+    }
+    __device__ __forceinline__ void set(int e, double v)
+    {
+        uint32_t u = __float_as_uint((float)v);               // round to nearest even, twice: fp32 then bf16
+        u += 0x7fffu + ((u >> 16) & 1u);
+        u >>= 16;
+        raw[e >> 1] = (e & 1) ? ((raw[e >> 1] & 0x0000ffffu) | (u << 16)) : ((raw[e >> 1] & 0xffff0000u) | u);
+    }
+};
+template <> struct Oct<float> {
+    f32x4 lo, hi;
+    __device__ __forceinline__ void load(const float* p) { lo = *(const f32x4*)p; hi = *(const f32x4*)(p + 4); }
+    __device__ __forceinline__ void store(float* p) const { *(f32x4*)p = lo; *(f32x4*)(p + 4) = hi; }
+    __device__ __forceinline__ double get(int e) const { return (double)(e < 4 ? lo[e & 3] : hi[e & 3]); }
+    __device__ __forceinline__ void set(int e, double v) { if (e < 4) lo[e & 3] = (float)v; else hi[e & 3] = (float)v; }
+};
+
+// One thread = one (row, group of 8 pairs, group of HPT heads): the table entries are loaded once and the
+// HPT heads of that row are turned with them; blockIdx.y picks the group of heads.  Rows: cache rows [j0, j1) (position j), then the chunk's L key rows
+// (position t + i, if kc is given), then the L query rows (position t + i).
+template <typename T, int D>
+__global__ void __launch_bounds__(256)
+rope_kernel(const T* __restrict__ K, T* __restrict__ Krot, int j0, int j1, int cap, int Hkv,
+            const T* __restrict__ kc, T* __restrict__ kcrot, const T* __restrict__ q, T* __restrict__ qrot, int Hq,
+            int t, int L, const double2* __restrict__ tab)
+{
+    constexpr int GPR = D / 16;                               // groups of 8 pairs per row
+    const int nA = j1 - j0, nB = kc ? L : 0, nC = q ? L : 0;
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)(nA + nB + nC) * GPR) return;
+    const int item = (int)(idx / GPR), cc = (int)(idx % GPR);
+    int pos, heads;
+    const T* src;
+    T* dst;
+    long hstride;                                             // elements between two heads of the same row
+    if (item < nA) {
+        pos = j0 + item; heads = Hkv; hstride = (long)cap * D;
+        src = K + (long)pos * D; dst = Krot + (long)pos * D;
+    } else if (item < nA + nB) {
+        const int i = item - nA;
+        pos = t + i; heads = Hkv; hstride = D;
+        src = kc + (long)i * Hkv * D; dst = kcrot + (long)i * Hkv * D;
+    } else {
+        const int i = item - nA - nB;
+        pos = t + i; heads = Hq; hstride = D;
+        src = q + (long)i * Hq * D; dst = qrot + (long)i * Hq * D;
+    }
+    double cs[8], sn[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const double2 v = tab[(long)pos * (D / 2) + 8 * cc + e];
+        cs[e] = v.x; sn[e] = v.y;
+    }
+    const int h0 = blockIdx.y * ROPE_HPT, h1 = min(heads, h0 + ROPE_HPT);
+    for (int h = h0; h < h1; ++h) {
+        Oct<T> a, b;                                          // x[8cc .. 8cc+8) and x[d/2 + 8cc .. +8)
+        a.load(src + h * hstride + 8 * cc);
+        b.load(src + h * hstride + D / 2 + 8 * cc);
+        Oct<T> ra = a, rb = b;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const double x = a.get(e), y = b.get(e);
+            ra.set(e, x * cs[e] - y * sn[e]);
+            rb.set(e, y * cs[e] + x * sn[e]);
+        }
+        ra.store(dst + h * hstride + 8 * cc);
+        rb.store(dst + h * hstride + D / 2 + 8 * cc);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_rope(const Geometry& g, const void* K, void* Krot, int j0, int j1, const void* kc, void* kcrot,
+                       const void* q, void* qrot, int t, int L, const double* tab, hipStream_t st)
+{
+    if (j1 < j0) j1 = j0;
+    const long items = (long)(j1 - j0) + (kc ? L : 0) + (q ? L : 0);
+    if (items <= 0) return hipSuccess;
+    const long threads = items * (g.d / 16);
+    const int hmax = g.Hq > g.Hkv ? g.Hq : g.Hkv;
+    const dim3 grid((unsigned)((threads + 255) / 256), (unsigned)((hmax + ROPE_HPT - 1) / ROPE_HPT)), block(256);
+#define INFMLLM_ROPE(TT, DD)                                                                                  \
+    hipLaunchKernelGGL((rope_kernel<TT, DD>), grid, block, 0, st, (const TT*)K, (TT*)Krot, j0, j1, g.cap, g.Hkv, \
+                       (const TT*)kc, (TT*)kcrot, (const TT*)q, (TT*)qrot, g.Hq, t, L, (const double2*)tab)
+    if (g.elt == 2 && g.d == 128) INFMLLM_ROPE(uint16_t, 128);
+    else if (g.elt == 2 && g.d == 64) INFMLLM_ROPE(uint16_t, 64);
+    else if (g.elt == 4 && g.d == 128) INFMLLM_ROPE(float, 128);
+    else if (g.elt == 4 && g.d == 64) INFMLLM_ROPE(float, 64);
+    else return hipErrorInvalidValue;
+#undef INFMLLM_ROPE
+    return hipGetLastError();
+}
+
+}  // namespace infmllm
