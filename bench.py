@@ -261,7 +261,27 @@ def main():
     run(prof_steps, warmup + args.steps)
     torch.cuda.synchronize()
     prof = s.profile_read()
+    # ... and once more with a single bracket around selection + gather (Alg. 1 l.5-8 as a whole)
+    s.profile_select(["evict"])
+    s.profile(prof_steps)
+    run(prof_steps, warmup + args.steps)
+    torch.cuda.synchronize()
+    prof["evict"] = s.profile_read()["evict"]
+    s.profile_select(binding.KERNELS)
     s.profile(0)
+
+    # pass 3: latency of single steps (event pair around each call, on the stream the kernels run on)
+    lat_steps = min(args.steps, 512)
+    ts = torch.cuda.ExternalStream(s.hip_stream, device=dev) if s.hip_stream else torch.cuda.current_stream(dev)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(lat_steps)]
+    for i, (e0, e1) in enumerate(evs):
+        e0.record(ts)
+        run(1, warmup + args.steps + prof_steps + i)
+        e1.record(ts)
+    torch.cuda.synchronize()
+    lat = sorted(1e3 * e0.elapsed_time(e1) for e0, e1 in evs)
+    latency = {"p50": round(lat[len(lat) // 2], 2), "p99": round(lat[min(len(lat) - 1, int(0.99 * len(lat)))], 2),
+               "max": round(lat[-1], 2), "steps": lat_steps}
 
     work = algorithmic_work(cfg, L, cfg.budget)
     kernels = {}
@@ -285,7 +305,8 @@ def main():
                 "unit": "TFLOP/s", "frac": round(attn["tflops"] / peak, 4),
                 "traffic": read_traffic("attn_fwd_%s_pmc.txt" % cfg.name),
                 "algorithmic_flops_per_launch": work["attn"]["flops"], "avg_us": attn["us"]}
-    evict_us = kernels.get("select", {}).get("us", 0.0) + kernels.get("compact", {}).get("us", 0.0)
+    # selection + gather as one bracket (start of the selection launch to end of the gather launch)
+    evict_us = kernels.get("evict", {}).get("us", 0.0)
     evict_bytes = work["select"]["bytes"] + work["compact"]["bytes"]
     evict = {"bound": "hbm", "achieved": round(evict_bytes / (evict_us * 1e-6) / 1e9, 1) if evict_us else None,
              "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -307,6 +328,7 @@ def main():
         "roofline": roofline,
         "evict_roofline": evict,
         "kernels": kernels,
+        "step_latency_us": latency,
     }
     result["decode"] = decode_leg(cfg, binding, chunks, dev, args.impl)
     if args.layers > 0:

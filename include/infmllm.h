@@ -238,7 +238,9 @@ enum {
     INFMLLM_K_COMPACT = 4,
     INFMLLM_K_DECODE = 5,
     INFMLLM_K_ROPE = 6,
-    INFMLLM_K_COUNT = 7
+    INFMLLM_K_EVICT = 7,  /* not a kernel: from the start of the selection launch to the end of the gather launch of
+                             a step (Alg. 1 l.5-8 as a whole, one event pair instead of two) */
+    INFMLLM_K_COUNT = 8
 };
 
 /*
@@ -248,6 +250,15 @@ enum {
  * Errors: EINVAL (max_steps outside 0..4096), ESTATE (not attached), EHIP.
  */
 int infmllm_stream_profile(infmllm_stream_t* s, int max_steps);
+
+/*
+ * Chooses which of the INFMLLM_K_* intervals get events in the steps recorded from now on: bit k of
+ * `kernels` switches interval k on (default: all).  Every event pair delays the stream a little, so a
+ * caller who wants the undisturbed duration of one interval records only that one; INFMLLM_K_EVICT
+ * alone records two events per step, before the selection launch and after the gather launch.
+ * Errors: EINVAL (null stream, empty mask or bits beyond INFMLLM_K_COUNT).
+ */
+int infmllm_stream_profile_select(infmllm_stream_t* s, unsigned kernels);
 
 /*
  * Measurement: waits for the recorded events and returns, per kernel, the summed duration in

@@ -23,9 +23,9 @@ EXPORTS = [
     "infmllm_stream_positions", "infmllm_stream_export", "infmllm_stream_import",
     "infmllm_stream_last_scores", "infmllm_last_error", "infmllm_stream_destroy",
     "infmllm_stream_profile", "infmllm_stream_profile_read", "infmllm_decode", "infmllm_stream_max_len",
-    "infmllm_step_attend", "infmllm_stream_pending", "infmllm_evict_batched",
+    "infmllm_step_attend", "infmllm_stream_pending", "infmllm_evict_batched", "infmllm_stream_profile_select",
 ]
-KERNELS = ["append", "attn", "score", "select", "compact", "decode", "rope"]
+KERNELS = ["append", "attn", "score", "select", "compact", "decode", "rope", "evict"]
 
 _lib = None
 
@@ -63,6 +63,7 @@ def lib():
         L.infmllm_stream_import.argtypes = [P, P, P, P, I, ctypes.c_int64]
         L.infmllm_stream_last_scores.argtypes = [P, P, ctypes.POINTER(I)]
         L.infmllm_stream_profile.argtypes = [P, I]
+        L.infmllm_stream_profile_select.argtypes = [P, ctypes.c_uint]
         L.infmllm_stream_profile_read.argtypes = [P, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(I)]
         L.infmllm_last_error.restype = ctypes.c_char_p
         L.infmllm_stream_destroy.argtypes = [P]
@@ -222,6 +223,13 @@ class Stream:
 
     def profile(self, max_steps):
         _check(lib().infmllm_stream_profile(self._h, int(max_steps)))
+
+    def profile_select(self, names):
+        """Record events only for these intervals (names from KERNELS) in the steps profiled from now on."""
+        mask = 0
+        for n in names:
+            mask |= 1 << KERNELS.index(n)
+        _check(lib().infmllm_stream_profile_select(self._h, mask))
 
     def profile_read(self):
         """{kernel: (total ms, launches)} of the steps recorded since the last read."""

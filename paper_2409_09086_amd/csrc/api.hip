@@ -4,6 +4,7 @@
 // streaming step.  No device memory is allocated here and nothing synchronises.
 #include "../../include/infmllm.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -72,11 +73,15 @@ struct infmllm_stream {
     std::vector<char> prof_used;       // [prof_cap][INFMLLM_K_COUNT]
     int prof_cap = 0, prof_steps = 0;
 
+    unsigned prof_mask = ~0u;          // kernels whose events are recorded (bit INFMLLM_K_*)
     void mark(int kernel, int edge)
     {
         if (prof_steps >= prof_cap) return;
+        const bool bracket = ((prof_mask >> INFMLLM_K_EVICT) & 1u) &&
+                             ((kernel == INFMLLM_K_SELECT && edge == 0) || (kernel == INFMLLM_K_COMPACT && edge == 1));
+        if (!((prof_mask >> kernel) & 1u) && !bracket) return;
         const size_t slot = (size_t)prof_steps * INFMLLM_K_COUNT + kernel;
-        if (hipEventRecord(prof_ev[slot * 2 + edge], st) == hipSuccess && edge == 1) prof_used[slot] = 1;
+        if (hipEventRecord(prof_ev[slot * 2 + edge], st) == hipSuccess) prof_used[slot] |= (char)(1 << edge);
     }
     void drop_events()
     {
@@ -470,6 +475,14 @@ int infmllm_stream_profile(infmllm_stream_t* s, int max_steps)
     return INFMLLM_OK;
 }
 
+int infmllm_stream_profile_select(infmllm_stream_t* s, unsigned kernels)
+{
+    if (!s) return fail(INFMLLM_EINVAL, "profile_select: stream is null");
+    if (kernels == 0 || (kernels >> INFMLLM_K_COUNT)) return fail(INFMLLM_EINVAL, "profile_select: bad kernel mask");
+    s->prof_mask = kernels;
+    return INFMLLM_OK;
+}
+
 int infmllm_stream_profile_read(infmllm_stream_t* s, float* ms, int* launches)
 {
     if (!s || !ms || !launches) return fail(INFMLLM_EINVAL, "profile_read: null argument");
@@ -477,15 +490,19 @@ int infmllm_stream_profile_read(infmllm_stream_t* s, float* ms, int* launches)
     for (int step = 0; step < s->prof_steps; ++step)
         for (int k = 0; k < INFMLLM_K_COUNT; ++k) {
             const size_t slot = (size_t)step * INFMLLM_K_COUNT + k;
-            if (!s->prof_used[slot]) continue;
-            hipError_t e = hipEventSynchronize(s->prof_ev[slot * 2 + 1]);
+            const bool whole_eviction = (k == INFMLLM_K_EVICT);
+            const size_t first = whole_eviction ? (size_t)step * INFMLLM_K_COUNT + INFMLLM_K_SELECT : slot;
+            const size_t last = whole_eviction ? (size_t)step * INFMLLM_K_COUNT + INFMLLM_K_COMPACT : slot;
+            if (!(s->prof_used[first] & 1) || !(s->prof_used[last] & 2)) continue;
+            if (!((s->prof_mask >> k) & 1u)) continue;
+            hipError_t e = hipEventSynchronize(s->prof_ev[last * 2 + 1]);
             float dt = 0.f;
-            if (e == hipSuccess) e = hipEventElapsedTime(&dt, s->prof_ev[slot * 2], s->prof_ev[slot * 2 + 1]);
+            if (e == hipSuccess) e = hipEventElapsedTime(&dt, s->prof_ev[first * 2], s->prof_ev[last * 2 + 1]);
             if (e != hipSuccess) return fail_hip(e, "profile_read: event");
             ms[k] += dt;
             ++launches[k];
-            s->prof_used[slot] = 0;
         }
+    std::fill(s->prof_used.begin(), s->prof_used.end(), 0);
     s->prof_steps = 0;
     return INFMLLM_OK;
 }
