@@ -113,7 +113,7 @@ struct infmllm_stream {
         L.part_rows = (g.elt == 2 && g.d == 128) ? (size_t)4 * (g.max_chunk < 4096 ? g.max_chunk : 4096) : 0;
         L.part_o = off; off += up(L.part_rows * g.Hq * g.d * 4);
         L.part_ml = off; off += up(L.part_rows * g.Hq * 2 * 4);
-        L.dec_part = off; off += up(g.max_decode > 0 ? (size_t)g.Hq * DECODE_MAX_SPLIT * (g.d + 2) * 4 : 0);
+        L.dec_part = off; off += up(g.max_decode > 0 ? (size_t)g.Hq * DECODE_MAX_SPLIT * (g.d + 2) * 4 + (size_t)g.Hkv * 4 : 0);
         const bool rope = rope_base > 0.0;
         L.K_rot = off; off += rope ? kv : 0;
         L.kc_rot = off; off += up(rope ? (size_t)g.max_chunk * g.Hkv * g.d * g.elt : 0);

@@ -5,9 +5,11 @@
 // step is HBM-bound and runs on the vector ALUs (no matrix cores).  The key range of a kv-head is cut
 // into `nsplit` pieces so that the grid covers the chip; a workgroup streams its piece with 16-byte
 // loads (consecutive lanes cover a row), keeps one online-softmax state per row slot and query head
-// of the group, merges the row slots through LDS and writes an un-normalised partial; a second
-// small kernel merges the partials of a head.  The token's own k, v are read from the caller's
-// tensors and written to cache row t by the workgroup that owns the last piece.
+// of the group, merges the row slots through LDS and writes an un-normalised partial.  The workgroup
+// of a kv-head that finishes last (a ticket counter per kv-head) merges the partials of its heads,
+// so the step is one launch; the partials travel through agent-scope stores and loads, which go
+// through to memory, so no cache has to be flushed.  The token's own k, v are read from the
+// caller's tensors and written to cache row t by the workgroup that owns the last piece.
 #include "launch.h"
 
 namespace infmllm {
@@ -68,7 +70,8 @@ template <typename T, int D, int NG>
 __global__ void __launch_bounds__(DEC_THREADS)
 decode_partial_kernel(const T* __restrict__ q, const T* __restrict__ knew, const T* __restrict__ vnew,
                       T* __restrict__ K, T* __restrict__ V, int32_t* __restrict__ pos, float* __restrict__ score,
-                      float* __restrict__ part, int t, int G, int cap, int nsplit, int pos_new, float c)
+                      float* __restrict__ part, int* __restrict__ arrived, T* __restrict__ out, int t, int G, int cap,
+                      int nsplit, int pos_new, float c)
 {
     using VT = Vec16<T>;
     typedef typename VT::raw raw;
@@ -77,6 +80,7 @@ decode_partial_kernel(const T* __restrict__ q, const T* __restrict__ knew, const
     constexpr int SLOTS = DEC_THREADS / LPR;           // rows in flight per workgroup pass
     __shared__ float s_m[SLOTS][NG], s_l[SLOTS][NG];
     __shared__ float s_o[SLOTS][NG][D];
+    __shared__ int s_ticket;
 
     const int sp = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
     const int slot = tid / LPR, cc = tid % LPR;
@@ -156,9 +160,14 @@ decode_partial_kernel(const T* __restrict__ q, const T* __restrict__ knew, const
                 lt += w * s_l[s][gg];
                 ot += w * s_o[s][gg][x];
             }
+            // The partials are read by whichever workgroup of this kv-head finishes last, possibly on another
+            // XCD with its own L2: they are written with agent-scope stores, which go through to memory.
             float* pp = part + ((size_t)(h * G + g0 + gg) * nsplit + sp) * (D + 2);
-            pp[2 + x] = ot;
-            if (x == 0) { pp[0] = mt; pp[1] = lt; }
+            __hip_atomic_store(pp + 2 + x, ot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (x == 0) {
+                __hip_atomic_store(pp, mt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(pp + 1, lt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     }
     // the token's own row becomes cache row t
@@ -172,44 +181,47 @@ decode_partial_kernel(const T* __restrict__ q, const T* __restrict__ knew, const
             score[(size_t)h * cap + t] = __builtin_inff();
         }
     }
-}
-
-// out[head][x] = sum_s w_s o_s[x] / sum_s w_s l_s, w_s = 2^(m_s - max m).  The partials were written by
-// workgroups all over the chip, so every read is a trip to memory: they are issued eight splits at a
-// time before any is used (a loop over the splits would serialise the round trips).
-template <typename T, int D>
-__global__ void __launch_bounds__(D)
-decode_combine_kernel(const float* __restrict__ part, T* __restrict__ out, int nsplit)
-{
+    // The workgroup of this kv-head that arrives last merges the splits: every workgroup waits until its own
+    // partials have been written through, then takes a ticket.  No workgroup waits for another one.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) s_ticket = __hip_atomic_fetch_add(arrived + h, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (s_ticket != nsplit - 1) return;
+    if (tid == 0) __hip_atomic_store(arrived + h, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
+    // out[head][x] = sum_s w_s o_s[x] / sum_s w_s l_s, w_s = 2^(m_s - max m); eight splits are requested at a
+    // time before any is used (a loop over the splits would serialise the trips to memory)
     constexpr int CH = 8;
-    const int g = blockIdx.x, x = threadIdx.x;
-    const float* pp = part + (size_t)g * nsplit * (D + 2);
-    float mt = -__builtin_inff(), lt = 0.f, ot = 0.f;
-    for (int s0 = 0; s0 < nsplit; s0 += CH) {
-        float mv[CH], lv[CH], ov[CH];
+    for (int idx = tid; idx < G * D; idx += DEC_THREADS) {
+        const int gq = h * G + idx / D, x = idx % D;
+        const float* pp = part + (size_t)gq * nsplit * (D + 2);
+        float mt = -__builtin_inff(), lt = 0.f, ot = 0.f;
+        for (int s0 = 0; s0 < nsplit; s0 += CH) {
+            float mv[CH], lv[CH], ov[CH];
 #pragma unroll
-        for (int u = 0; u < CH; ++u) {
-            const int s = min(s0 + u, nsplit - 1);
-            mv[u] = pp[(size_t)s * (D + 2)];
-            lv[u] = pp[(size_t)s * (D + 2) + 1];
-            ov[u] = pp[(size_t)s * (D + 2) + 2 + x];
+            for (int u = 0; u < CH; ++u) {
+                const int s = min(s0 + u, nsplit - 1);
+                mv[u] = __hip_atomic_load(pp + (size_t)s * (D + 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                lv[u] = __hip_atomic_load(pp + (size_t)s * (D + 2) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ov[u] = __hip_atomic_load(pp + (size_t)s * (D + 2) + 2 + x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            float mc = mt;
+#pragma unroll
+            for (int u = 0; u < CH; ++u) mc = fmaxf(mc, mv[u]);
+            const float rescale = __builtin_amdgcn_exp2f(mt - mc);          // first chunk: 2^-inf = 0
+            lt *= rescale;
+            ot *= rescale;
+            mt = mc;
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {
+                if (s0 + u >= nsplit) break;
+                const float w = __builtin_amdgcn_exp2f(mv[u] - mt);         // an empty piece has m = -inf
+                lt += w * lv[u];
+                ot += w * ov[u];
+            }
         }
-        float mc = mt;
-#pragma unroll
-        for (int u = 0; u < CH; ++u) mc = fmaxf(mc, mv[u]);
-        const float rescale = __builtin_amdgcn_exp2f(mt - mc);          // first chunk: 2^-inf = 0
-        lt *= rescale;
-        ot *= rescale;
-        mt = mc;
-#pragma unroll
-        for (int u = 0; u < CH; ++u) {
-            if (s0 + u >= nsplit) break;
-            const float w = __builtin_amdgcn_exp2f(mv[u] - mt);         // an empty piece has m = -inf
-            lt += w * lv[u];
-            ot += w * ov[u];
-        }
+        out[(size_t)gq * D + x] = VT::from_float(ot / lt);
     }
-    out[(size_t)g * D + x] = Vec16<T>::from_float(ot / lt);
 }
 
 }  // namespace
@@ -223,19 +235,17 @@ hipError_t launch_decode(const Geometry& g, const CacheView& c, const void* q, c
     if (nsplit > max_split) nsplit = max_split;
     if (nsplit < 1) nsplit = 1;
     const float cc = g.scale * 1.4426950408889634f;
+    int* arrived = (int*)(part + (size_t)g.Hq * max_split * (g.d + 2));   // one ticket counter per kv-head, zero between launches
     const dim3 grid(nsplit, g.Hkv);
 #define INFMLLM_DECODE_NG(TT, DD, NG)                                                                            \
     hipLaunchKernelGGL((decode_partial_kernel<TT, DD, NG>), grid, dim3(DEC_THREADS), 0, st, (const TT*)q,        \
-                       (const TT*)k, (const TT*)v, (TT*)c.K, (TT*)c.V, c.pos, c.score, part, t, g.G, g.cap,      \
-                       nsplit, (int)T, cc)
+                       (const TT*)k, (const TT*)v, (TT*)c.K, (TT*)c.V, c.pos, c.score, part, arrived, (TT*)out, t, \
+                       g.G, g.cap, nsplit, (int)T, cc)
 #define INFMLLM_DECODE(TT, DD)                                                                                   \
     do {                                                                                                         \
         if (g.G % 4 == 0) INFMLLM_DECODE_NG(TT, DD, 4);                                                          \
         else if (g.G % 2 == 0) INFMLLM_DECODE_NG(TT, DD, 2);                                                     \
         else INFMLLM_DECODE_NG(TT, DD, 1);                                                                       \
-        hipError_t e = hipGetLastError();                                                                        \
-        if (e != hipSuccess) return e;                                                                           \
-        hipLaunchKernelGGL((decode_combine_kernel<TT, DD>), dim3(g.Hq), dim3(DD), 0, st, part, (TT*)out, nsplit); \
     } while (0)
     if (g.elt == 2 && g.d == 128) INFMLLM_DECODE(uint16_t, 128);
     else if (g.elt == 2 && g.d == 64) INFMLLM_DECODE(uint16_t, 64);

@@ -131,7 +131,8 @@ hipError_t launch_rope(const Geometry& g, const void* K, void* Krot, int j0, int
 hipError_t launch_iota(const Geometry& g, int n, int32_t* user_I, int32_t* user_count, hipStream_t st);
 
 // Decoding step: appends the token's k, v as cache row t and attends all t + 1 keys with q (one
-// row per query head).  part is scratch of [Hq][max_split][d + 2] floats.
+// row per query head).  part is scratch of [Hq][max_split][d + 2] floats followed by Hkv ints that are zero
+// between launches (ticket counters; the last workgroup of a kv-head to finish merges its splits).
 constexpr int DECODE_MAX_SPLIT = 64;
 hipError_t launch_decode(const Geometry& g, const CacheView& c, const void* q, const void* k, const void* v, int t,
                          int64_t T, void* out, float* part, int max_split, hipStream_t st);
