@@ -77,6 +77,48 @@ def test_host_state_machine_without_a_device():
     assert L.infmllm_stream_len(None) == -1 and L.infmllm_stream_workspace_bytes(None) == 0
 
 
+def test_optional_modes_are_checked_and_sized_on_the_host():
+    """decoding room, comparison policies, position encoding, batched eviction: parameter checks and the
+    workspace they ask for, all without a device"""
+    L = B.lib()
+    rc, h = make(budget=64, recent=16, heads=4, kv=2, d=128)
+    assert rc == B.OK
+    assert L.infmllm_stream_set_param(h, B.PARAM_MAX_CHUNK, 32.0) == B.OK
+    base = L.infmllm_stream_workspace_bytes(h)
+    assert L.infmllm_stream_max_len(h) == 64
+    assert L.infmllm_stream_set_param(h, B.PARAM_MAX_DECODE, -1.0) == B.EINVAL
+    assert L.infmllm_stream_set_param(h, B.PARAM_MAX_DECODE, 2.5) == B.EINVAL
+    assert L.infmllm_stream_set_param(h, B.PARAM_MAX_DECODE, 8.0) == B.OK
+    with_decode = L.infmllm_stream_workspace_bytes(h)
+    assert with_decode > base and L.infmllm_stream_max_len(h) == 72           # 8 more rows per head + partials
+    for bad in (-1.0, 4.0, 1.5):
+        assert L.infmllm_stream_set_param(h, B.PARAM_POLICY, bad) == B.EINVAL
+    for ok in (1.0, 2.0, 3.0, 0.0):
+        assert L.infmllm_stream_set_param(h, B.PARAM_POLICY, ok) == B.OK
+    assert L.infmllm_stream_workspace_bytes(h) == with_decode                 # policies need no memory
+    for bad in (1.0, 0.5, -10000.0, float("inf")):
+        assert L.infmllm_stream_set_param(h, B.PARAM_ROPE_BASE, bad) == B.EINVAL
+    assert L.infmllm_stream_set_param(h, B.PARAM_ROPE_BASE, 10000.0) == B.OK
+    with_rope = L.infmllm_stream_workspace_bytes(h)
+    cap, d, elt = 64 + 8 + 32, 128, 2
+    assert with_rope - with_decode >= 2 * cap * d * elt + cap * (d // 2) * 16   # turned keys of 2 heads + the table
+    assert L.infmllm_stream_set_param(h, B.PARAM_ROPE_BASE, 0.0) == B.OK
+    assert L.infmllm_stream_workspace_bytes(h) == with_decode
+    # calls that need an attached stream are refused on the host
+    one = ctypes.c_void_p(256)
+    assert L.infmllm_decode(h, one, one, one, one) == B.ESTATE
+    assert L.infmllm_step_attend(h, one, one, one, 4, one, None, None) == B.ESTATE
+    assert L.infmllm_stream_pending(h) == 0 and L.infmllm_stream_pending(None) == -1
+    arr = (ctypes.c_void_p * 1)(h)
+    assert L.infmllm_evict_batched(arr, 1, None, None) == B.ESTATE
+    assert L.infmllm_evict_batched(arr, 0, None, None) == B.EINVAL
+    assert L.infmllm_evict_batched(None, 1, None, None) == B.EINVAL
+    assert L.infmllm_stream_profile_select(h, 0) == B.EINVAL
+    assert L.infmllm_stream_profile_select(h, 1 << 20) == B.EINVAL
+    assert L.infmllm_stream_profile_select(h, 0xFF) == B.OK
+    L.infmllm_stream_destroy(h)
+
+
 @pytest.mark.gpu
 def test_step_argument_checks_after_attach():
     """host-side checks of step on an attached stream: every call is refused before any launch"""
