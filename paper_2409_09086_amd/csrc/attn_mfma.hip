@@ -181,7 +181,9 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
         bx = ntile - 1 - rem / nsplit;                       // longest (most keys visible) tiles first
         sp = rem % nsplit;
     }
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: branches on it are scalar
+    const bool stage_first = C::NW == 8 && wave >= 4;        // wavefronts w and w + 4 share a SIMD
     const int rb = wave % RB, kw = wave / RB;
     const int rbph = RB / hpw;                               // row blocks per head inside the workgroup
     const int ngrp = G / hpw;                                // head groups per kv-head
@@ -297,6 +299,14 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
         }
         const char* const kbase = smem + buf * C::BUF + koff;
         const char* const vbase = smem + buf * C::BUF + voff;
+        // The other buffer was last read one iteration ago, before the barrier that ended it, so the next
+        // tile may be staged at any point of this iteration.  The second wavefront of every SIMD does it
+        // first and the first one last: the two then reach their MFMA and VALU phases at different times
+        // instead of queueing for the same pipe.
+        if (C::NBUF == 2 && stage_first) {
+            if (tile + 1 < ntiles) stash(buf ^ 1);
+            if (tile + 2 < ntiles) fetch(kv0 + 2 * C::TILE);
+        }
 
         const int sub0 = kv0 + kw * C::SUB;                  // first key of my slice of the tile
         if (sub0 < wave_end) {                               // else nothing visible for this wavefront
@@ -373,9 +383,10 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
             }
         }
         if (C::NBUF == 2) {
-            // the other buffer was last read one iteration ago, before the barrier that ended it
-            if (tile + 1 < ntiles) stash(buf ^ 1);
-            if (tile + 2 < ntiles) fetch(kv0 + 2 * C::TILE);
+            if (!stage_first) {
+                if (tile + 1 < ntiles) stash(buf ^ 1);
+                if (tile + 2 < ntiles) fetch(kv0 + 2 * C::TILE);
+            }
             __syncthreads();
         }
     }
