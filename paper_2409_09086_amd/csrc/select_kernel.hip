@@ -85,11 +85,7 @@ __device__ __forceinline__ void select_mem_body(const float* __restrict__ Wb, in
                 // wavefront 0 walks the bins from the top; lane l owns bins 255-4l .. 252-4l
                 const int l = threadIdx.x;
                 uint32_t c0 = hist[255 - 4 * l], c1 = hist[254 - 4 * l], c2 = hist[253 - 4 * l], c3 = hist[252 - 4 * l];
-                uint32_t mine = c0 + c1 + c2 + c3, incl = mine;
-                for (int o = 1; o < 64; o <<= 1) {
-                    const uint32_t up = __shfl_up(incl, o);
-                    if (l >= o) incl += up;
-                }
+                const uint32_t mine = c0 + c1 + c2 + c3, incl = wave_inclusive_sum(mine);
                 const uint32_t before = incl - mine;          // keys in higher bins than my four
                 const uint32_t need = s_remaining;
                 if (before < need && need <= incl) {          // the r-th largest falls in my bins
