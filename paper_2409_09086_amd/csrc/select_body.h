@@ -1,6 +1,5 @@
-// Device code of the per-head top-r selection (Alg. 1 l.5-7) and of the recent-window move, shared by the
-// selection kernels and by the scoring kernel, whose last workgroup of a kv-head can run the selection
-// itself.  TPB = threads of the calling workgroup.
+// Device code of the per-head top-r selection (Alg. 1 l.5-7) and of the recent-window move, templated
+// on TPB, the threads of the calling workgroup.
 #pragma once
 #include "launch.h"
 
@@ -116,7 +115,7 @@ __device__ __forceinline__ void copy_recent(const RecentCopy& rc, int wg, int Hk
 // bin search and a pass costs two barriers.  The digits stop as soon as the bin that holds the
 // r-th largest key is wanted whole (as a rule after the second: few of a few thousand candidates
 // share 16 bits), and the ordered write needs two more barriers.
-template <int KPT, int TPB, bool THROUGH>
+template <int KPT, int TPB>
 __device__ __forceinline__ void select_reg_body(const float* __restrict__ Wb, int32_t* __restrict__ I,
                                                 int32_t* __restrict__ userI, int32_t* __restrict__ user_count,
                                                 int h, int cnd, int r, int R, int B, int cap)
@@ -142,7 +141,7 @@ __device__ __forceinline__ void select_reg_body(const float* __restrict__ Wb, in
             const int j = k * TPB + tid;
             key[k] = 0u;
             if (j < cnd) {
-                key[k] = order_key(THROUGH ? __hip_atomic_load(W + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : W[j]);
+                key[k] = order_key(W[j]);
                 lo_key = key[k] < lo_key ? key[k] : lo_key;
                 hi_key = key[k] > hi_key ? key[k] : hi_key;
             }

@@ -1,12 +1,13 @@
 // Per-head top-r selection for gfx950 (Alg. 1 l.5-7).
 //
 // One workgroup of 1024 threads per kv-head.  The r-th largest biased score is found with an
-// MSB-first radix select over order-preserving 32-bit keys (four 8-bit digits); digit
-// histograms are built from wavefront ballots of the candidates that still match the
-// prefix, so LDS sees one atomic per distinct digit per wavefront instead of one per key.
-// The kept set {key > T} U {the newest ties of key == T} is then written in ascending
-// index order through a block-wide ballot/popcount scan, followed by the recent window
-// [c, n), which is kept unconditionally.  Ties go to the larger index (the newer key).
+// MSB-first radix select over order-preserving 32-bit keys (8-bit digits).  With the candidates
+// of a head in registers (select_body.h) the digits start below the bits all keys share and are
+// counted with LDS atomics; with the candidates left in memory (more than 16 per thread) the
+// histograms are built from wavefront ballots of the candidates that still match the prefix.
+// The kept set {key > T} U {the newest ties of key == T} is then written in ascending index
+// order through block-wide ballot/popcount scans, followed by the recent window [c, n), which
+// is kept unconditionally.  Ties go to the larger index (the newer key).
 #include "launch.h"
 #include "select_body.h"
 
@@ -155,7 +156,7 @@ __device__ __forceinline__ void select_body(const float* Wb, int32_t* I, int32_t
                                             int cnd, int r, int R, int B, int cap)
 {
     if constexpr (KPT == 0) select_mem_body(Wb, I, userI, user_count, h, cnd, r, R, B, cap);
-    else select_reg_body<KPT, TPB, false>(Wb, I, userI, user_count, h, cnd, r, R, B, cap);
+    else select_reg_body<KPT, TPB>(Wb, I, userI, user_count, h, cnd, r, R, B, cap);
 }
 
 // One stream: workgroups [0, Hkv) select, the next rc.ncopy move the recent window, the rest

@@ -49,7 +49,9 @@ class LockStep:
         self.max_err = 0.0
         self.steps = 0
 
-    def step(self, q, k, v, check_state=False):
+    def step(self, q, k, v, check_state=False, strict=False):
+        """strict: the retained sets must be identical, ties included (for inputs whose ties are exact on
+        both sides, where the band of check_retained would hide a wrong choice among them)."""
         dev = self.gpu.device
         out_g, ret_g, n_g = self.gpu.step(q.to(dev), k.to(dev), v.to(dev))
         t = len(self.oracle)
@@ -64,6 +66,8 @@ class LockStep:
         I_o = self.oracle.select()
         I_g = ret_g.cpu().numpy()[:, :count]
         self.swaps += check_retained(I_g, I_o, None if sc is None else sc[1], n, self.gpu.budget, self.gpu.recent)
+        if strict:
+            assert (I_g == I_o).all(), "step %d: retained lists differ at %s" % (self.steps, np.argwhere(I_g != I_o)[:4])
         self.oracle.commit(I_g)
         if check_state:
             self.check_state()
