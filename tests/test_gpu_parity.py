@@ -49,6 +49,9 @@ def test_cfg1_tiny_fp32_stream(bias):
     (6, 2, 128, 128, 40, [60, 60, 33, 60, 60]),                     # group of 3 query heads
     (8, 1, 64, 96, 32, [48, 48, 48, 48]),                           # group of 8 query heads
     (2, 2, 128, 300, 100, [300, 7, 300, 150]),                      # chunk as long as the budget
+    (4, 2, 128, 96, 32, [150, 40, 150, 1, 97]),                     # chunks longer than the budget: the first step evicts
+    (2, 2, 64, 24, 8, [40, 3, 17, 24, 5]),                          # budget below one 32-row tile
+    (2, 1, 128, 40, 40, [64, 9]),                                   # r = 0 and chunk > budget
 ])
 def test_small_bf16_streams(impl, heads, kv, d, budget, recent, chunks):
     ls = pair(budget, recent, heads, kv, d, "bf16", 1e-3, max_chunk=max(chunks), impl=impl)
