@@ -522,24 +522,39 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
         if (tid < TROWS) *(float*)(base + QBYTES + tid * 4) = (stl_idx >= 0) ? s_lse[stl_idx] : stl;
     };
     if (niter > 0) fetch();
-    // The key fragments are requested last: loads return in order, so the small loads above (log-sum-exp,
-    // first query rows) can be waited for and staged while the 64 KB of keys are still on their way.
-    // key fragments: B operand of S = Q.K^T, lane (column l32, half hh) holds K[col][16s + 8hh .. +8)
+    // Key fragments: B operand of S = Q.K^T, lane (column l32, half hh) holds K[col][16s + 8hh .. +8).
+    // Loaded in that layout straight from memory a wavefront touches 32 rows with every instruction; the
+    // workgroup's 128*CB key rows are therefore read once with whole-row (coalesced) loads into the query
+    // tile buffers, which are not in use yet, and the fragments are picked up from there.
+    constexpr int KROWS = 128 * CB, KLD = KROWS * CPR / 512;
+    static_assert(KROWS * QP <= 2 * BUF, "the key tile is staged in the query buffers");
+    {
+        u32x4 kt[KLD];
+#pragma unroll
+        for (int u = 0; u < KLD; ++u) {
+            const int ch = tid + u * 512, r = ch / CPR;
+            const int col = bx * KROWS + r;
+            const bool ok = col < cnd;
+            const int cc = ok ? col : 0;
+            const uint16_t* kp = (cc < tc ? K + ((size_t)h * cap + cc) * D : kc + ((size_t)(cc - tc) * Hkv + h) * D) + (ch % CPR) * 8;
+            kt[u] = *(const u32x4*)kp;
+            if (!ok) kt[u] = u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < KLD; ++u) {
+            const int ch = tid + u * 512;
+            *(u32x4*)(smem + (ch / CPR) * QP + (ch % CPR) * 16) = kt[u];
+        }
+    }
+    __syncthreads();                                          // key tile and s_lse are complete
     bf16x8 kf[CB][D / 16];
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
-        const int col = col0 + 32 * cb + l32;
-        const bool ok = col < cnd;
-        const int cc = ok ? col : 0;
-        const uint16_t* kp = (cc < tc ? K + ((size_t)h * cap + cc) * D : kc + ((size_t)(cc - tc) * Hkv + h) * D) + 8 * hh;
+        const char* kp = smem + (cg * 32 * CB + 32 * cb + l32) * QP + 16 * hh;
 #pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-            u32x4 v = *(const u32x4*)(kp + 16 * s);
-            if (!ok) v = u32x4{0u, 0u, 0u, 0u};
-            kf[cb][s] = as_bf16x8(v);
-        }
+        for (int s = 0; s < D / 16; ++s) kf[cb][s] = as_bf16x8(*(const u32x4*)(kp + 32 * s));
     }
-    __syncthreads();                                          // s_lse is complete
+    __syncthreads();                                          // every wavefront has its fragments: the buffers are free
     if (niter > 0) {
         stash(0);
         if (niter > 1) fetch();
