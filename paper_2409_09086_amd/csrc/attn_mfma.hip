@@ -562,28 +562,30 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
     __syncthreads();
     for (int it = 0; it < niter; ++it) {
         const char* base = smem + (it & 1) * BUF;
-        // a row group takes two of the four blocks; the MFMAs of the second run under the exponentials of
-        // the first
-        f32x16 acc[2][CB];
+        // A row group takes two of the four blocks.  The fragments of both are requested up front, so that
+        // only the first product waits for LDS; each block is then formed (8*CB MFMAs) and weighed (exp2)
+        // in turn through one set of accumulators, and the other wavefront of the SIMD, a phase apart, has
+        // the matrix pipe while this one is in its exponentials.
+        bf16x8 qf[2][D / 16];
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
             const char* qp = base + (64 * rg + 32 * k + l32) * QP + 16 * hh;
 #pragma unroll
+            for (int s = 0; s < D / 16; ++s) qf[k][s] = as_bf16x8(*(const u32x4*)(qp + 32 * s));
+        }
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            f32x16 acc[CB];
+#pragma unroll
             for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[k][cb][i] = 0.f;
-            bf16x8 qf[D / 16];
-#pragma unroll
-            for (int s = 0; s < D / 16; ++s) qf[s] = as_bf16x8(*(const u32x4*)(qp + 32 * s));
+                for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
 #pragma unroll
             for (int s = 0; s < D / 16; ++s)
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb)
-                    acc[k][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[s], kf[cb][s], acc[k][cb], 0, 0, 0);
-        }
-        // lane (column, half hh) holds rows 8a + 4hh + e of a block in register 4a + e
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
+                    acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[k][s], kf[cb][s], acc[cb], 0, 0, 0);
+            // lane (column, half hh) holds rows 8a + 4hh + e of a block in register 4a + e
             const float* lp = (const float*)(base + QBYTES) + 64 * rg + 32 * k;
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
@@ -592,7 +594,14 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
                     for (int cb = 0; cb < CB; ++cb)
-                        part[cb][4 * a + e] += fast_exp2(__builtin_fmaf(acc[k][cb][4 * a + e], c, -ls[e]));
+                        part[cb][4 * a + e] += fast_exp2(__builtin_fmaf(acc[cb][4 * a + e], c, -ls[e]));
+            }
+            // One set of accumulators: block 1 is formed after block 0 is weighed.  The empty statement makes
+            // block 1's first operand depend on block 0's sums, which is what keeps the compiler from gathering
+            // all MFMAs first and all exponentials last.
+            if (k == 0) {
+                if constexpr (CB == 2) asm volatile("" : "+v"(part[0]), "+v"(part[1]), "+v"(qf[1][0]));
+                else asm volatile("" : "+v"(part[0]), "+v"(qf[1][0]));
             }
         }
         // the other buffer was last read one iteration ago, before the barrier that ended it
