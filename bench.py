@@ -70,7 +70,7 @@ def cpu_baseline(cfg, budget_seconds=12.0, policy="infmllm", rope_base=0.0):
     orc.load(K, V, pos, cfg.budget)                          # start from a full cache
     stream = ChunkStream(cfg, start_step=0) if cfg.ar_rho else ChunkStream(cfg, start_step=cfg.budget // cfg.chunk)
     tokens, steps, spent = 0, 0, 0.0
-    while spent < budget_seconds and steps < 32:
+    while spent < budget_seconds and steps < 48:
         q, k, v = [x.double().numpy() for x in next(stream)]
         t0 = time.perf_counter()
         orc.step(q, k, v)
