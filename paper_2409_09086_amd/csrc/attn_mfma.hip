@@ -481,7 +481,8 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
         toff[u] = (uint32_t)(rr[u] * Hq * D + (ch % CPR) * 8);
     }
     int fg = 0, fb = 0;                                       // (head in group, block in head) of the next block
-    auto fetch = [&]() {
+    // direct: take the rows' log-sum-exp from memory (before s_lse is complete)
+    auto fetch = [&](bool direct = false) {
         int gk[4], bk[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {                         // past the last block: fg == G
@@ -507,7 +508,7 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
             stl = __builtin_inff();                           // +inf: weight 0
             stl_idx = -1;
             if (g1 < G && i < L) {
-                if (lse_in_lds) stl_idx = g1 * lq + (i - (L - lq));
+                if (lse_in_lds && !direct) stl_idx = g1 * lq + (i - (L - lq));
                 else stl = row_lse(h * G + g1, i);
             }
         }
@@ -521,13 +522,14 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
         }
         if (tid < TROWS) *(float*)(base + QBYTES + tid * 4) = (stl_idx >= 0) ? s_lse[stl_idx] : stl;
     };
-    if (niter > 0) fetch();
+    if (niter > 0) fetch(true);
     // Key fragments: B operand of S = Q.K^T, lane (column l32, half hh) holds K[col][16s + 8hh .. +8).
     // Loaded in that layout straight from memory a wavefront touches 32 rows with every instruction; the
-    // workgroup's 128*CB key rows are therefore read once with whole-row (coalesced) loads into the query
-    // tile buffers, which are not in use yet, and the fragments are picked up from there.
+    // workgroup's 128*CB key rows are therefore read once with whole-row (coalesced) loads into an LDS
+    // region of their own and the fragments are picked up from there, behind the same barrier that
+    // publishes the first query blocks.
     constexpr int KROWS = 128 * CB, KLD = KROWS * CPR / 512;
-    static_assert(KROWS * QP <= 2 * BUF, "the key tile is staged in the query buffers");
+    __shared__ __attribute__((aligned(16))) char ktile[KROWS * QP];
     {
         u32x4 kt[KLD];
 #pragma unroll
@@ -543,23 +545,21 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
 #pragma unroll
         for (int u = 0; u < KLD; ++u) {
             const int ch = tid + u * 512;
-            *(u32x4*)(smem + (ch / CPR) * QP + (ch % CPR) * 16) = kt[u];
+            *(u32x4*)(ktile + (ch / CPR) * QP + (ch % CPR) * 16) = kt[u];
         }
     }
-    __syncthreads();                                          // key tile and s_lse are complete
+    if (niter > 0) {
+        stash(0);
+        if (niter > 1) fetch(true);
+    }
+    __syncthreads();                                          // key tile, first query blocks and s_lse are complete
     bf16x8 kf[CB][D / 16];
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
-        const char* kp = smem + (cg * 32 * CB + 32 * cb + l32) * QP + 16 * hh;
+        const char* kp = ktile + (cg * 32 * CB + 32 * cb + l32) * QP + 16 * hh;
 #pragma unroll
         for (int s = 0; s < D / 16; ++s) kf[cb][s] = as_bf16x8(*(const u32x4*)(kp + 32 * s));
     }
-    __syncthreads();                                          // every wavefront has its fragments: the buffers are free
-    if (niter > 0) {
-        stash(0);
-        if (niter > 1) fetch();
-    }
-    __syncthreads();
     for (int it = 0; it < niter; ++it) {
         const char* base = smem + (it & 1) * BUF;
         // A row group takes two of the four blocks.  The fragments of both are requested up front, so that
