@@ -230,7 +230,7 @@ hipError_t launch_decode(const Geometry& g, const CacheView& c, const void* q, c
                          int64_t T, void* out, float* part, int max_split, hipStream_t st)
 {
     const int n = t + 1;
-    int nsplit = 1024 / g.Hkv;                          // ~1024 workgroups ...
+    int nsplit = 256 / g.Hkv;                           // one workgroup per CU (more only add partials to merge) ...
     if (nsplit > n / 128) nsplit = n / 128;             // ... of at least 128 keys each
     if (nsplit > max_split) nsplit = max_split;
     if (nsplit < 1) nsplit = 1;
