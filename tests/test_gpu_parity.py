@@ -99,6 +99,35 @@ def test_full_shape_streams_lockstep(name, steps):
     print("%s: max err %.3g swaps %d" % (name, ls.max_err, ls.swaps), flush=True)
 
 
+@pytest.mark.parametrize("name,steps", [("cfg2", 30), ("cfg3", 12), ("cfg4", 30), ("cfg5", 12)])
+def test_retained_list_is_the_top_r_of_the_reported_scores(name, steps):
+    """A property that holds at any size, checked at the real shapes over many steps without the oracle: the
+    list a step reports is exactly Alg. 1 l.5-7 applied to the scores W' the library itself reports for that
+    step (r largest, ties to the newer row, ascending, then the recent window).  This isolates the selection
+    kernel (two, four and eight candidates per thread at these shapes) from the precision of the scores."""
+    cfg = CONFIGS[name]
+    gpu = B.Stream(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, dtype=DT[cfg.dtype], bias=cfg.bias,
+                   max_chunk=cfg.max_chunk)
+    r = cfg.budget - cfg.recent
+    checked = 0
+    for step, (q, k, v) in zip(range(steps), ChunkStream(cfg)):
+        n = len(gpu) + q.shape[0]
+        _, ret, cnt = gpu.step(q.cuda(), k.cuda(), v.cuda())
+        if n <= cfg.budget:
+            continue
+        w = gpu.last_scores().cpu().numpy()                           # [kv_heads, c], fp32 as ranked
+        I = ret.cpu().numpy()[:, : int(cnt.item())]
+        c = n - cfg.recent
+        assert w.shape == (cfg.kv_heads, c)
+        for h in range(cfg.kv_heads):
+            order = np.lexsort((-np.arange(c), -w[h].astype(np.float64)))   # by score descending, then newer first
+            assert (I[h, :r] == np.sort(order[:r])).all(), (name, step, h)
+            assert (I[h, r:] == np.arange(c, n)).all()
+        checked += 1
+    assert checked >= steps // 2
+    print("%s: %d evicting steps checked" % (name, checked), flush=True)
+
+
 @pytest.mark.parametrize("name,skip,steps", [("cfg2", 40, 3), ("cfg4", 25, 5), ("cfg5", 47, 3)])
 def test_late_steps_spot_check(name, skip, steps):
     """Steps far into a stream, which the oracle cannot reach on its own: the GPU runs `skip`
