@@ -103,15 +103,19 @@ def test_full_shape_streams_lockstep(name, steps):
 def test_retained_list_is_the_top_r_of_the_reported_scores(name, steps):
     """A property that holds at any size, checked at the real shapes over many steps without the oracle: the
     list a step reports is exactly Alg. 1 l.5-7 applied to the scores W' the library itself reports for that
-    step (r largest, ties to the newer row, ascending, then the recent window).  This isolates the selection
-    kernel (two, four and eight candidates per thread at these shapes) from the precision of the scores."""
+    step (r largest, ties to the newer row, ascending, then the recent window), and the cache after the step is
+    the cache before it followed by the chunk, gathered by that list (Alg. 1 l.8), bit for bit.  This isolates
+    the selection kernel (two, four and eight candidates per thread at these shapes) and the gather from the
+    precision of the scores."""
     cfg = CONFIGS[name]
     gpu = B.Stream(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, dtype=DT[cfg.dtype], bias=cfg.bias,
                    max_chunk=cfg.max_chunk)
     r = cfg.budget - cfg.recent
     checked = 0
     for step, (q, k, v) in zip(range(steps), ChunkStream(cfg)):
-        n = len(gpu) + q.shape[0]
+        t, T = len(gpu), gpu.streamed
+        n = t + q.shape[0]
+        K0, V0, pos0, _ = gpu.export()
         _, ret, cnt = gpu.step(q.cuda(), k.cuda(), v.cuda())
         if n <= cfg.budget:
             continue
@@ -123,6 +127,15 @@ def test_retained_list_is_the_top_r_of_the_reported_scores(name, steps):
             order = np.lexsort((-np.arange(c), -w[h].astype(np.float64)))   # by score descending, then newer first
             assert (I[h, :r] == np.sort(order[:r])).all(), (name, step, h)
             assert (I[h, r:] == np.arange(c, n)).all()
+        # Alg. 1 l.8: the new cache is the old cache followed by the chunk, gathered by that list, bit for bit
+        K1, V1, pos1, _ = gpu.export()
+        Kall = torch.cat([K0, k.cuda().permute(1, 0, 2)], dim=1)
+        Vall = torch.cat([V0, v.cuda().permute(1, 0, 2)], dim=1)
+        pall = torch.cat([pos0, torch.arange(T, T + q.shape[0], dtype=torch.int32, device="cuda").repeat(cfg.kv_heads, 1)], dim=1)
+        idx = ret[:, : int(cnt.item())].long()
+        assert torch.equal(K1, torch.gather(Kall, 1, idx[:, :, None].expand(-1, -1, cfg.head_dim)))
+        assert torch.equal(V1, torch.gather(Vall, 1, idx[:, :, None].expand(-1, -1, cfg.head_dim)))
+        assert torch.equal(pos1, torch.gather(pall, 1, idx))
         checked += 1
     assert checked >= steps // 2
     print("%s: %d evicting steps checked" % (name, checked), flush=True)
