@@ -100,13 +100,14 @@ def test_full_shape_streams_lockstep(name, steps):
 
 
 @pytest.mark.parametrize("name,steps", [("cfg2", 30), ("cfg3", 12), ("cfg4", 30), ("cfg5", 12)])
-def test_retained_list_is_the_top_r_of_the_reported_scores(name, steps):
+def test_step_properties_at_the_real_shapes(name, steps):
     """A property that holds at any size, checked at the real shapes over many steps without the oracle: the
     list a step reports is exactly Alg. 1 l.5-7 applied to the scores W' the library itself reports for that
     step (r largest, ties to the newer row, ascending, then the recent window), and the cache after the step is
     the cache before it followed by the chunk, gathered by that list (Alg. 1 l.8), bit for bit.  This isolates
     the selection kernel (two, four and eight candidates per thread at these shapes) and the gather from the
-    precision of the scores."""
+    precision of the scores.  Every fourth step the chunk's output is also compared with torch's fp32 arithmetic
+    on the same cache and chunk (2e-2)."""
     cfg = CONFIGS[name]
     gpu = B.Stream(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, dtype=DT[cfg.dtype], bias=cfg.bias,
                    max_chunk=cfg.max_chunk)
@@ -116,7 +117,7 @@ def test_retained_list_is_the_top_r_of_the_reported_scores(name, steps):
         t, T = len(gpu), gpu.streamed
         n = t + q.shape[0]
         K0, V0, pos0, _ = gpu.export()
-        _, ret, cnt = gpu.step(q.cuda(), k.cuda(), v.cuda())
+        out_g, ret, cnt = gpu.step(q.cuda(), k.cuda(), v.cuda())
         if n <= cfg.budget:
             continue
         w = gpu.last_scores().cpu().numpy()                           # [kv_heads, c], fp32 as ranked
@@ -129,6 +130,17 @@ def test_retained_list_is_the_top_r_of_the_reported_scores(name, steps):
             assert (I[h, r:] == np.arange(c, n)).all()
         # Alg. 1 l.8: the new cache is the old cache followed by the chunk, gathered by that list, bit for bit
         K1, V1, pos1, _ = gpu.export()
+        if step % 4 == 0:
+            # Sec. 3.2: the chunk's output against torch's own fp32 arithmetic on the same cache and chunk
+            G = cfg.heads // cfg.kv_heads
+            Kf = torch.cat([K0, k.cuda().permute(1, 0, 2)], dim=1).float().repeat_interleave(G, dim=0)   # [Hq, n, d]
+            Vf = torch.cat([V0, v.cuda().permute(1, 0, 2)], dim=1).float().repeat_interleave(G, dim=0)
+            s_ = torch.einsum("lhd,hnd->hln", q.cuda().float(), Kf) / np.sqrt(cfg.head_dim)
+            L_ = q.shape[0]
+            vis = torch.arange(n, device="cuda")[None, :] <= (t + torch.arange(L_, device="cuda"))[:, None]
+            ref = torch.einsum("hln,hnd->lhd", torch.softmax(s_.masked_fill(~vis[None], float("-inf")), dim=-1), Vf)
+            err = float((out_g.float() - ref).abs().max())
+            assert err <= 2e-2, (name, step, err)
         Kall = torch.cat([K0, k.cuda().permute(1, 0, 2)], dim=1)
         Vall = torch.cat([V0, v.cuda().permute(1, 0, 2)], dim=1)
         pall = torch.cat([pos0, torch.arange(T, T + q.shape[0], dtype=torch.int32, device="cuda").repeat(cfg.kv_heads, 1)], dim=1)
