@@ -90,7 +90,7 @@ struct infmllm_stream {
     }
 
     struct Layout {
-        size_t K[2], V[2], pos[2], score[2], lse, Wb, I, part_o, part_ml, dec_part, K_rot, kc_rot, q_rot, rope_tab, total;
+        size_t K[2], V[2], pos[2], score[2], lse, Wb, I, part_o, part_ml, score_part, dec_part, K_rot, kc_rot, q_rot, rope_tab, total;
         size_t part_rows;
     };
     Layout layout() const
@@ -113,6 +113,8 @@ struct infmllm_stream {
         L.part_rows = (g.elt == 2 && g.d == 128) ? (size_t)4 * (g.max_chunk < 4096 ? g.max_chunk : 4096) : 0;
         L.part_o = off; off += up(L.part_rows * g.Hq * g.d * 4);
         L.part_ml = off; off += up(L.part_rows * g.Hq * 2 * 4);
+        // row-split scoring (bf16 streams): partial column sums and arrival counters
+        L.score_part = off; off += up(g.elt == 2 ? (size_t)SCORE_SPLIT_WGS * (256 + 1) * 4 : 0);
         L.dec_part = off; off += up(g.max_decode > 0 ? (size_t)g.Hq * DECODE_MAX_SPLIT * (g.d + 2) * 4 + (size_t)g.Hkv * 4 : 0);
         const bool rope = rope_base > 0.0;
         L.K_rot = off; off += rope ? kv : 0;
@@ -241,6 +243,7 @@ int infmllm_stream_attach(infmllm_stream_t* s, void* ws, size_t bytes, void* hip
     s->fwd.part_o = (float*)(base + L.part_o);
     s->fwd.part_ml = (float*)(base + L.part_ml);
     s->fwd.part_rows = L.part_rows;
+    s->fwd.score_part = (float*)(base + L.score_part);
     s->dec_part = (float*)(base + L.dec_part);
     s->K_rot = base + L.K_rot;
     s->kc_rot = base + L.kc_rot;

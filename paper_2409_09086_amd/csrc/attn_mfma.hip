@@ -408,7 +408,7 @@ __global__ void __launch_bounds__(512)
 score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ kc, int tc,
              const float* __restrict__ lse2, const float* __restrict__ part_ml, int nsplit,
              const float* __restrict__ carry, float* __restrict__ Wb, int L, int lq, int Hq, int Hkv, int G, int cap, int max_chunk, int cnd,
-             int nxb, float c, float bias)
+             int nxb, float c, float bias, int rsplit, float* __restrict__ spart)
 {
     constexpr int QP = D * 2 + 16;                            // pitch of a staged query row
     constexpr int CPR = D / 8;
@@ -420,23 +420,28 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
     __shared__ __attribute__((aligned(16))) char smem[2 * BUF];
     __shared__ float s_part[4 * CB * 32];
     __shared__ float s_lse[LSE_ROWS];
+    __shared__ int s_ticket;
 
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: what depends on it stays scalar
     const int cg = wave & 3, rg = wave >> 2;                  // column group, row group
     // all column blocks of a kv-head get workgroup ids of one residue class mod 8, i.e. one XCD,
     // so that the head's scored queries are fetched into one L2 only
-    int h, bx;
+    // With rsplit > 1 the scored rows of a column block are shared out over rsplit workgroups (slice rs).
+    int h, bx, rs;
     {
-        const int bid = blockIdx.x;
+        const int bid = blockIdx.x, per_head = nxb * rsplit;
+        int rem;
         if ((Hkv & 7) == 0) {
             const int xcd = bid & 7, li = bid >> 3;
-            h = xcd + 8 * (li / nxb);
-            bx = li % nxb;
+            h = xcd + 8 * (li / per_head);
+            rem = li % per_head;
         } else {
-            h = bid / nxb;
-            bx = bid % nxb;
+            h = bid / per_head;
+            rem = bid % per_head;
         }
+        bx = rem % nxb;
+        rs = rem / nxb;
     }
     const int col0 = bx * (128 * CB) + cg * (32 * CB);
 
@@ -448,7 +453,9 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
 
     const int nblk = (lq + 31) / 32;                          // 32-row blocks per query head
     const int total = G * nblk;                               // blocks to sweep, four per iteration
-    const int niter = (total + 3) / 4;
+    const int niter_all = (total + 3) / 4;
+    const int it_first = (int)((long)rs * niter_all / rsplit);               // this workgroup's iterations
+    const int niter = (int)((long)(rs + 1) * niter_all / rsplit) - it_first;
     // Row log-sum-exp of every scored row of the group, once per workgroup: row (gg, i) -> s_lse[gg*lq + i].
     // After a key-split attention launch it is derived from the partials: max m + log2(sum_s l_s 2^(m_s - max m)).
     auto row_lse = [&](int g, int i) -> float {
@@ -480,7 +487,8 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
         rr[u] = r & 31;
         toff[u] = (uint32_t)(rr[u] * Hq * D + (ch % CPR) * 8);
     }
-    int fg = 0, fb = 0;                                       // (head in group, block in head) of the next block
+    // (head in group, block in head) of the next block
+    int fg = (4 * it_first) / nblk, fb = (4 * it_first) % nblk;
     // direct: take the rows' log-sum-exp from memory (before s_lse is complete)
     auto fetch = [&](bool direct = false) {
         int gk[4], bk[4];
@@ -620,6 +628,26 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
         if (rg == 1 && hh == 0) s_part[(cg * CB + cb) * 32 + l32] = sum[cb];
     }
     __syncthreads();
+    // Row-split launch: every workgroup puts its raw column sums where the other slices' workgroups can read
+    // them (agent-scope stores go through to memory), waits until they have left, and takes a ticket; the one
+    // that arrives last adds the slices up and finishes the columns.  No workgroup waits for another one.
+    float* my_part = nullptr;
+    if (rsplit > 1) {
+        my_part = spart + ((size_t)(h * rsplit + rs) * nxb + bx) * 256;
+        if (rg == 0 && hh == 0) {
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+                __hip_atomic_store(my_part + cg * 32 * CB + 32 * cb + l32, sum[cb] + s_part[(cg * CB + cb) * 32 + l32],
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        int* arrived = (int*)(spart + (size_t)SCORE_SPLIT_WGS * 256) + h * nxb + bx;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) s_ticket = __hip_atomic_fetch_add(arrived, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (s_ticket != rsplit - 1) return;
+        if (tid == 0) __hip_atomic_store(arrived, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
+    }
     if (rg == 0 && hh == 0) {
         const float norm = (lq > 0) ? 1.0f / (float)(G * lq) : 0.f;
         const float dstep = bias / (float)cnd;                // Alg. 1 l.2
@@ -627,7 +655,14 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
         for (int cb = 0; cb < CB; ++cb) {
             const int col = col0 + 32 * cb + l32;
             if (col < cnd) {
-                const float tot = sum[cb] + s_part[(cg * CB + cb) * 32 + l32];
+                float tot = sum[cb] + s_part[(cg * CB + cb) * 32 + l32];
+                if (rsplit > 1) {
+                    // fixed order over the slices, whichever workgroup does the adding
+                    tot = 0.f;
+                    for (int sp = 0; sp < rsplit; ++sp)
+                        tot += __hip_atomic_load(my_part + (sp - rs) * nxb * 256 + cg * 32 * CB + 32 * cb + l32,
+                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
                 float w = tot * norm - (float)(cnd - 1 - col) * dstep;                     // Alg. 1 l.1, l.3-4
                 if (carry) {
                     // cumulative policy: this step's S on top of what the row has gathered, no bias; the
@@ -736,16 +771,28 @@ hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySou
     const int n = t + L, cnd = n - g.R, lq = g.R < L ? g.R : L;
     if (cnd <= 0) return hipSuccess;
     const float cc = g.scale * LOG2E;
-    // 256 columns per workgroup unless that leaves CUs without one
-    const bool wide = (long)((cnd + 255) / 256) * g.Hkv >= 200;
-    const int nxb = wide ? (cnd + 255) / 256 : (cnd + 127) / 128;
-    const dim3 grid(nxb * g.Hkv), block(512);
+    // 256 columns per workgroup.  Where that leaves CUs without one, the scored rows of a column block are
+    // shared out over up to four workgroups (whose sums the last to finish adds up); where there are too few
+    // rows for that, a workgroup takes 128 columns.
+    const int nx256 = (cnd + 255) / 256;
+    const long wgs256 = (long)nx256 * g.Hkv;
+    const int niter = (g.G * ((lq + 31) / 32) + 3) / 4;       // iterations of the kernel's row loop
+    int rsplit = 1;
+    if (wgs256 < 200) {
+        rsplit = (int)(256 / wgs256);
+        if (rsplit > 4) rsplit = 4;
+        if (rsplit > niter / 2) rsplit = niter / 2;
+        if (rsplit < 1 || !sc.score_part || wgs256 * rsplit > SCORE_SPLIT_WGS) rsplit = 1;
+    }
+    const bool wide = wgs256 >= 200 || rsplit > 1;
+    const int nxb = wide ? nx256 : (cnd + 127) / 128;
+    const dim3 grid(nxb * g.Hkv * rsplit), block(512);
 #define INFMLLM_SCORE(DD, CB)                                                                              \
     hipLaunchKernelGGL((score_kernel<DD, CB>), grid, block, 0, st, (const uint16_t*)q, (const uint16_t*)c.K, \
                        (const uint16_t*)ks.k, ks.rows, lse, sc.part_ml, nsplit,                              \
                        g.policy == POLICY_CUMULATIVE ? c.score : nullptr, Wb, L, lq, g.Hq, g.Hkv, g.G, g.cap, \
                        g.max_chunk,                                                                          \
-                       cnd, nxb, cc, g.bias)
+                       cnd, nxb, cc, g.bias, rsplit, sc.score_part)
     if (g.d == 128 && wide) INFMLLM_SCORE(128, 2);
     else if (g.d == 128) INFMLLM_SCORE(128, 1);
     else if (g.d == 64 && wide) INFMLLM_SCORE(64, 2);

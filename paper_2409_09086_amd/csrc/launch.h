@@ -57,7 +57,12 @@ struct FwdScratch {
     float* part_o;
     float* part_ml;
     size_t part_rows;     // split * rows the buffers can hold
+    // Row-split scoring: raw column sums of each split, [SCORE_SPLIT_WGS][256] fp32, followed by one
+    // arrival counter per (kv-head, column block), [SCORE_SPLIT_WGS] int32, zero between launches.
+    float* score_part;
 };
+// most workgroups a row-split scoring launch may have
+constexpr int SCORE_SPLIT_WGS = 512;
 
 // Where the keys and values of a step live.  Rows below `rows` come from the cache; rows from
 // `rows` on are taken straight from the chunk tensors k, v ([L][Hkv][d]) as chunk row j - rows.

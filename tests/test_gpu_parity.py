@@ -52,6 +52,9 @@ def test_cfg1_tiny_fp32_stream(bias):
     (4, 2, 128, 96, 32, [150, 40, 150, 1, 97]),                     # chunks longer than the budget: the first step evicts
     (2, 2, 64, 24, 8, [40, 3, 17, 24, 5]),                          # budget below one 32-row tile
     (2, 1, 128, 40, 40, [64, 9]),                                   # r = 0 and chunk > budget
+    (8, 2, 128, 256, 128, [128, 128, 128, 128]),                    # scored rows shared out over 2 workgroups
+    (4, 1, 128, 384, 192, [192, 192, 192, 101, 192]),               # ... over 3
+    (16, 2, 64, 320, 160, [160, 160, 160, 45, 160]),                # ... over 4, uneven shares, ragged last block
 ])
 def test_small_bf16_streams(impl, heads, kv, d, budget, recent, chunks):
     ls = pair(budget, recent, heads, kv, d, "bf16", 1e-3, max_chunk=max(chunks), impl=impl)
