@@ -252,15 +252,17 @@ int infmllm_stream_attach(infmllm_stream_t* s, void* ws, size_t bytes, void* hip
     s->rot_rows = 0;
     if (s->rope_base > 0.0) {
         // (cos, sin) of p * base^(-2i/d) in fp64 for every cache position p and pair i; the copy is finished
-        // before this function returns (the host buffer is pageable and goes out of scope)
-        const int half = s->g.d / 2;
+        // before this function returns (the host buffer is pageable and goes out of scope).  Within a position
+        // pair i = 8a + e sits in slot e * (d/16) + a (see launch_rope).
+        const int half = s->g.d / 2, groups = s->g.d / 16;
         std::vector<double> tab((size_t)s->g.cap * half * 2);
         for (int i = 0; i < half; ++i) {
             const double inv = std::pow(s->rope_base, -2.0 * (double)i / (double)s->g.d);
+            const int slot = (i % 8) * groups + i / 8;
             for (int p = 0; p < s->g.cap; ++p) {
                 const double ang = (double)p * inv;
-                tab[((size_t)p * half + i) * 2] = std::cos(ang);
-                tab[((size_t)p * half + i) * 2 + 1] = std::sin(ang);
+                tab[((size_t)p * half + slot) * 2] = std::cos(ang);
+                tab[((size_t)p * half + slot) * 2 + 1] = std::sin(ang);
             }
         }
         hipError_t e = hipMemcpyAsync(s->rope_tab, tab.data(), tab.size() * sizeof(double), hipMemcpyHostToDevice,

@@ -128,7 +128,8 @@ hipError_t launch_rank_scores(const Geometry& g, float* Wb, int cnd, float sign,
 
 // Cache-relative rotary encoding pre-pass: Krot[h][j] <- K[h][j] turned to position j for j in [j0, j1);
 // kcrot[i][h] <- kc[i][h] and qrot[i][h] <- q[i][h] turned to position t + i for i < L (kc and q may each
-// be null).  tab = [cap][d/2] pairs (cos, sin) of doubles.
+// be null).  tab = [cap][d/2] pairs (cos, sin) of doubles; within a position, the entry of pair 8a + e is at
+// index e * (d/16) + a, so that the threads of a row (one per a) read consecutive entries.
 hipError_t launch_rope(const Geometry& g, const void* K, void* Krot, int j0, int j1, const void* kc, void* kcrot,
                        const void* q, void* qrot, int t, int L, const double* tab, hipStream_t st);
 

@@ -30,12 +30,13 @@ template <> struct Oct<uint16_t> {
         const uint32_t w = raw[e >> 1];
         return (double)__uint_as_float((e & 1) ? (w & 0xffff0000u) : (w << 16));
     }
-    __device__ __forceinline__ void set(int e, double v)
+    // elements 2w and 2w + 1 at once; each is rounded to nearest even twice: to fp32, then to bf16
+    __device__ __forceinline__ void set2(int w, double v0, double v1)
     {
-        uint32_t u = __float_as_uint((float)v);               // round to nearest even, twice: fp32 then bf16
-        u += 0x7fffu + ((u >> 16) & 1u);
-        u >>= 16;
-        raw[e >> 1] = (e & 1) ? ((raw[e >> 1] & 0x0000ffffu) | (u << 16)) : ((raw[e >> 1] & 0xffff0000u) | u);
+        uint32_t u0 = __float_as_uint((float)v0), u1 = __float_as_uint((float)v1);
+        u0 += 0x7fffu + ((u0 >> 16) & 1u);
+        u1 += 0x7fffu + ((u1 >> 16) & 1u);
+        raw[w] = (u0 >> 16) | (u1 & 0xffff0000u);
     }
 };
 template <> struct Oct<float> {
@@ -43,7 +44,11 @@ template <> struct Oct<float> {
     __device__ __forceinline__ void load(const float* p) { lo = *(const f32x4*)p; hi = *(const f32x4*)(p + 4); }
     __device__ __forceinline__ void store(float* p) const { *(f32x4*)p = lo; *(f32x4*)(p + 4) = hi; }
     __device__ __forceinline__ double get(int e) const { return (double)(e < 4 ? lo[e & 3] : hi[e & 3]); }
-    __device__ __forceinline__ void set(int e, double v) { if (e < 4) lo[e & 3] = (float)v; else hi[e & 3] = (float)v; }
+    __device__ __forceinline__ void set2(int w, double v0, double v1)
+    {
+        if (w < 2) { lo[2 * w] = (float)v0; lo[2 * w + 1] = (float)v1; }
+        else { hi[2 * w - 4] = (float)v0; hi[2 * w - 3] = (float)v1; }
+    }
 };
 
 // One thread = one (row, group of 8 pairs, group of HPT heads): the table entries are loaded once and the
@@ -79,23 +84,38 @@ rope_kernel(const T* __restrict__ K, T* __restrict__ Krot, int j0, int j1, int c
     double cs[8], sn[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        const double2 v = tab[(long)pos * (D / 2) + 8 * cc + e];
+        const double2 v = tab[(long)pos * (D / 2) + e * GPR + cc];   // lanes of a row read consecutive entries
         cs[e] = v.x; sn[e] = v.y;
     }
     const int h0 = blockIdx.y * ROPE_HPT, h1 = min(heads, h0 + ROPE_HPT);
-    for (int h = h0; h < h1; ++h) {
-        Oct<T> a, b;                                          // x[8cc .. 8cc+8) and x[d/2 + 8cc .. +8)
-        a.load(src + h * hstride + 8 * cc);
-        b.load(src + h * hstride + D / 2 + 8 * cc);
-        Oct<T> ra = a, rb = b;
+    auto turn = [&](const Oct<T>& a, const Oct<T>& b, T* out) {
+        Oct<T> ra, rb;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const double x = a.get(e), y = b.get(e);
-            ra.set(e, x * cs[e] - y * sn[e]);
-            rb.set(e, y * cs[e] + x * sn[e]);
+        for (int w = 0; w < 4; ++w) {
+            const double x0 = a.get(2 * w), y0 = b.get(2 * w), x1 = a.get(2 * w + 1), y1 = b.get(2 * w + 1);
+            ra.set2(w, x0 * cs[2 * w] - y0 * sn[2 * w], x1 * cs[2 * w + 1] - y1 * sn[2 * w + 1]);
+            rb.set2(w, y0 * cs[2 * w] + x0 * sn[2 * w], y1 * cs[2 * w + 1] + x1 * sn[2 * w + 1]);
         }
-        ra.store(dst + h * hstride + 8 * cc);
-        rb.store(dst + h * hstride + D / 2 + 8 * cc);
+        ra.store(out + 8 * cc);
+        rb.store(out + D / 2 + 8 * cc);
+    };
+    if (h1 - h0 == ROPE_HPT) {
+        // a full group of heads: every load is requested before the first value is used
+        Oct<T> a[ROPE_HPT], b[ROPE_HPT];                      // x[8cc .. 8cc+8) and x[d/2 + 8cc .. +8)
+#pragma unroll
+        for (int u = 0; u < ROPE_HPT; ++u) {
+            a[u].load(src + (h0 + u) * hstride + 8 * cc);
+            b[u].load(src + (h0 + u) * hstride + D / 2 + 8 * cc);
+        }
+#pragma unroll
+        for (int u = 0; u < ROPE_HPT; ++u) turn(a[u], b[u], dst + (h0 + u) * hstride);
+    } else {
+        for (int h = h0; h < h1; ++h) {
+            Oct<T> a, b;
+            a.load(src + h * hstride + 8 * cc);
+            b.load(src + h * hstride + D / 2 + 8 * cc);
+            turn(a, b, dst + h * hstride);
+        }
     }
 }
 
