@@ -42,6 +42,7 @@ def batched_step(ls, chunks):
     (2, 4, 2, 64, "bf16", 96, 96, [32, 64, 50, 50]),                  # r = 0
     (3, 4, 4, 64, "fp32", 128, 32, [64, 64, 40, 64]),
     (18, 2, 2, 64, "bf16", 96, 32, [48, 48, 48, 30]),                 # more streams than one launch takes
+    (2, 16, 2, 64, "bf16", 320, 160, [160, 160, 160, 45, 160]),       # scoring shares its rows out over workgroups
 ])
 def test_batched_eviction_matches_oracle(n_layers, heads, kv, d, dtype, budget, recent, lens):
     ls = layers(n_layers, budget, recent, heads, kv, d, dtype, 1e-3, max(lens))

@@ -36,6 +36,7 @@ SHAPES = [
     (8, 2, 128, "bf16", 1, 160, 48, [100, 37, 64, 1, 129, 77]),
     (4, 2, 64, "bf16", 0, 128, 0, [64, 64, 64, 64]),
     (4, 4, 64, "fp32", None, 128, 32, [64, 64, 40, 64, 64]),
+    (8, 2, 128, "bf16", 0, 256, 128, [128, 128, 128, 128, 128]),      # scoring shares its rows out over workgroups
 ]
 
 
