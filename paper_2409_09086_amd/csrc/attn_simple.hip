@@ -8,24 +8,35 @@
 //                  chunk's own keys.  One workgroup per (query row, query head): logits into
 //                  LDS, block softmax, then P.V with lanes along head_dim.  Also writes the
 //                  row's log-sum-exp, which the scoring kernel needs.
-//   score_simple : Alg. 1 l.1-4 -- every thread owns one candidate key column (its key row
-//                  lives in registers), sweeps the scored query rows and sums the exact
-//                  softmax weights exp(s - lse); mean over rows and group heads, plus the bias
-//                  ramp.  Column sums are complete inside a thread, so the result does not
-//                  depend on any reduction order across workgroups.
+//   score_simple : Alg. 1 l.1-4 -- a thread owns one candidate key column (its key row lives in
+//                  registers) and a quarter of the scored query rows, and sums the exact softmax
+//                  weights exp(s - lse); the four quarters are added in a fixed order, then mean
+//                  over rows and group heads, plus the bias ramp.  Column sums are complete
+//                  inside a workgroup, so the result does not depend on any order across
+//                  workgroups.
 #include "launch.h"
 
 namespace infmllm {
 
 namespace {
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
 template <typename T> struct Elt;
 template <> struct Elt<float> {
     static __device__ __forceinline__ float load(const float* p) { return *p; }
+    static __device__ __forceinline__ f32x4 load4(const float* p) { return *(const f32x4*)p; }   // p 16-byte aligned
     static __device__ __forceinline__ void store(float* p, float x) { *p = x; }
 };
 template <> struct Elt<uint16_t> {   // bf16 held as raw bits
     static __device__ __forceinline__ float load(const uint16_t* p) { return __uint_as_float((uint32_t)(*p) << 16); }
+    static __device__ __forceinline__ f32x4 load4(const uint16_t* p)                              // p 8-byte aligned
+    {
+        const u32x2 w = *(const u32x2*)p;
+        return f32x4{__uint_as_float(w[0] << 16), __uint_as_float(w[0] & 0xffff0000u), __uint_as_float(w[1] << 16),
+                     __uint_as_float(w[1] & 0xffff0000u)};
+    }
     static __device__ __forceinline__ void store(uint16_t* p, float x)
     {
         uint32_t u = __float_as_uint(x);
@@ -69,7 +80,7 @@ attn_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const T* __
     extern __shared__ float p[];                 // [vis]
     __shared__ float qs[D];
     __shared__ float red[4];
-    __shared__ float part[256];
+    __shared__ __attribute__((aligned(16))) float part[1024];   // [256 / (D/4)][D]
 
     const int i = blockIdx.x, g = blockIdx.y, h = g / G;
     const int vis = t + i + 1;                   // columns 0 .. t+i are visible
@@ -83,8 +94,14 @@ attn_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const T* __
     for (int j = threadIdx.x; j < vis; j += 256) {
         const T* kj = Kh + (size_t)j * D;
         float acc = 0.f;
-#pragma unroll 8
-        for (int x = 0; x < D; ++x) acc = fmaf(qs[x], Elt<T>::load(kj + x), acc);
+#pragma unroll 4
+        for (int x = 0; x < D; x += 4) {
+            const f32x4 kv = Elt<T>::load4(kj + x);
+            acc = fmaf(qs[x], kv[0], acc);
+            acc = fmaf(qs[x + 1], kv[1], acc);
+            acc = fmaf(qs[x + 2], kv[2], acc);
+            acc = fmaf(qs[x + 3], kv[3], acc);
+        }
         acc *= scale;
         p[j] = acc;
         mx = fmaxf(mx, acc);
@@ -99,11 +116,18 @@ attn_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const T* __
     sum = block_reduce_sum(sum, red);            // its barriers also publish p[]
     const float inv = 1.0f / sum;
 
-    constexpr int NG = 256 / D;                  // groups of lanes along the key axis
-    const int x = threadIdx.x % D, grp = threadIdx.x / D;
-    float acc = 0.f;
-    for (int j = grp; j < vis; j += NG) acc = fmaf(p[j], Elt<T>::load(Vh + (size_t)j * D + x), acc);
-    part[threadIdx.x] = acc;
+    constexpr int LPR = D / 4, NG = 256 / LPR;   // lanes along a value row (four columns each), groups along the keys
+    const int x4 = 4 * (threadIdx.x % LPR), grp = threadIdx.x / LPR;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int j = grp; j < vis; j += NG) {
+        const f32x4 vv = Elt<T>::load4(Vh + (size_t)j * D + x4);
+        const float w = p[j];
+        acc[0] = fmaf(w, vv[0], acc[0]);
+        acc[1] = fmaf(w, vv[1], acc[1]);
+        acc[2] = fmaf(w, vv[2], acc[2]);
+        acc[3] = fmaf(w, vv[3], acc[3]);
+    }
+    *(f32x4*)(part + grp * D + x4) = acc;
     __syncthreads();
     if (threadIdx.x < D) {
         float o = 0.f;
@@ -114,25 +138,32 @@ attn_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const T* __
     if (threadIdx.x == 0) lse[(size_t)g * max_chunk + i] = mx + logf(sum);
 }
 
-// grid (ceil(cnd/128), Hkv), 128 threads.  Thread = candidate column j.
+// grid (ceil(cnd/64), Hkv), 256 threads = 64 candidate columns x 4 slices of the scored rows (a slice is a
+// wavefront).  Thread = (column j, slice): the key row lives in registers, the thread sums the weights of
+// every fourth scored row, and the four slices are added in slice order.
 template <typename T, int D>
-__global__ void __launch_bounds__(128)
+__global__ void __launch_bounds__(256)
 score_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const float* __restrict__ lse,
                     const float* __restrict__ carry, float* __restrict__ Wb, int L, int lq, int Hq, int G, int cap,
                     int max_chunk, int cnd, float scale, float bias)
 {
-    constexpr int RT = 16;                       // query rows staged per round
-    __shared__ float qs[RT][D];
+    constexpr int RT = 16, NS = 4;               // query rows staged per round, row slices
+    __shared__ __attribute__((aligned(16))) float qs[RT][D];
     __shared__ float ls[RT];
+    __shared__ float red[NS][64];
 
     const int h = blockIdx.y;
-    const int j = blockIdx.x * 128 + threadIdx.x;
+    const int col = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const int j = blockIdx.x * 64 + col;
     const bool live = j < cnd;
     float kr[D];
     {
         const T* kj = K + ((size_t)h * cap + (live ? j : 0)) * D;
 #pragma unroll
-        for (int x = 0; x < D; ++x) kr[x] = Elt<T>::load(kj + x);
+        for (int x = 0; x < D; x += 4) {
+            const f32x4 kv = Elt<T>::load4(kj + x);
+            kr[x] = kv[0]; kr[x + 1] = kv[1]; kr[x + 2] = kv[2]; kr[x + 3] = kv[3];
+        }
     }
     float acc = 0.f;
     for (int gg = 0; gg < G; ++gg) {
@@ -140,13 +171,13 @@ score_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const floa
         for (int i0 = L - lq; i0 < L; i0 += RT) {
             const int rows = min(RT, L - i0);
             __syncthreads();
-            for (int e = threadIdx.x; e < rows * D; e += 128) {
-                const int r = e / D, x = e - r * D;
-                qs[r][x] = Elt<T>::load(q + ((size_t)(i0 + r) * Hq + g) * D + x);
+            for (int e = threadIdx.x; e < rows * (D / 4); e += 256) {
+                const int r = e / (D / 4), x = 4 * (e - r * (D / 4));
+                *(f32x4*)&qs[r][x] = Elt<T>::load4(q + ((size_t)(i0 + r) * Hq + g) * D + x);
             }
             if (threadIdx.x < rows) ls[threadIdx.x] = lse[(size_t)g * max_chunk + i0 + threadIdx.x];
             __syncthreads();
-            for (int r = 0; r < rows; ++r) {
+            for (int r = slice; r < rows; r += NS) {
                 float s = 0.f;
 #pragma unroll
                 for (int x = 0; x < D; ++x) s = fmaf(qs[r][x], kr[x], s);
@@ -154,8 +185,11 @@ score_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const floa
             }
         }
     }
-    if (live) {
-        const float S = (lq > 0) ? acc / (float)(G * lq) : 0.f;        // Alg. 1 l.1, pooled over the group
+    red[slice][col] = acc;
+    __syncthreads();
+    if (live && slice == 0) {
+        const float tot = ((red[0][col] + red[1][col]) + red[2][col]) + red[3][col];
+        const float S = (lq > 0) ? tot / (float)(G * lq) : 0.f;        // Alg. 1 l.1, pooled over the group
         const float dstep = bias / (float)cnd;                         // Alg. 1 l.2
         float w = S - (float)(cnd - 1 - j) * dstep;                    // Alg. 1 l.3-4
         if (carry) {                                                   // cumulative policy: total so far, no bias
@@ -198,7 +232,7 @@ hipError_t launch_score_simple(const Geometry& g, const CacheView& c, const void
 {
     const int n = t + L, cnd = n - g.R, lq = g.R < L ? g.R : L;
     if (cnd <= 0) return hipSuccess;
-    const dim3 grid((cnd + 127) / 128, g.Hkv), block(128);
+    const dim3 grid((cnd + 63) / 64, g.Hkv), block(256);
 #define INFMLLM_SCORE(TT, DD)                                                                           \
     hipLaunchKernelGGL((score_simple_kernel<TT, DD>), grid, block, 0, st, (const TT*)q, (const TT*)c.K, \
                        lse, g.policy == POLICY_CUMULATIVE ? c.score : nullptr, Wb, L, lq, g.Hq, g.G, g.cap,     \
