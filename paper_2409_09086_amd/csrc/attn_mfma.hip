@@ -473,40 +473,42 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
     if (lse_in_lds)
         for (int x = tid; x < G * lq; x += 512) s_lse[x] = row_lse(h * G + x / lq, L - lq + x % lq);
 
-    // Staging of the next four blocks.  Chunk u of a thread is row rr[u] of block slot sl[u] (the slot is
-    // uniform over a wavefront), so the block's address is scalar and only toff[u] is per lane.
+    // Staging of the next four blocks.  Chunk u of a thread is row rr of block slot u * RPU / 32 + sbase (the
+    // slot is uniform over a wavefront), so the block's address is scalar and only toff is per lane.  The
+    // loads are unconditional: a chunk past the last scored row, or of a block past the last one, is read
+    // from the nearest valid row instead and zeroed on its way to LDS, which keeps branches out of the loop.
     u32x4 st[NLD];
+    bool st_ok[NLD];
     float stl = 0.f;                                          // log-sum-exp of the staged row, or ...
     int stl_idx = -1;                                         // ... its index in s_lse (looked up when it is staged)
-    int sl[NLD], rr[NLD];
-    uint32_t toff[NLD];
-#pragma unroll
-    for (int u = 0; u < NLD; ++u) {
-        const int ch = tid + u * 512, r = ch / CPR;           // r in 0..127
-        sl[u] = __builtin_amdgcn_readfirstlane(r >> 5);
-        rr[u] = r & 31;
-        toff[u] = (uint32_t)(rr[u] * Hq * D + (ch % CPR) * 8);
-    }
+    constexpr int RPU = 512 / CPR;                            // rows between a thread's consecutive chunks: 32 or 64
+    const int sbase = RPU > 32 ? (wave >> 2) : 0;
+    const int rr = (tid / CPR) & 31;
+    const uint32_t tcol = (uint32_t)((tid % CPR) * 8);
+    const uint32_t rowlen = (uint32_t)(Hq * D);
+    const uint32_t toff = (uint32_t)rr * rowlen + tcol;
     // (head in group, block in head) of the next block
-    int fg = (4 * it_first) / nblk, fb = (4 * it_first) % nblk;
+    int fg = nblk > 0 ? (4 * it_first) / nblk : 0, fb = nblk > 0 ? (4 * it_first) % nblk : 0;
     // direct: take the rows' log-sum-exp from memory (before s_lse is complete)
     auto fetch = [&](bool direct = false) {
         int gk[4], bk[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {                         // past the last block: fg == G
+        for (int k = 0; k < 4; ++k) {                         // past the last block: fg >= G
             gk[k] = fg; bk[k] = fb;
-            if (fg < G && ++fb >= nblk) { fb = 0; ++fg; }
+            const bool wrap = fb + 1 >= nblk;
+            fb = wrap ? 0 : fb + 1;
+            fg += wrap ? 1 : 0;
         }
 #pragma unroll
         for (int u = 0; u < NLD; ++u) {
-            const int g1 = gk[sl[u]], b1 = bk[sl[u]];
-            const int i0 = L - lq + 32 * b1;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (g1 < G) {
-                const uint16_t* base = q + ((size_t)i0 * Hq + h * G + g1) * D;
-                if (i0 + rr[u] < L) v = *(const u32x4*)(base + toff[u]);
-            }
-            st[u] = v;
+            constexpr int KS = RPU > 32 ? 2 : 1;              // slots between a thread's consecutive chunks
+            const int g1 = sbase ? gk[(KS * u + 1) & 3] : gk[KS * u], b1 = sbase ? bk[(KS * u + 1) & 3] : bk[KS * u];
+            const int i0 = L - lq + 32 * b1;                  // < L for every block in range
+            const int gc = g1 < G ? g1 : G - 1;
+            const uint16_t* base = q + ((size_t)i0 * Hq + h * G + gc) * D;
+            const uint32_t lim = (uint32_t)(L - 1 - i0) * rowlen + tcol;   // this thread's columns in the last row
+            st[u] = *(const u32x4*)(base + (toff < lim ? toff : lim));
+            st_ok[u] = g1 < G && toff <= lim;                 // applied when the chunk is written to LDS
         }
         if (tid < TROWS) {
             const int k = tid >> 5;                           // block slot of the row whose lse this thread stages
@@ -526,7 +528,7 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
 #pragma unroll
         for (int u = 0; u < NLD; ++u) {
             const int ch = tid + u * 512;
-            *(u32x4*)(base + (ch / CPR) * QP + (ch % CPR) * 16) = st[u];
+            *(u32x4*)(base + (ch / CPR) * QP + (ch % CPR) * 16) = st_ok[u] ? st[u] : u32x4{0u, 0u, 0u, 0u};
         }
         if (tid < TROWS) *(float*)(base + QBYTES + tid * 4) = (stl_idx >= 0) ? s_lse[stl_idx] : stl;
     };
