@@ -119,13 +119,22 @@ attn_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const T* __
     constexpr int LPR = D / 4, NG = 256 / LPR;   // lanes along a value row (four columns each), groups along the keys
     const int x4 = 4 * (threadIdx.x % LPR), grp = threadIdx.x / LPR;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int j = grp; j < vis; j += NG) {
-        const f32x4 vv = Elt<T>::load4(Vh + (size_t)j * D + x4);
-        const float w = p[j];
-        acc[0] = fmaf(w, vv[0], acc[0]);
-        acc[1] = fmaf(w, vv[1], acc[1]);
-        acc[2] = fmaf(w, vv[2], acc[2]);
-        acc[3] = fmaf(w, vv[3], acc[3]);
+    for (int j = grp; j < vis; j += 4 * NG) {                 // four rows requested before the first is used
+        f32x4 vv[4];
+        float w[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int ju = j + u * NG;
+            vv[u] = Elt<T>::load4(Vh + (size_t)(ju < vis ? ju : j) * D + x4);
+            w[u] = ju < vis ? p[ju] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            acc[0] = fmaf(w[u], vv[u][0], acc[0]);
+            acc[1] = fmaf(w[u], vv[u][1], acc[1]);
+            acc[2] = fmaf(w[u], vv[u][2], acc[2]);
+            acc[3] = fmaf(w[u], vv[u][3], acc[3]);
+        }
     }
     *(f32x4*)(part + grp * D + x4) = acc;
     __syncthreads();
@@ -148,8 +157,9 @@ score_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const floa
                     int max_chunk, int cnd, float scale, float bias)
 {
     constexpr int RT = 16, NS = 4;               // query rows staged per round, row slices
-    __shared__ __attribute__((aligned(16))) float qs[RT][D];
-    __shared__ float ls[RT];
+    constexpr int CPT = (RT * D / 4 + 255) / 256; // 16-byte chunks of a round per thread
+    __shared__ __attribute__((aligned(16))) float qs[2][RT][D];
+    __shared__ float ls[2][RT];
     __shared__ float red[NS][64];
 
     const int h = blockIdx.y;
@@ -165,25 +175,44 @@ score_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const floa
             kr[x] = kv[0]; kr[x + 1] = kv[1]; kr[x + 2] = kv[2]; kr[x + 3] = kv[3];
         }
     }
-    float acc = 0.f;
-    for (int gg = 0; gg < G; ++gg) {
-        const int g = h * G + gg;
-        for (int i0 = L - lq; i0 < L; i0 += RT) {
-            const int rows = min(RT, L - i0);
-            __syncthreads();
-            for (int e = threadIdx.x; e < rows * (D / 4); e += 256) {
-                const int r = e / (D / 4), x = 4 * (e - r * (D / 4));
-                *(f32x4*)&qs[r][x] = Elt<T>::load4(q + ((size_t)(i0 + r) * Hq + g) * D + x);
-            }
-            if (threadIdx.x < rows) ls[threadIdx.x] = lse[(size_t)g * max_chunk + i0 + threadIdx.x];
-            __syncthreads();
-            for (int r = slice; r < rows; r += NS) {
-                float s = 0.f;
+    // Rounds of RT scored rows, over the heads of the group one after the other.  The rows of round rd + 1 are
+    // requested before round rd is used and go to the other LDS buffer afterwards: one barrier per round.
+    const int rpg = (lq + RT - 1) / RT, nrounds = G * rpg;
+    f32x4 nq[CPT];
+    float nl = 0.f;
+    auto request = [&](int rd) {
+        const int g = h * G + rd / rpg, i0 = L - lq + (rd % rpg) * RT;
+        const int rows = min(RT, L - i0);
 #pragma unroll
-                for (int x = 0; x < D; ++x) s = fmaf(qs[r][x], kr[x], s);
-                acc += expf(s * scale - ls[r]);
-            }
+        for (int u = 0; u < CPT; ++u) {
+            const int e = threadIdx.x + u * 256, r = e / (D / 4), x = 4 * (e % (D / 4));
+            nq[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (r < rows) nq[u] = Elt<T>::load4(q + ((size_t)(i0 + r) * Hq + g) * D + x);
         }
+        if (threadIdx.x < rows) nl = lse[(size_t)g * max_chunk + i0 + threadIdx.x];
+    };
+    auto publish = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < CPT; ++u) {
+            const int e = threadIdx.x + u * 256, r = e / (D / 4), x = 4 * (e % (D / 4));
+            if (r < RT) *(f32x4*)&qs[buf][r][x] = nq[u];
+        }
+        if (threadIdx.x < RT) ls[buf][threadIdx.x] = nl;
+    };
+    float acc = 0.f;
+    if (nrounds > 0) { request(0); publish(0); }
+    for (int rd = 0; rd < nrounds; ++rd) {
+        const int buf = rd & 1;
+        if (rd + 1 < nrounds) request(rd + 1);
+        __syncthreads();                         // round rd is complete in qs[buf]; qs[buf ^ 1] is no longer read
+        const int rows = min(RT, lq - (rd % rpg) * RT);
+        for (int r = slice; r < rows; r += NS) {
+            float s = 0.f;
+#pragma unroll
+            for (int x = 0; x < D; ++x) s = fmaf(qs[buf][r][x], kr[x], s);
+            acc += expf(s * scale - ls[buf][r]);
+        }
+        if (rd + 1 < nrounds) publish(buf ^ 1);
     }
     red[slice][col] = acc;
     __syncthreads();
