@@ -55,6 +55,7 @@ def test_cfg1_tiny_fp32_stream(bias):
     (8, 2, 128, 256, 128, [128, 128, 128, 128]),                    # scored rows shared out over 2 workgroups
     (4, 1, 128, 384, 192, [192, 192, 192, 101, 192]),               # ... over 3
     (16, 2, 64, 320, 160, [160, 160, 160, 45, 160]),                # ... over 4, uneven shares, ragged last block
+    (32, 32, 128, 640, 128, [576, 608, 576, 530]),                  # full head count, chunks of 9 and 10 row tiles
 ])
 def test_small_bf16_streams(impl, heads, kv, d, budget, recent, chunks):
     ls = pair(budget, recent, heads, kv, d, "bf16", 1e-3, max_chunk=max(chunks), impl=impl)
