@@ -227,6 +227,30 @@ def test_scores_reported_match_oracle_scores():
     ls.check_state()
 
 
+def test_scores_do_not_depend_on_workgroup_order():
+    """Where the scored rows of a column block are shared out over several workgroups, whichever finishes last
+    adds the slices up; the slices are added in slice order, so W' is the same bits on every run."""
+    heads, kv, d, budget, recent, L = 16, 2, 64, 320, 160, 160          # four slices per column block
+    chunks = [random_chunk(900 + step, L, heads, kv, d, "bf16") for step in range(4)]
+    seen = None
+    for rep in range(6):
+        gpu = B.Stream(budget, recent, heads, kv, d, dtype=torch.bfloat16, bias=1e-3, max_chunk=L)
+        ws = []
+        for q, k, v in chunks:
+            _, ret, _ = gpu.step(q.cuda(), k.cuda(), v.cuda())
+            w = gpu.last_scores()
+            ws.append(None if w is None else w.clone())
+        torch.cuda.synchronize()
+        assert ws[-1] is not None
+        if seen is None:
+            seen = ws
+        else:
+            for a, b in zip(seen, ws):
+                assert (a is None) == (b is None)
+                if a is not None:
+                    assert torch.equal(a.view(torch.int32), b.view(torch.int32)), "scores differ between runs"
+
+
 # ---------------------------------------------------------------------------------------
 # decoding steps (Sec. 3.2: no eviction while tokens are decoded)
 # ---------------------------------------------------------------------------------------
