@@ -1,15 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the Inf-MLLM streaming step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5] [--sub cfg1,cfg2,cfg3,cfg4]
 
 A step is one infmllm_step (append, chunk attention, column score + bias, top-r select,
 compaction) over one chunk of a seeded synthetic stream whose inputs already sit in HBM.
-Prints ONE JSON line: whole-job streamed tokens/s, the roofline of the dominant kernel (from
-HIP events recorded around every kernel of a second, identical pass) and the fp64 CPU oracle
-timed on a bounded sample of the same workload.  Before the W warm-up steps the same steps are
-run untimed for --spinup-ms (50 ms) so that the device has reached its sustained clocks; the K
-timed steps follow the warm-up directly.
+Prints ONE JSON line.  Its headline (value, ms_per_step, roofline, cpu_baseline) is the largest
+single-GPU workload, cfg5 (one layer of the long-text stress stream: 32 heads x 128, budget 8192, chunks
+of 2048); the other workloads are carried as sub-records under "workloads", each with its own throughput,
+roofline fractions and oracle timing.  Rooflines come from HIP events recorded around the kernels in
+further passes over the same steps; the fp64 CPU oracle is timed on a bounded sample of each workload.
+Before the W warm-up steps the same steps are run untimed for --spinup-ms (50 ms) so that the device has
+reached its sustained clocks; the K timed steps follow the warm-up directly.
 """
 import argparse
 import ctypes
@@ -46,19 +48,25 @@ def algorithmic_work(cfg, L, t):
     }
 
 
-def read_traffic(name):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+def read_counters(name):
+    """Figures that only a rocprofv3 --pmc run can give (HBM bytes per launch of the dominant kernel, the share
+    of SIMD-cycles its matrix pipes were busy), from the committed summary of such runs of this same command,
+    if there is one for the workload; None otherwise.  They are not measured in this process."""
     path = os.path.join(ROOT, "profiles", name)
+    out = {"traffic": None, "mfma_busy": None, "source": None}
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":", 1)[1])
+                out["traffic"] = float(line.split(":", 1)[1])
+                out["source"] = "profiles/" + name
+            elif line.startswith("mfma_busy_frac:"):
+                out["mfma_busy"] = float(line.split(":", 1)[1])
     except OSError:
         pass
-    return None
+    return out
 
 
-def cpu_baseline(cfg, budget_seconds=12.0, policy="infmllm", rope_base=0.0):
+def cpu_baseline(cfg, budget_seconds=12.0, policy="infmllm", rope_base=0.0, max_steps=48):
     """The oracle as it stands, timed on steady-state steps of the same workload."""
     import numpy as np
     import oracle
@@ -72,7 +80,7 @@ def cpu_baseline(cfg, budget_seconds=12.0, policy="infmllm", rope_base=0.0):
     orc.load(K, V, pos, cfg.budget)                          # start from a full cache
     stream = ChunkStream(cfg, start_step=0) if cfg.ar_rho else ChunkStream(cfg, start_step=cfg.budget // cfg.chunk)
     tokens, steps, spent = 0, 0, 0.0
-    while spent < budget_seconds and steps < 48:
+    while spent < budget_seconds and steps < max_steps:
         q, k, v = [x.double().numpy() for x in next(stream)]
         t0 = time.perf_counter()
         orc.step(q, k, v)
@@ -175,45 +183,18 @@ def layer_batched_leg(cfg, binding, chunks, dev, impl, n_layers, steps):
     return res
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=64)
-    ap.add_argument("--spinup-ms", type=float, default=50.0,
-                    help="untimed steps run before the warm-up steps until this much time has passed: the GPU "
-                         "raises its clocks only after some tens of milliseconds of load")
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
-    ap.add_argument("--chunks", type=int, default=32, help="distinct chunks kept in HBM and cycled through")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
-    ap.add_argument("--impl", type=int, default=None, help="debug: 1 = plain-arithmetic kernels")
-    ap.add_argument("--policy", default="infmllm", choices=["infmllm", "window", "initial_recent", "cumulative"],
-                    help="score the selection ranks (comparison policies); the default is the paper's method")
-    ap.add_argument("--rope", type=float, default=0.0, metavar="BASE",
-                    help="cache-relative rotary position encoding with this base (0 = off, the default)")
-    ap.add_argument("--layers", type=int, default=16, help="streams in the layer-batched eviction leg (0 = skip)")
-    ap.add_argument("--copy-calib", type=int, default=0, metavar="MIB",
-                    help="also run an elementwise copy of this many MiB (reads MIB, writes MIB) three times, as "
-                         "the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        sys.exit("bench.py: this path runs on one GPU (heads would shard with no communication); "
-                 "run it with --gpus 1")
-
+def measure(cfg, args, binding, dev, steps, nchunks, full):
+    """One workload: throughput pass, per-kernel event passes, (full only) single-step latencies and the decode
+    and layer-batched legs.  Returns the record and the chunks kept in HBM."""
     import torch
-    from paper_2409_09086_amd import binding
-    from paper_2409_09086_amd.workloads import CONFIGS, ChunkStream
-
-    cfg = CONFIGS[args.workload]
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
+    from paper_2409_09086_amd.workloads import ChunkStream
     L = cfg.chunk
     fill_steps = -(-cfg.budget // L)                         # steps until the cache is full
     warmup = max(args.warmup, fill_steps + 1)
 
     # inputs: seeded chunks of the configured stream, resident in HBM before any timing
     stream_in = ChunkStream(cfg)
-    nchunks = min(max(args.chunks, 2), cfg.steps)
+    nchunks = min(max(nchunks, 2), cfg.steps)
     chunks = []
     for _ in range(nchunks):
         q, k, v = next(stream_in)
@@ -240,23 +221,15 @@ def main():
             if rc != 0:
                 raise RuntimeError(binding.last_error())
 
-    if args.copy_calib:
-        src = torch.ones(args.copy_calib << 18, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.add(src, 1.0, out=dst)
-        torch.cuda.synchronize()
-        del src, dst
-
     # Clock spin-up, untimed and before the warm-up steps: from idle the device takes some tens of milliseconds of
     # load to reach its sustained clocks (the first 1-2 ms of steps run ~8 % slower); the state of the stream
     # is the same steady state afterwards.
     spin_steps = 0
     t_spin = time.perf_counter()
     while (time.perf_counter() - t_spin) * 1e3 < args.spinup_ms:
-        run(max(64, fill_steps + 1), 0)
+        run(max(16, fill_steps + 1), 0)
         torch.cuda.synchronize()
-        spin_steps += max(64, fill_steps + 1)
+        spin_steps += max(16, fill_steps + 1)
     run(warmup, 0)
     torch.cuda.synchronize()
     assert len(s) == cfg.budget and int(n_ret.item()) == cfg.budget
@@ -264,44 +237,46 @@ def main():
     # pass 1: whole-step throughput, no events inside the region
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run(args.steps, warmup)
+    run(steps, warmup)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    ms_per_step = 1e3 * elapsed / args.steps
+    ms_per_step = 1e3 * elapsed / steps
 
     # pass 2: the same steps with HIP events around every kernel, on the stream they run on
-    prof_steps = min(args.steps, 256)
+    prof_steps = min(steps, 256)
     s.profile(prof_steps)
-    run(prof_steps, warmup + args.steps)
+    run(prof_steps, warmup + steps)
     torch.cuda.synchronize()
     prof = s.profile_read()
-    # ... and once more with a single bracket around selection + gather (Alg. 1 l.5-8 as a whole)
+    # ... and once more with a single bracket around selection + placement (Alg. 1 l.5-8 as a whole)
     s.profile_select(["evict"])
     s.profile(prof_steps)
-    run(prof_steps, warmup + args.steps)
+    run(prof_steps, warmup + steps)
     torch.cuda.synchronize()
     prof["evict"] = s.profile_read()["evict"]
     # ... and the dominant kernel on its own, so that no other event pair sits next to it in the stream
     s.profile_select(["attn"])
     s.profile(prof_steps)
-    run(prof_steps, warmup + args.steps)
+    run(prof_steps, warmup + steps)
     torch.cuda.synchronize()
     prof["attn"] = s.profile_read()["attn"]
     s.profile_select(binding.KERNELS)
     s.profile(0)
 
-    # pass 3: latency of single steps (event pair around each call, on the stream the kernels run on)
-    lat_steps = min(args.steps, 512)
-    ts = torch.cuda.ExternalStream(s.hip_stream, device=dev) if s.hip_stream else torch.cuda.current_stream(dev)
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(lat_steps)]
-    for i, (e0, e1) in enumerate(evs):
-        e0.record(ts)
-        run(1, warmup + args.steps + prof_steps + i)
-        e1.record(ts)
-    torch.cuda.synchronize()
-    lat = sorted(1e3 * e0.elapsed_time(e1) for e0, e1 in evs)
-    latency = {"p50": round(lat[len(lat) // 2], 2), "p99": round(lat[min(len(lat) - 1, int(0.99 * len(lat)))], 2),
-               "max": round(lat[-1], 2), "steps": lat_steps}
+    latency = None
+    if full:
+        # pass 3: latency of single steps (event pair around each call, on the stream the kernels run on)
+        lat_steps = min(steps, 512)
+        ts = torch.cuda.ExternalStream(s.hip_stream, device=dev) if s.hip_stream else torch.cuda.current_stream(dev)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(lat_steps)]
+        for i, (e0, e1) in enumerate(evs):
+            e0.record(ts)
+            run(1, warmup + steps + prof_steps + i)
+            e1.record(ts)
+        torch.cuda.synchronize()
+        lat = sorted(1e3 * e0.elapsed_time(e1) for e0, e1 in evs)
+        latency = {"p50": round(lat[len(lat) // 2], 2), "p99": round(lat[min(len(lat) - 1, int(0.99 * len(lat)))], 2),
+                   "max": round(lat[-1], 2), "steps": lat_steps}
 
     work = algorithmic_work(cfg, L, cfg.budget)
     kernels = {}
@@ -321,43 +296,108 @@ def main():
     attn = kernels["attn"]
     mfma = cfg.dtype == "bf16" and args.impl != 1
     peak = PEAK_BF16_TFLOPS if mfma else PEAK_FP32_TFLOPS
-    roofline = {"kernel": "attn_fwd", "bound": "mfma" if mfma else "alu", "achieved": attn["tflops"], "peak": peak,
-                "unit": "TFLOP/s", "frac": round(attn["tflops"] / peak, 4),
-                "traffic": read_traffic("attn_fwd_%s_pmc.txt" % cfg.name),
+    ctr = read_counters("attn_fwd_%s_pmc.txt" % cfg.name)
+    roofline = {"kernel": "attn_fwd" if mfma else "attn_simple", "bound": "mfma" if mfma else "alu",
+                "achieved": attn["tflops"], "peak": peak, "unit": "TFLOP/s", "frac": round(attn["tflops"] / peak, 4),
+                "traffic": ctr["traffic"], "mfma_busy_counter": ctr["mfma_busy"], "counters_from": ctr["source"],
                 "algorithmic_flops_per_launch": work["attn"]["flops"], "avg_us": attn["us"]}
-    # selection + gather as one bracket (start of the selection launch to end of the gather launch)
+    # selection + placement as one bracket (start of the selection launch to end of the last eviction launch)
     evict_us = kernels.get("evict", {}).get("us", 0.0)
     evict_bytes = work["select"]["bytes"] + work["compact"]["bytes"]
     evict = {"bound": "hbm", "achieved": round(evict_bytes / (evict_us * 1e-6) / 1e9, 1) if evict_us else None,
              "peak": PEAK_HBM_GBS, "unit": "GB/s",
              "frac": round(evict_bytes / (evict_us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4) if evict_us else None,
              "algorithmic_bytes_per_step": evict_bytes, "avg_us": round(evict_us, 3)}
-
-    result = {
-        "metric": "streamed tokens/s per layer-step at budget B",
-        "value": round(L * args.steps / elapsed, 1),
-        "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": warmup,
-        "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg.dtype, "data": "synthetic",
+    rec = {
+        "value": round(L * steps / elapsed, 1), "ms_per_step": round(ms_per_step, 5), "steps": steps, "warmup": warmup,
+        "dtype": cfg.dtype,
         "config": {"workload": "%s: %d q-heads / %d kv-heads x %d, budget %d (recent %d), chunk %d, steady state n = %d"
                    % (cfg.name, cfg.heads, cfg.kv_heads, cfg.head_dim, cfg.budget, cfg.recent, L, cfg.budget + L),
-                   "bias": cfg.bias, "seed": cfg.seed, "chunks_in_hbm": nchunks, "policy": args.policy, "rope_base": args.rope,
-                   "spinup_ms": args.spinup_ms, "spinup_steps": spin_steps,
+                   "bias": cfg.bias, "seed": cfg.seed, "chunks_in_hbm": nchunks, "policy": args.policy,
+                   "rope_base": args.rope, "spinup_ms": args.spinup_ms, "spinup_steps": spin_steps,
                    "kernels": "mfma" if mfma else "plain"},
-        "roofline": roofline,
-        "evict_roofline": evict,
-        "kernels": kernels,
-        "step_latency_us": latency,
+        "roofline": roofline, "evict_roofline": evict, "kernels": kernels,
     }
-    result["decode"] = decode_leg(cfg, binding, chunks, dev, args.impl)
-    if args.layers > 0:
-        del s
-        result["layer_batched"] = layer_batched_leg(cfg, binding, chunks, dev, args.impl, args.layers,
-                                                    max(4, min(args.steps, 2000 // args.layers)))
+    if latency:
+        rec["step_latency_us"] = latency
+    rec["decode"] = decode_leg(cfg, binding, chunks, dev, args.impl)
+    del s
+    if full and args.layers > 0:
+        rec["layer_batched"] = layer_batched_leg(cfg, binding, chunks, dev, args.impl, args.layers,
+                                                 max(4, min(steps, 2000 // args.layers)))
+    return rec
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--spinup-ms", type=float, default=50.0,
+                    help="untimed steps run before the warm-up steps until this much time has passed: the GPU "
+                         "raises its clocks only after some tens of milliseconds of load")
+    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"],
+                    help="the headline workload (default: the largest single-GPU one)")
+    ap.add_argument("--sub", default="cfg1,cfg2,cfg3,cfg4",
+                    help="comma-separated workloads carried as sub-records under \"workloads\" (empty = none)")
+    ap.add_argument("--chunks", type=int, default=8, help="distinct chunks kept in HBM and cycled through")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--impl", type=int, default=None, help="debug: 1 = plain-arithmetic kernels")
+    ap.add_argument("--policy", default="infmllm", choices=["infmllm", "window", "initial_recent", "cumulative"],
+                    help="score the selection ranks (comparison policies); the default is the paper's method")
+    ap.add_argument("--rope", type=float, default=0.0, metavar="BASE",
+                    help="cache-relative rotary position encoding with this base (0 = off, the default)")
+    ap.add_argument("--layers", type=int, default=8, help="streams in the layer-batched eviction leg (0 = skip)")
+    ap.add_argument("--copy-calib", type=int, default=0, metavar="MIB",
+                    help="also run an elementwise copy of this many MiB (reads MIB, writes MIB) three times, as "
+                         "the known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this path runs on one GPU (heads would shard with no communication); "
+                 "run it with --gpus 1")
+
+    import torch
+    from paper_2409_09086_amd import binding
+    from paper_2409_09086_amd.workloads import CONFIGS
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    if args.copy_calib:
+        src = torch.ones(args.copy_calib << 18, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+
+    cfg = CONFIGS[args.workload]
+    rec = measure(cfg, args, binding, dev, args.steps, args.chunks, full=True)
+    result = {
+        "metric": "streamed tokens/s per layer-step at budget B",
+        "value": rec["value"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": rec["steps"], "warmup": rec["warmup"], "ms_per_step": rec["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": rec["dtype"], "data": "synthetic", "config": rec["config"],
+        "roofline": rec["roofline"], "evict_roofline": rec["evict_roofline"], "kernels": rec["kernels"],
+        "step_latency_us": rec.get("step_latency_us"), "decode": rec["decode"],
+    }
+    if "layer_batched" in rec:
+        result["layer_batched"] = rec["layer_batched"]
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(cfg, policy=args.policy, rope_base=args.rope)
+        result["cpu_baseline"] = cpu_baseline(cfg, budget_seconds=12.0, policy=args.policy, rope_base=args.rope)
+    subs = {}
+    for name in [x for x in args.sub.split(",") if x and x != args.workload]:
+        sc = CONFIGS[name]
+        torch.cuda.empty_cache()
+        r = measure(sc, args, binding, dev, max(4, min(args.steps, 200)), args.chunks, full=False)
+        sub = {"tokens_per_s": r["value"], "us_per_step": round(1e3 * r["ms_per_step"], 3), "steps": r["steps"],
+               "dtype": r["dtype"], "workload": r["config"]["workload"], "roofline": r["roofline"],
+               "evict_roofline": r["evict_roofline"], "kernels": r["kernels"], "decode": r["decode"]}
+        if not args.no_cpu:
+            sub["cpu_baseline"] = cpu_baseline(sc, budget_seconds=3.0, policy=args.policy, rope_base=args.rope, max_steps=16)
+        subs[name] = sub
+    if subs:
+        result["workloads"] = subs
     print(json.dumps(result))
 
 

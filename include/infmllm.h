@@ -18,7 +18,13 @@
  *     device except infmllm_stream_profile_read.
  *   - Every function that returns int returns INFMLLM_OK or a negative INFMLLM_E* code and
  *     never throws or aborts; infmllm_last_error() gives a message for the calling thread's
- *     last failure.  A failed call leaves the stream as it was.
+ *     last failure.  A call refused for its arguments or for the stream's state (EINVAL, ENOMEM,
+ *     ECAPACITY, ESTATE) leaves the stream as it was.  EHIP means a HIP call or a kernel launch
+ *     failed part-way through the call's launches: the host counters (length, tokens streamed) are
+ *     not advanced, but cache rows may already have been written, so the stream's contents are
+ *     undefined from then on and the only calls that make sense are infmllm_stream_import (which
+ *     replaces the cache) and infmllm_stream_destroy.  infmllm_evict_batched commits its streams
+ *     in groups of 16; after EHIP the groups before the failing one are complete.
  *   - A stream is not thread-safe; different streams may be used from different threads.
  *   - Tensors are dense, row-major, token-major: q and out are [chunk_len, heads, head_dim],
  *     k and v are [chunk_len, kv_heads, head_dim], in the stream's dtype.
@@ -71,9 +77,14 @@ enum {
                                     (pairs (x[i], x[i + head_dim/2]), angle p * base^(-2i/head_dim)), so
                                     relative distances never exceed the cache size.  Costs one extra pass over
                                     the cached keys per step and workspace for the turned copies     */
-    INFMLLM_PARAM_IMPL = 3       /* debug/test: 0 (default) = bf16 streams run attention and
+    INFMLLM_PARAM_IMPL = 3,      /* debug/test: 0 (default) = bf16 streams run attention and
                                     scoring on the matrix cores; 1 = every dtype runs the
                                     plain fp32-arithmetic kernels (fp32 streams always do)   */
+    INFMLLM_PARAM_ATTN_TILE = 7  /* debug/test, head_dim 128 on the matrix cores: 0 (default) = the
+                                    attention launch picks its workgroup shape from the chunk length;
+                                    1 = 128 query rows x 2 key ways x 64 keys, 2 = 64 rows x 4 ways x 32,
+                                    3 = 128 rows x 2 ways x 32, 4 = 128 rows x 1 way x 64.  Results are
+                                    the same up to the rounding order of the key-way merge          */
 };
 
 /*
@@ -93,9 +104,11 @@ int infmllm_stream_create(int budget, int recent, int heads, int kv_heads, int h
 
 /*
  * Sets b, the softmax scale, max_chunk, max_decode or the kernel family (Alg. 1 input b;
- * Sec. 3.3).  Only before infmllm_stream_attach (ESTATE afterwards).  EINVAL for an unknown
+ * Sec. 3.3).  Only before infmllm_stream_attach (ESTATE afterwards: the parameters size the
+ * workspace, so they are fixed earlier than the first step).  EINVAL for an unknown
  * parameter, a non-finite value, bias < 0, scale <= 0, max_chunk < 1, max_decode < 0 or impl
- * outside {0, 1}.
+ * outside {0, 1}.  bias and scale are kept in double; a kernel receives the constant it needs
+ * (scale * log2(e), the ramp step b / c of Alg. 1 l.2) formed in double and rounded once to float.
  */
 int infmllm_stream_set_param(infmllm_stream_t* s, int which, double value);
 

@@ -54,9 +54,13 @@
  *   of position j and the query of chunk row i by that of position t + i (the row its own key
  *   occupies), so that relative distances are distances inside the cache and never exceed its
  *   size.  Rotation: pairs (x[i], x[i + d/2]), angle p * base^(-2i/d), i < d/2 (the half-split
- *   form of rotary embeddings).  The rotated values are rounded to the stream's element type
- *   (bf16 or fp32) before the dot products, because that is the precision in which the HIP
- *   path hands them to its attention kernels and the rounding decides retained sets.
+ *   form of rotary embeddings).  A model applies its rotary embedding to the projected q and k
+ *   tensors and stores the result in the model's element type before the attention product
+ *   (that is what "q and k arrive in the stream's dtype" means once the rotation is part of
+ *   the step), so with oracle_set_rope(..., round_to = bf16 | fp32) the rotated values are
+ *   rounded once, to nearest even, to that type; round_to = none keeps them exact, which is
+ *   the mathematical statement of the same reading and the reference for how much that
+ *   rounding can move a result.
  *
  * All arithmetic is IEEE double.  Inputs are taken as exact values (a bf16 or fp32
  * input converts to double without rounding).

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libinfmllm.so")
 
 BF16, FP32 = 0, 1
 OK, EINVAL, ENOMEM, ECAPACITY, ESTATE, EHIP = 0, -1, -2, -3, -4, -5
-PARAM_BIAS, PARAM_SCALE, PARAM_MAX_CHUNK, PARAM_IMPL, PARAM_MAX_DECODE, PARAM_POLICY, PARAM_ROPE_BASE = 0, 1, 2, 3, 4, 5, 6
+PARAM_BIAS, PARAM_SCALE, PARAM_MAX_CHUNK, PARAM_IMPL, PARAM_MAX_DECODE, PARAM_POLICY, PARAM_ROPE_BASE, PARAM_ATTN_TILE = 0, 1, 2, 3, 4, 5, 6, 7
 POLICIES = {"infmllm": 0, "window": 1, "initial_recent": 2, "cumulative": 3}
 
 EXPORTS = [
@@ -97,8 +97,8 @@ class Stream:
     """infmllm_stream_t with its workspace: one layer of one sequence on one GPU."""
 
     def __init__(self, budget, recent, heads, kv_heads, head_dim, dtype=torch.bfloat16, bias=None, scale=None,
-                 max_chunk=None, impl=None, max_decode=None, policy=None, rope_base=None, device="cuda:0",
-                 hip_stream=None):
+                 max_chunk=None, impl=None, max_decode=None, policy=None, rope_base=None, attn_tile=None,
+                 device="cuda:0", hip_stream=None):
         L = lib()
         self.dtype = dtype
         code = {torch.bfloat16: BF16, torch.float32: FP32}.get(dtype)
@@ -111,19 +111,27 @@ class Stream:
         for which, val in ((PARAM_BIAS, bias), (PARAM_SCALE, scale), (PARAM_MAX_CHUNK, max_chunk), (PARAM_IMPL, impl),
                            (PARAM_MAX_DECODE, max_decode),
                            (PARAM_POLICY, None if policy is None else POLICIES[policy]),
-                           (PARAM_ROPE_BASE, rope_base)):
+                           (PARAM_ROPE_BASE, rope_base), (PARAM_ATTN_TILE, attn_tile)):
             if val is not None:
                 _check(L.infmllm_stream_set_param(self._h, which, float(val)))
         self.device = torch.device(device)
         nbytes = L.infmllm_stream_workspace_bytes(self._h)
         with torch.cuda.device(self.device):
+            self.hip_stream = hip_stream if hip_stream is not None else torch.cuda.current_stream(self.device).cuda_stream
             self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
             base = self.workspace.data_ptr()
             aligned = (base + 255) // 256 * 256
-            self.hip_stream = hip_stream if hip_stream is not None else torch.cuda.current_stream(self.device).cuda_stream
-            _check(L.infmllm_stream_attach(self._h, ctypes.c_void_p(aligned), nbytes, ctypes.c_void_p(self.hip_stream)))
+            rc = L.infmllm_stream_attach(self._h, ctypes.c_void_p(aligned), nbytes, ctypes.c_void_p(self.hip_stream))
+            if rc != OK:
+                h, self._h = self._h, None
+                L.infmllm_stream_destroy(h)
+                _check(rc)
 
     def __del__(self):
+        self.close()
+
+    def close(self):
+        """infmllm_stream_destroy."""
         h, self._h = getattr(self, "_h", None), None
         if h and _lib is not None:
             _lib.infmllm_stream_destroy(h)

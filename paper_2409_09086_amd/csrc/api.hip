@@ -66,7 +66,7 @@ struct infmllm_stream {
     float* lse;          // [Hq][max_chunk]
     float* Wb;           // [Hkv][cap]
     int32_t* I;          // [Hkv][B]
-    FwdScratch fwd;      // key-split partials of the matrix-core attention
+    FwdScratch fwd;      // scratch of the row-split scoring launch
     float* dec_part;     // partials of the decoding step
     // optional per-kernel timing: one event pair per kernel per step, up to prof_cap steps
     std::vector<hipEvent_t> prof_ev;   // [prof_cap][INFMLLM_K_COUNT][2]
@@ -90,8 +90,7 @@ struct infmllm_stream {
     }
 
     struct Layout {
-        size_t K[2], V[2], pos[2], score[2], lse, Wb, I, part_o, part_ml, score_part, dec_part, K_rot, kc_rot, q_rot, rope_tab, total;
-        size_t part_rows;
+        size_t K[2], V[2], pos[2], score[2], lse, Wb, I, score_part, dec_part, K_rot, kc_rot, q_rot, rope_tab, total;
     };
     Layout layout() const
     {
@@ -108,11 +107,6 @@ struct infmllm_stream {
         L.lse = off; off += up((size_t)g.Hq * g.max_chunk * 4);
         L.Wb = off; off += ps;
         L.I = off; off += up((size_t)g.Hkv * g.B * 4);
-        // key-split partials (bf16 streams): only chunks too short to fill the chip are split,
-        // so the scratch covers min(max_chunk, 4096) rows at up to 4 splits
-        L.part_rows = (g.elt == 2 && g.d == 128) ? (size_t)4 * (g.max_chunk < 4096 ? g.max_chunk : 4096) : 0;
-        L.part_o = off; off += up(L.part_rows * g.Hq * g.d * 4);
-        L.part_ml = off; off += up(L.part_rows * g.Hq * 2 * 4);
         // row-split scoring (bf16 streams): partial column sums and arrival counters
         L.score_part = off; off += up(g.elt == 2 ? (size_t)SCORE_SPLIT_WGS * (256 + 1) * 4 : 0);
         L.dec_part = off; off += up(g.max_decode > 0 ? (size_t)g.Hq * DECODE_MAX_SPLIT * (g.d + 2) * 4 + (size_t)g.Hkv * 4 : 0);
@@ -151,9 +145,10 @@ int infmllm_stream_create(int budget, int recent, int heads, int kv_heads, int h
     s->g.B = budget; s->g.R = recent; s->g.Hq = heads; s->g.Hkv = kv_heads; s->g.G = heads / kv_heads;
     s->g.d = head_dim; s->g.max_chunk = budget; s->g.max_decode = 0; s->g.cap = 2 * budget;
     s->g.elt = dtype == INFMLLM_BF16 ? 2 : 4;
-    s->g.scale = (float)(1.0 / std::sqrt((double)head_dim));
-    s->g.bias = 1e-4f;
+    s->g.scale = 1.0 / std::sqrt((double)head_dim);
+    s->g.bias = 1e-4;
     s->g.policy = POLICY_INFMLLM;
+    s->g.attn_tile = 0;
     s->dtype = dtype; s->impl = 0; s->attached = false; s->st = nullptr; s->cur = 0; s->len = 0;
     s->streamed = 0; s->last_cnd = 0; s->lse = nullptr; s->Wb = nullptr; s->I = nullptr;
     *out = s;
@@ -175,11 +170,11 @@ int infmllm_stream_set_param(infmllm_stream_t* s, int which, double value)
     switch (which) {
         case INFMLLM_PARAM_BIAS:
             if (value < 0) return fail(INFMLLM_EINVAL, "set_param: bias must be >= 0");
-            s->g.bias = (float)value;
+            s->g.bias = value;
             return INFMLLM_OK;
         case INFMLLM_PARAM_SCALE:
             if (value <= 0) return fail(INFMLLM_EINVAL, "set_param: scale must be > 0");
-            s->g.scale = (float)value;
+            s->g.scale = value;
             return INFMLLM_OK;
         case INFMLLM_PARAM_MAX_CHUNK:
             if (value < 1 || value > (double)(1 << 24) || value != std::floor(value))
@@ -206,6 +201,11 @@ int infmllm_stream_set_param(infmllm_stream_t* s, int which, double value)
             if (value != 0 && value != 1) return fail(INFMLLM_EINVAL, "set_param: impl must be 0 or 1");
             s->impl = (int)value;
             return INFMLLM_OK;
+        case INFMLLM_PARAM_ATTN_TILE:
+            if (value != 0 && value != 1 && value != 2 && value != 3 && value != 4)
+                return fail(INFMLLM_EINVAL, "set_param: attn_tile must be 0..4");
+            s->g.attn_tile = (int)value;
+            return INFMLLM_OK;
         default:
             return fail(INFMLLM_EINVAL, "set_param: unknown parameter %d", which);
     }
@@ -228,7 +228,7 @@ int infmllm_stream_attach(infmllm_stream_t* s, void* ws, size_t bytes, void* hip
     char* base = (char*)ws;
     {
         // kernels that read whole key tiles rely on every byte of the cache being finite
-        hipError_t e = hipMemsetAsync(ws, 0, L.total, (hipStream_t)hip_stream);
+        hipError_t e = launch_zero(ws, L.total, (hipStream_t)hip_stream);
         if (e != hipSuccess) return fail_hip(e, "attach: clearing the workspace");
     }
     for (int i = 0; i < 2; ++i) {
@@ -240,9 +240,6 @@ int infmllm_stream_attach(infmllm_stream_t* s, void* ws, size_t bytes, void* hip
     s->lse = (float*)(base + L.lse);
     s->Wb = (float*)(base + L.Wb);
     s->I = (int32_t*)(base + L.I);
-    s->fwd.part_o = (float*)(base + L.part_o);
-    s->fwd.part_ml = (float*)(base + L.part_ml);
-    s->fwd.part_rows = L.part_rows;
     s->fwd.score_part = (float*)(base + L.score_part);
     s->dec_part = (float*)(base + L.dec_part);
     s->K_rot = base + L.K_rot;
@@ -284,8 +281,7 @@ namespace {
 // index list or the scores.  On return *evict says whether a5-a7 are still to run; the stream's
 // counters are advanced only when they are not.
 int step_front(infmllm_stream* s, const void* q, const void* k, const void* v, int L, void* out, int32_t* retained,
-               int32_t* n_retained, bool merge_in_select, bool* evict, KeySource* ks_out, int* nsplit_out,
-               const char* who)
+               int32_t* n_retained, bool* evict, KeySource* ks_out, const char* who)
 {
     if (!s) return fail(INFMLLM_EINVAL, "%s: stream is null", who);
     if (!s->attached) return fail(INFMLLM_ESTATE, "%s: stream has no workspace attached", who);
@@ -330,16 +326,13 @@ int step_front(infmllm_stream* s, const void* q, const void* k, const void* v, i
         s->rot_rows = in_place ? t : n;
     }
     s->mark(INFMLLM_K_ATTN, 0);
-    int nsplit = 1;     // > 1: the attention left key-split partials that the select launch merges into out
-    e = mfma ? launch_attn_mfma(g, att, ks_att, q_att, t, L, out, s->lse, s->fwd,
-                                /*defer_combine=*/merge_in_select && n > g.B, &nsplit, s->st)
+    e = mfma ? launch_attn_mfma(g, att, ks_att, q_att, t, L, out, s->lse, s->st)
              : launch_attn_simple(g, att, q_att, t, L, out, s->lse, s->st);
     if (e != hipSuccess) return fail_hip(e, "attention");
     s->mark(INFMLLM_K_ATTN, 1);
 
     *evict = n > g.B;
     *ks_out = ks;
-    *nsplit_out = nsplit;
     if (n <= g.B) {
         // the chunk fits: nothing is evicted
         if ((e = launch_iota(g, n, retained, n_retained, s->st)) != hipSuccess) return fail_hip(e, "index list");
@@ -353,7 +346,7 @@ int step_front(infmllm_stream* s, const void* q, const void* k, const void* v, i
     if (g.policy == POLICY_WINDOW || g.policy == POLICY_INITIAL_RECENT)
         e = launch_rank_scores(g, s->Wb, n - g.R, g.policy == POLICY_WINDOW ? 1.f : -1.f, s->st);
     else
-        e = mfma ? launch_score_mfma(g, att, ks_att, q_att, s->lse, s->fwd, nsplit, t, L, s->Wb, s->st)
+        e = mfma ? launch_score_mfma(g, att, ks_att, q_att, s->lse, s->fwd, t, L, s->Wb, s->st)
                  : launch_score_simple(g, att, q_att, s->lse, t, L, s->Wb, s->st);
     if (e != hipSuccess) return fail_hip(e, "score");
     s->mark(INFMLLM_K_SCORE, 1);
@@ -381,8 +374,7 @@ int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* 
 {
     bool evict = false;
     KeySource ks{0, nullptr, nullptr};
-    int nsplit = 1;
-    const int rc = step_front(s, q, k, v, L, out, retained, n_retained, true, &evict, &ks, &nsplit, "step");
+    const int rc = step_front(s, q, k, v, L, out, retained, n_retained, &evict, &ks, "step");
     if (rc != INFMLLM_OK || !evict) return rc;
     const Geometry& g = s->g;
     const CacheView& cur = s->cache[s->cur];
@@ -390,8 +382,7 @@ int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* 
     const int n = s->len + L;
     hipError_t e;
     s->mark(INFMLLM_K_SELECT, 0);
-    const CombineJob cj{s->fwd.part_o, s->fwd.part_ml, out, L, g.Hq, nsplit};
-    if ((e = launch_select(g, s->Wb, n, s->I, retained, n_retained, cur, ks, s->streamed, nxt, cj, s->st)) != hipSuccess)
+    if ((e = launch_select(g, s->Wb, n, s->I, retained, n_retained, cur, ks, s->streamed, nxt, s->st)) != hipSuccess)
         return fail_hip(e, "step: select");
     s->mark(INFMLLM_K_SELECT, 1);
     s->mark(INFMLLM_K_COMPACT, 0);
@@ -406,8 +397,7 @@ int infmllm_step_attend(infmllm_stream_t* s, const void* q, const void* k, const
 {
     bool evict = false;
     KeySource ks{0, nullptr, nullptr};
-    int nsplit = 1;
-    const int rc = step_front(s, q, k, v, L, out, retained, n_retained, false, &evict, &ks, &nsplit, "step_attend");
+    const int rc = step_front(s, q, k, v, L, out, retained, n_retained, &evict, &ks, "step_attend");
     if (rc != INFMLLM_OK || !evict) return rc;
     s->pending = true;
     s->pend_ks = ks;

@@ -20,8 +20,6 @@
 //
 // fp32 is kept from the MFMA accumulators to the score: the bf16 rounding of P is applied only
 // to the copy that feeds the P.V product.
-#include <cstdlib>
-
 #include "launch.h"
 #include "mfma_common.h"
 
@@ -58,16 +56,14 @@ struct FwdCfg {
 };
 
 // Tail of the attention kernel: merge the key ways of a query block through LDS, then normalise and
-// store (or store the un-normalised partial of a key split).  Every wavefront leaves its (m, l, O) in
+// store.  Every wavefront leaves its (m, l, O) in
 // LDS; the KW wavefronts of a query block then each merge and store their own D / KW output columns,
 // so the tail's LDS reads, arithmetic and stores are spread over the whole workgroup.
 // Lane (row l32, half hh) holds O[row][32b + 8(i/4) + 4hh + i%4] in o[b][i].
 template <int D, int RB, int KW>
 __device__ __forceinline__ void fwd_finish(char* smem, bool sync_first, f32x16 (&o)[D / 32], float m_ref, float lsum,
-                                           int rb, int kw, int lane, int hh, int my_row, int g, int sp, int L, int Hq,
-                                           int max_chunk, int nsplit, float* __restrict__ part_o,
-                                           float* __restrict__ part_ml, uint16_t* __restrict__ out,
-                                           float* __restrict__ lse2)
+                                           int rb, int kw, int lane, int hh, int my_row, int g, int L, int Hq,
+                                           int max_chunk, uint16_t* __restrict__ out, float* __restrict__ lse2)
 {
     constexpr int OREG = D / 2, NB = D / 32;
     static_assert(NB % KW == 0, "the output column blocks must split evenly over the key ways");
@@ -106,7 +102,6 @@ __device__ __forceinline__ void fwd_finish(char* smem, bool sync_first, f32x16 (
     }
     const float ltot = lsum + xhalf(lsum);
     const float inv = 1.0f / ltot;
-    const size_t rowi = ((size_t)sp * L + my_row) * Hq + g;   // row of the key-split partials
     uint16_t* op = out + ((size_t)my_row * Hq + g) * D;
 #pragma unroll
     for (int bb = 0; bb < BPW; ++bb) {
@@ -126,28 +121,13 @@ __device__ __forceinline__ void fwd_finish(char* smem, bool sync_first, f32x16 (
         }
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-            if (nsplit > 1) {
-                // un-normalised partial of this key split: [split][row][head][D] fp32, (m, l) beside it
-                f32x4 w;
+            bf16x4 w;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = v[4 * q4 + e];
-                *(f32x4*)(part_o + rowi * D + 32 * b + 8 * q4 + 4 * hh) = w;
-            } else {
-                bf16x4 w;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = (__bf16)(v[4 * q4 + e] * inv);
-                *(bf16x4*)(op + 32 * b + 8 * q4 + 4 * hh) = w;
-            }
+            for (int e = 0; e < 4; ++e) w[e] = (__bf16)(v[4 * q4 + e] * inv);
+            *(bf16x4*)(op + 32 * b + 8 * q4 + 4 * hh) = w;
         }
     }
-    if (kw == 0 && hh == 0) {
-        if (nsplit > 1) {
-            part_ml[rowi * 2] = m_ref;
-            part_ml[rowi * 2 + 1] = ltot;
-        } else {
-            lse2[(size_t)g * max_chunk + my_row] = m_ref + __builtin_log2f(ltot);
-        }
-    }
+    if (kw == 0 && hh == 0) lse2[(size_t)g * max_chunk + my_row] = m_ref + __builtin_log2f(ltot);
 }
 
 template <int D, int RB, int KW, int KVB>
@@ -155,8 +135,7 @@ __global__ void __launch_bounds__(64 * RB * KW)
 attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                 const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc, int tc,
                 uint16_t* __restrict__ out, float* __restrict__ lse2, int t, int L, int Hq, int G, int cap,
-                int max_chunk, int hpw, int ntile, int ny, int nsplit, float* __restrict__ part_o,
-                float* __restrict__ part_ml, float c /* scale * log2(e) */)
+                int max_chunk, int hpw, int ntile, int ny, float c /* scale * log2(e) */)
 {
     using C = FwdCfg<D, RB, KW, KVB>;
     __shared__ __attribute__((aligned(16))) char smem[C::LDS];
@@ -164,22 +143,19 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
     // Workgroup -> (row tile, head group).  Consecutive workgroup ids go round-robin over the 8
     // XCDs; all row tiles of one kv-head are given ids of one residue class so that they share
     // that XCD's L2 copy of the head's K and V.
-    // With nsplit > 1 the key range of a row tile is cut into nsplit pieces handled by different
-    // workgroups; each writes an un-normalised partial and a second kernel combines them.
-    int bx, by, sp;
+    int bx, by;
     {
-        const int bid = blockIdx.x, per_y = ntile * nsplit;
+        const int bid = blockIdx.x;
         int rem;
         if ((ny & 7) == 0) {
             const int xcd = bid & 7, li = bid >> 3;
-            by = xcd + 8 * (li / per_y);
-            rem = li % per_y;
+            by = xcd + 8 * (li / ntile);
+            rem = li % ntile;
         } else {
-            by = bid / per_y;
-            rem = bid % per_y;
+            by = bid / ntile;
+            rem = bid % ntile;
         }
-        bx = ntile - 1 - rem / nsplit;                       // longest (most keys visible) tiles first
-        sp = rem % nsplit;
+        bx = ntile - 1 - rem;                                // longest (most keys visible) tiles first
     }
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: branches on it are scalar
@@ -280,8 +256,8 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
     const int voff = C::KBYTES + (kw * C::SUB + 4 * hh + ((lane & 15) >> 2)) * C::VP +
                      (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
 
-    const int ntiles_all = (n_end + C::TILE - 1) / C::TILE;
-    const int tile_lo = (int)((long)ntiles_all * sp / nsplit), ntiles = (int)((long)ntiles_all * (sp + 1) / nsplit);
+    const int ntiles = (n_end + C::TILE - 1) / C::TILE;
+    constexpr int tile_lo = 0;
     if (tile_lo < ntiles) fetch(tile_lo * C::TILE);
     if (C::NBUF == 2) {
         if (tile_lo < ntiles) stash(tile_lo & 1);
@@ -391,8 +367,7 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
         }
     }
 
-    fwd_finish<D, RB, KW>(smem, C::NBUF == 1, o, m_ref, lsum, rb, kw, lane, hh, my_row, g, sp, L, Hq, max_chunk, nsplit,
-                          part_o, part_ml, out, lse2);
+    fwd_finish<D, RB, KW>(smem, C::NBUF == 1, o, m_ref, lsum, rb, kw, lane, hh, my_row, g, L, Hq, max_chunk, out, lse2);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -406,9 +381,8 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
 template <int D, int CB>
 __global__ void __launch_bounds__(512)
 score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ kc, int tc,
-             const float* __restrict__ lse2, const float* __restrict__ part_ml, int nsplit,
-             const float* __restrict__ carry, float* __restrict__ Wb, int L, int lq, int Hq, int Hkv, int G, int cap, int max_chunk, int cnd,
-             int nxb, float c, float bias, int rsplit, float* __restrict__ spart)
+             const float* __restrict__ lse2, const float* __restrict__ carry, float* __restrict__ Wb, int L, int lq, int Hq, int Hkv, int G, int cap, int max_chunk, int cnd,
+             int nxb, float c, float dstep /* b / c, Alg. 1 l.2 */, int rsplit, float* __restrict__ spart)
 {
     constexpr int QP = D * 2 + 16;                            // pitch of a staged query row
     constexpr int CPR = D / 8;
@@ -457,18 +431,7 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
     const int it_first = (int)((long)rs * niter_all / rsplit);               // this workgroup's iterations
     const int niter = (int)((long)(rs + 1) * niter_all / rsplit) - it_first;
     // Row log-sum-exp of every scored row of the group, once per workgroup: row (gg, i) -> s_lse[gg*lq + i].
-    // After a key-split attention launch it is derived from the partials: max m + log2(sum_s l_s 2^(m_s - max m)).
-    auto row_lse = [&](int g, int i) -> float {
-        if (nsplit <= 1) return lse2[(size_t)g * max_chunk + i];
-        float mt = -__builtin_inff();
-        for (int sp = 0; sp < nsplit; ++sp) mt = fmaxf(mt, part_ml[(((size_t)sp * L + i) * Hq + g) * 2]);
-        float lt = 0.f;
-        for (int sp = 0; sp < nsplit; ++sp) {
-            const size_t r = (((size_t)sp * L + i) * Hq + g) * 2;
-            lt += fast_exp2(part_ml[r] - mt) * part_ml[r + 1];
-        }
-        return mt + __builtin_log2f(lt);
-    };
+    auto row_lse = [&](int g, int i) -> float { return lse2[(size_t)g * max_chunk + i]; };
     const bool lse_in_lds = G * lq <= LSE_ROWS;
     if (lse_in_lds)
         for (int x = tid; x < G * lq; x += 512) s_lse[x] = row_lse(h * G + x / lq, L - lq + x % lq);
@@ -652,7 +615,6 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
     }
     if (rg == 0 && hh == 0) {
         const float norm = (lq > 0) ? 1.0f / (float)(G * lq) : 0.f;
-        const float dstep = bias / (float)cnd;                // Alg. 1 l.2
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
             const int col = col0 + 32 * cb + l32;
@@ -678,101 +640,46 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
     }
 }
 
-// Second pass of a key-split launch (head_dim 128):
-// out[row][head][:] = sum_s w_s O_s / sum_s w_s l_s with w_s = exp2(m_s - max m); lse2 = max m + log2(sum).
-// One thread per 8 output columns.  A kernel boundary is the one ordering across XCDs that needs
-// no cache maintenance, which is why the merge is not done by the last workgroup to finish.
-__global__ void __launch_bounds__(256)
-attn_combine_kernel(const float* __restrict__ part_o, const float* __restrict__ part_ml, uint16_t* __restrict__ out,
-                    float* __restrict__ lse2, int L, int Hq, int max_chunk, int nsplit)
-{
-    constexpr int D = 128;
-    const long total = (long)L * Hq * (D / 8);
-    for (long idx = (long)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (long)gridDim.x * blockDim.x) {
-        const int x = (int)(idx % (D / 8));
-        const long rowi = idx / (D / 8);                      // row * Hq + head
-        float mt = -__builtin_inff();
-        for (int s = 0; s < nsplit; ++s) mt = fmaxf(mt, part_ml[((size_t)s * L * Hq + rowi) * 2]);
-        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, lt = 0.f;
-        for (int s = 0; s < nsplit; ++s) {
-            const size_t r = (size_t)s * L * Hq + rowi;
-            const float w = fast_exp2(part_ml[r * 2] - mt);   // an empty split has m = -inf, weight 0
-            lt += w * part_ml[r * 2 + 1];
-            const f32x4 a = *(const f32x4*)(part_o + r * D + 8 * x), b = *(const f32x4*)(part_o + r * D + 8 * x + 4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { acc[e] += w * a[e]; acc[4 + e] += w * b[e]; }
-        }
-        const float inv = 1.0f / lt;
-        bf16x8 o;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = (__bf16)(acc[e] * inv);
-        *(bf16x8*)(out + rowi * D + 8 * x) = o;
-        if (x == 0) {
-            const int row = (int)(rowi / Hq), g = (int)(rowi % Hq);
-            lse2[(size_t)g * max_chunk + row] = mt + __builtin_log2f(lt);
-        }
-    }
-}
-
 }  // namespace
 
 template <int D, int RB, int KW, int KVB>
 hipError_t launch_fwd_cfg(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q, int t, int L,
-                          void* out, float* lse, const FwdScratch& sc, int nsplit, bool defer_combine, int* nsplit_out,
-                          hipStream_t st)
+                          void* out, float* lse, hipStream_t st)
 {
     const int hpw = (RB % g.G == 0) ? g.G : ((g.G % RB == 0) ? RB : 1);
     const int rbph = RB / hpw;
     const int ntile = (L + 32 * rbph - 1) / (32 * rbph), ny = g.Hkv * (g.G / hpw);
-    if (D != 128 || (nsplit > 1 && (size_t)nsplit * L > sc.part_rows)) nsplit = 1;   // no scratch: no split
-    const dim3 grid(ntile * ny * nsplit), block(64 * RB * KW);
+    const dim3 grid(ntile * ny), block(64 * RB * KW);
     hipLaunchKernelGGL((attn_fwd_kernel<D, RB, KW, KVB>), grid, block, 0, st, (const uint16_t*)q, (const uint16_t*)c.K, (const uint16_t*)c.V,
                        (const uint16_t*)ks.k, (const uint16_t*)ks.v, ks.rows, (uint16_t*)out, lse, t, L, g.Hq, g.G,
-                       g.cap, g.max_chunk, hpw, ntile, ny, nsplit, sc.part_o, sc.part_ml, g.scale * LOG2E);
-    hipError_t e = hipGetLastError();
-    *nsplit_out = (defer_combine && e == hipSuccess) ? nsplit : 1;
-    if (e != hipSuccess || nsplit == 1 || defer_combine) return e;
-    const long total = (long)L * g.Hq * 16;
-    int blocks = (int)((total + 255) / 256);
-    if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(attn_combine_kernel, dim3(blocks), dim3(256), 0, st, sc.part_o, sc.part_ml, (uint16_t*)out,
-                       lse, L, g.Hq, g.max_chunk, nsplit);
+                       g.cap, g.max_chunk, hpw, ntile, ny, (float)(g.scale * (double)LOG2E));
     return hipGetLastError();
 }
 
 hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q, int t, int L,
-                            void* out, float* lse, const FwdScratch& sc, bool defer_combine, int* nsplit,
-                            hipStream_t st)
+                            void* out, float* lse, hipStream_t st)
 {
-    static const int variant = [] { const char* e = getenv("INFMLLM_FWD"); return e ? atoi(e) : -1; }();
-    static const int split = [] { const char* e = getenv("INFMLLM_SPLIT"); return e ? atoi(e) : 0; }();
-    *nsplit = 1;
-    if (g.d == 64) return launch_fwd_cfg<64, 4, 1, 2>(g, c, ks, q, t, L, out, lse, sc, 1, false, nsplit, st);
+    if (g.d == 64) return launch_fwd_cfg<64, 4, 1, 2>(g, c, ks, q, t, L, out, lse, st);
     if (g.d != 128) return hipErrorInvalidValue;
-    // 128 query rows x 64 keys per wavefront-tile is the efficient shape (57 % MFMA utilisation on the
-    // CUs it occupies); when that grid would cover only about half of the chip (cfg2: 128 workgroups),
-    // 64-row workgroups with four key ways inside the workgroup are faster.  Splitting the key range
-    // over workgroups (INFMLLM_SPLIT, merged by the select launch or a combine kernel) was measured
-    // to gain nothing at the five workloads -- the partials cost what the extra workgroups save --
-    // and is off by default.
+    // 128 query rows x 64 keys per wavefront-tile is the efficient shape; when that grid would cover
+    // only about half of the chip (128 workgroups at 32 heads x 512 rows), 64-row workgroups with four
+    // key ways inside the workgroup are faster.  g.attn_tile > 0 (a test hook) forces one shape.
     const int wgs128 = g.Hq * ((L + 31) / 32) / 4;
-    const int ns = split > 0 ? split : 1;
-    const int v = variant >= 0 ? variant : (wgs128 >= 140 ? 1 : 2);
+    const int v = g.attn_tile > 0 ? g.attn_tile : (wgs128 >= 140 ? 1 : 2);
     switch (v) {
-        case 1: return launch_fwd_cfg<128, 4, 2, 2>(g, c, ks, q, t, L, out, lse, sc, ns, defer_combine, nsplit, st);
-        case 2: return launch_fwd_cfg<128, 2, 4, 1>(g, c, ks, q, t, L, out, lse, sc, ns, defer_combine, nsplit, st);
-        case 3: return launch_fwd_cfg<128, 4, 2, 1>(g, c, ks, q, t, L, out, lse, sc, ns, defer_combine, nsplit, st);
-        default: return launch_fwd_cfg<128, 4, 1, 2>(g, c, ks, q, t, L, out, lse, sc, ns, defer_combine, nsplit, st);
+        case 1: return launch_fwd_cfg<128, 4, 2, 2>(g, c, ks, q, t, L, out, lse, st);
+        case 2: return launch_fwd_cfg<128, 2, 4, 1>(g, c, ks, q, t, L, out, lse, st);
+        case 3: return launch_fwd_cfg<128, 4, 2, 1>(g, c, ks, q, t, L, out, lse, st);
+        default: return launch_fwd_cfg<128, 4, 1, 2>(g, c, ks, q, t, L, out, lse, st);
     }
 }
 
 hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q,
-                             const float* lse, const FwdScratch& sc, int nsplit, int t, int L, float* Wb,
-                             hipStream_t st)
+                             const float* lse, const FwdScratch& sc, int t, int L, float* Wb, hipStream_t st)
 {
     const int n = t + L, cnd = n - g.R, lq = g.R < L ? g.R : L;
     if (cnd <= 0) return hipSuccess;
-    const float cc = g.scale * LOG2E;
+    const float cc = (float)(g.scale * (double)LOG2E);
     // 256 columns per workgroup.  Where that leaves CUs without one, the scored rows of a column block are
     // shared out over up to four workgroups (whose sums the last to finish adds up); where there are too few
     // rows for that, a workgroup takes 128 columns.
@@ -791,10 +698,10 @@ hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySou
     const dim3 grid(nxb * g.Hkv * rsplit), block(512);
 #define INFMLLM_SCORE(DD, CB)                                                                              \
     hipLaunchKernelGGL((score_kernel<DD, CB>), grid, block, 0, st, (const uint16_t*)q, (const uint16_t*)c.K, \
-                       (const uint16_t*)ks.k, ks.rows, lse, sc.part_ml, nsplit,                              \
+                       (const uint16_t*)ks.k, ks.rows, lse,                                                  \
                        g.policy == POLICY_CUMULATIVE ? c.score : nullptr, Wb, L, lq, g.Hq, g.Hkv, g.G, g.cap, \
                        g.max_chunk,                                                                          \
-                       cnd, nxb, cc, g.bias, rsplit, sc.score_part)
+                       cnd, nxb, cc, (float)(g.bias / (double)cnd), rsplit, sc.score_part)
     if (g.d == 128 && wide) INFMLLM_SCORE(128, 2);
     else if (g.d == 128) INFMLLM_SCORE(128, 1);
     else if (g.d == 64 && wide) INFMLLM_SCORE(64, 2);

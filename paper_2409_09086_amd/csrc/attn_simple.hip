@@ -154,7 +154,7 @@ template <typename T, int D>
 __global__ void __launch_bounds__(256)
 score_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const float* __restrict__ lse,
                     const float* __restrict__ carry, float* __restrict__ Wb, int L, int lq, int Hq, int G, int cap,
-                    int max_chunk, int cnd, float scale, float bias)
+                    int max_chunk, int cnd, float scale, float dstep /* b / c, Alg. 1 l.2 */)
 {
     constexpr int RT = 16, NS = 4;               // query rows staged per round, row slices
     constexpr int CPT = (RT * D / 4 + 255) / 256; // 16-byte chunks of a round per thread
@@ -219,7 +219,6 @@ score_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const floa
     if (live && slice == 0) {
         const float tot = ((red[0][col] + red[1][col]) + red[2][col]) + red[3][col];
         const float S = (lq > 0) ? tot / (float)(G * lq) : 0.f;        // Alg. 1 l.1, pooled over the group
-        const float dstep = bias / (float)cnd;                         // Alg. 1 l.2
         float w = S - (float)(cnd - 1 - j) * dstep;                    // Alg. 1 l.3-4
         if (carry) {                                                   // cumulative policy: total so far, no bias
             const float a = carry[(size_t)h * cap + j];
@@ -245,7 +244,7 @@ hipError_t launch_attn_simple(const Geometry& g, const CacheView& c, const void*
         }                                                                                               \
         hipLaunchKernelGGL((attn_simple_kernel<TT, DD>), grid, block, lds, st, (const TT*)q,            \
                            (const TT*)c.K, (const TT*)c.V, (TT*)out, lse, t, L, g.Hq, g.G, g.cap,       \
-                           g.max_chunk, g.scale);                                                       \
+                           g.max_chunk, (float)g.scale);                                                       \
     } while (0)
     if (g.elt == 4 && g.d == 64) INFMLLM_ATTN(float, 64);
     else if (g.elt == 4 && g.d == 128) INFMLLM_ATTN(float, 128);
@@ -265,7 +264,7 @@ hipError_t launch_score_simple(const Geometry& g, const CacheView& c, const void
 #define INFMLLM_SCORE(TT, DD)                                                                           \
     hipLaunchKernelGGL((score_simple_kernel<TT, DD>), grid, block, 0, st, (const TT*)q, (const TT*)c.K, \
                        lse, g.policy == POLICY_CUMULATIVE ? c.score : nullptr, Wb, L, lq, g.Hq, g.G, g.cap,     \
-                       g.max_chunk, cnd, g.scale, g.bias)
+                       g.max_chunk, cnd, (float)g.scale, (float)(g.bias / (double)cnd))
     if (g.elt == 4 && g.d == 64) INFMLLM_SCORE(float, 64);
     else if (g.elt == 4 && g.d == 128) INFMLLM_SCORE(float, 128);
     else if (g.elt == 2 && g.d == 64) INFMLLM_SCORE(uint16_t, 64);

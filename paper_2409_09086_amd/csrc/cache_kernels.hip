@@ -34,6 +34,13 @@ append_kernel(const u32x4* __restrict__ k, const u32x4* __restrict__ v, u32x4* _
 }
 
 __global__ void __launch_bounds__(256)
+zero_kernel(u32x4* __restrict__ p, size_t nvec)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = u32x4{0u, 0u, 0u, 0u};
+}
+
+__global__ void __launch_bounds__(256)
 iota_kernel(int32_t* __restrict__ I, int32_t* __restrict__ count, int n, int Hkv, int B)
 {
     const int total = n * Hkv;
@@ -144,6 +151,17 @@ hipError_t launch_append(const Geometry& g, const CacheView& c, const void* k, c
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(append_kernel, dim3(blocks), dim3(256), 0, st, (const u32x4*)k, (const u32x4*)v,
                        (u32x4*)c.K, (u32x4*)c.V, c.pos, c.score, t, L, g.Hkv, g.cap, vpr, (int)T);
+    return hipGetLastError();
+}
+
+hipError_t launch_zero(void* p, size_t bytes, hipStream_t st)
+{
+    if (bytes == 0) return hipSuccess;
+    if (((uintptr_t)p | bytes) & 15) return hipErrorInvalidValue;
+    const size_t nvec = bytes / 16;
+    size_t blocks = (nvec + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (u32x4*)p, nvec);
     return hipGetLastError();
 }
 

@@ -234,7 +234,7 @@ hipError_t launch_decode(const Geometry& g, const CacheView& c, const void* q, c
     if (nsplit > n / 128) nsplit = n / 128;             // ... of at least 128 keys each
     if (nsplit > max_split) nsplit = max_split;
     if (nsplit < 1) nsplit = 1;
-    const float cc = g.scale * 1.4426950408889634f;
+    const float cc = (float)(g.scale * 1.4426950408889634);
     int* arrived = (int*)(part + (size_t)g.Hq * max_split * (g.d + 2));   // one ticket counter per kv-head, zero between launches
     const dim3 grid(nsplit, g.Hkv);
 #define INFMLLM_DECODE_NG(TT, DD, NG)                                                                            \

@@ -23,9 +23,10 @@ struct Geometry {
     int max_chunk;
     int max_decode;
     int elt;      // bytes per element (2 = bf16, 4 = fp32)
-    float scale;  // softmax scale
-    float bias;   // b of Alg. 1
+    double scale; // softmax scale (kernels take it, times log2(e) where they work in base 2, rounded once to float)
+    double bias;  // b of Alg. 1 (the ramp step b / c is formed in double and rounded once to float)
     int policy;   // score ranked by the selection: 0 Alg. 1, 1 window, 2 initial + recent, 3 cumulative
+    int attn_tile;// test hook: 0 = the matrix-core attention picks its tile shape, 1..4 = forces one
 };
 enum { POLICY_INFMLLM = 0, POLICY_WINDOW = 1, POLICY_INITIAL_RECENT = 2, POLICY_CUMULATIVE = 3 };
 
@@ -51,12 +52,8 @@ hipError_t launch_attn_simple(const Geometry& g, const CacheView& c, const void*
 hipError_t launch_score_simple(const Geometry& g, const CacheView& c, const void* q, const float* lse,
                                int t, int L, float* Wb, hipStream_t st);
 
-// Scratch of the matrix-core attention when the key range of a row tile is split over several
-// workgroups: un-normalised fp32 partial outputs [split][row][head][d] and (max, sum) pairs.
+// Scratch of the matrix-core scoring launch.
 struct FwdScratch {
-    float* part_o;
-    float* part_ml;
-    size_t part_rows;     // split * rows the buffers can hold
     // Row-split scoring: raw column sums of each split, [SCORE_SPLIT_WGS][256] fp32, followed by one
     // arrival counter per (kv-head, column block), [SCORE_SPLIT_WGS] int32, zero between launches.
     float* score_part;
@@ -73,34 +70,20 @@ struct KeySource {
     const void* v;
 };
 
-// a2 on bf16 MFMA (bf16 streams only).  Short chunks are run with the key range of every row tile
-// split over several workgroups, which leaves un-normalised partials in `sc`; *nsplit receives
-// the number of splits (1 = out and lse are final).  With defer_combine the merge of the partials
-// into `out` is left to the caller (launch_select does it on otherwise idle CUs); without it a
-// combine kernel is launched here and *nsplit is 1.
+// a2 on bf16 MFMA (bf16 streams only): out and the row log-sum-exp (base 2).
 hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q, int t, int L,
-                            void* out, float* lse, const FwdScratch& sc, bool defer_combine, int* nsplit,
-                            hipStream_t st);
+                            void* out, float* lse, hipStream_t st);
 
 // a3+a4 on bf16 MFMA (bf16 streams only).
-// nsplit > 1: the row log-sum-exp is derived from the partials in `sc` instead of read from lse.
 hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q,
-                             const float* lse, const FwdScratch& sc, int nsplit, int t, int L, float* Wb,
-                             hipStream_t st);
+                             const float* lse, const FwdScratch& sc, int t, int L, float* Wb, hipStream_t st);
 
 // a5+a6: I[h] = sort_asc(top-r of W'[h][0..cnd)) ++ [cnd, n).  I has row stride B.
 // user_I (row stride B) and user_count may be null.  The same launch also moves the recent
 // window (rows cnd..n-1 of src / the chunk) to rows r..B-1 of dst, on workgroups of its own.
-// With cj.nsplit > 1 further workgroups merge the attention partials into cj.out (head_dim 128).
-struct CombineJob {
-    const float* part_o;
-    const float* part_ml;
-    void* out;            // [L][Hq][128] bf16
-    int L, Hq, nsplit;
-};
 hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, int32_t* user_I,
                          int32_t* user_count, const CacheView& src, const KeySource& ks, int64_t T,
-                         const CacheView& dst, const CombineJob& cj, hipStream_t st);
+                         const CacheView& dst, hipStream_t st);
 
 // One stream's share of a batched eviction (a5-a7 for the layers of a model in one launch each,
 // Alg. 1 Input note).  All streams of a batch have the same geometry.
@@ -132,6 +115,10 @@ hipError_t launch_rank_scores(const Geometry& g, float* Wb, int cnd, float sign,
 // index e * (d/16) + a, so that the threads of a row (one per a) read consecutive entries.
 hipError_t launch_rope(const Geometry& g, const void* K, void* Krot, int j0, int j1, const void* kc, void* kcrot,
                        const void* q, void* qrot, int t, int L, const double* tab, hipStream_t st);
+
+// Clears `bytes` bytes (a multiple of 16) at p (16-byte aligned) with a fill kernel, which, unlike a
+// memset node, may be recorded into a HIP graph.
+hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
 
 // warm-up: I[h][j] = j for j < n.
 hipError_t launch_iota(const Geometry& g, int n, int32_t* user_I, int32_t* user_count, hipStream_t st);

@@ -5,10 +5,11 @@
 // layout, the chunk's keys and the queries token-major) which the attention and scoring kernels then read
 // in place of the originals; selection and compaction keep working on the unrotated rows.
 //
-// Pair (x[i], x[i + d/2]) is turned by p * base^(-2i/d).  The arithmetic is fp64 on a (cos, sin) table
-// computed on the host in fp64, and the result is rounded once to the stream type: retained sets are
-// decided by these values, so they are produced in a way a plain fp64 restatement reproduces bit for bit
-// (HBM-bound pass; the fp64 work hides behind the loads).
+// Pair (x[i], x[i + d/2]) is turned by p * base^(-2i/d).  The turned values are stored in the stream's
+// element type, as a model stores its rotated q and k.  The arithmetic is fp64 on a (cos, sin) table
+// computed on the host in fp64, so that each stored value is the correctly rounded one: an fp32 rotation
+// lands on the other side of a bf16 rounding boundary about once in 10^5 values, and one such key can
+// change which rows a step retains.  The pass is HBM-bound; the fp64 work hides behind the loads.
 #include "launch.h"
 
 namespace infmllm {

@@ -18,39 +18,6 @@ namespace {
 constexpr int TPB = 1024;
 constexpr int NW = TPB / 64;
 
-// Workgroups beyond the copy workgroups merge the key-split partials of the attention launch
-// (head_dim 128): out[row][head][:] = sum_s w_s O_s / sum_s w_s l_s with w_s = 2^(m_s - max m).
-// Nothing later in the step reads `out`, so this too runs beside the selection.
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-__device__ __forceinline__ void combine_partials(const CombineJob& cj, int first_wg, int nwg)
-{
-    constexpr int D = 128;
-    const long total = (long)cj.L * cj.Hq * (D / 8);
-    const size_t plane = (size_t)cj.L * cj.Hq;
-    uint16_t* out = (uint16_t*)cj.out;
-    for (long idx = (long)(blockIdx.x - first_wg) * TPB + threadIdx.x; idx < total; idx += (long)nwg * TPB) {
-        const int x = (int)(idx % (D / 8));
-        const long rowi = idx / (D / 8);                      // row * Hq + head
-        float mt = -__builtin_inff();
-        for (int s = 0; s < cj.nsplit; ++s) mt = fmaxf(mt, cj.part_ml[(s * plane + rowi) * 2]);
-        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, lt = 0.f;
-        for (int s = 0; s < cj.nsplit; ++s) {
-            const size_t rr = s * plane + rowi;
-            const float w = __builtin_amdgcn_exp2f(cj.part_ml[rr * 2] - mt);   // an empty split has m = -inf
-            lt += w * cj.part_ml[rr * 2 + 1];
-            const f32x4 a = *(const f32x4*)(cj.part_o + rr * D + 8 * x), b = *(const f32x4*)(cj.part_o + rr * D + 8 * x + 4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { acc[e] += w * a[e]; acc[4 + e] += w * b[e]; }
-        }
-        const float inv = 1.0f / lt;
-        bf16x8 o;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = (__bf16)(acc[e] * inv);
-        *(bf16x8*)(out + rowi * D + 8 * x) = o;
-    }
-}
-
 // Selection of kv-head h by one workgroup, candidates re-read from memory in every pass.
 __device__ __forceinline__ void select_mem_body(const float* __restrict__ Wb, int32_t* __restrict__ I,
                                                 int32_t* __restrict__ userI, int32_t* __restrict__ user_count,
@@ -159,15 +126,12 @@ __device__ __forceinline__ void select_body(const float* Wb, int32_t* I, int32_t
     else select_reg_body<KPT, TPB>(Wb, I, userI, user_count, h, cnd, r, R, B, cap);
 }
 
-// One stream: workgroups [0, Hkv) select, the next rc.ncopy move the recent window, the rest
-// merge attention partials.
+// One stream: workgroups [0, Hkv) select, the next rc.ncopy move the recent window.
 template <int KPT>
 __global__ void __launch_bounds__(TPB)
 select_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __restrict__ userI,
-              int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap, int Hkv, RecentCopy rc,
-              CombineJob cj, int ncomb)
+              int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap, int Hkv, RecentCopy rc)
 {
-    if ((int)blockIdx.x >= Hkv + rc.ncopy) { combine_partials(cj, Hkv + rc.ncopy, ncomb); return; }
     if ((int)blockIdx.x >= Hkv) { copy_recent<TPB>(rc, blockIdx.x - Hkv, Hkv, cnd, r, R, cap); return; }
     select_body<KPT>(Wb, I, userI, user_count, blockIdx.x, cnd, r, R, B, cap);
 }
@@ -198,7 +162,7 @@ select_batch_kernel(EvictBatch eb, int r, int R, int B, int cap, int Hkv, int vp
 
 hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, int32_t* user_I,
                          int32_t* user_count, const CacheView& src, const KeySource& ks, int64_t T,
-                         const CacheView& dst, const CombineJob& cj, hipStream_t st)
+                         const CacheView& dst, hipStream_t st)
 {
     const int cnd = n - g.R, r = g.B - g.R;
     RecentCopy rc;
@@ -210,15 +174,10 @@ hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, 
     const long vecs = (long)g.Hkv * g.R * rc.vpr;
     long want = (vecs + 4 * TPB - 1) / (4 * TPB);
     rc.ncopy = (int)(want > 448 ? 448 : want);
-    int ncomb = 0;
-    if (cj.nsplit > 1) {
-        const long cw = ((long)cj.L * cj.Hq * 16 + 2 * TPB - 1) / (2 * TPB);
-        ncomb = (int)(cw > 256 ? 256 : cw);
-    }
-    const dim3 grid(g.Hkv + rc.ncopy + ncomb);
+    const dim3 grid(g.Hkv + rc.ncopy);
 #define INFMLLM_SELECT(KPT)                                                                                \
     hipLaunchKernelGGL(select_kernel<KPT>, grid, dim3(TPB), 0, st, Wb, I, user_I, user_count, cnd, r, g.R, g.B, g.cap, \
-                       g.Hkv, rc, cj, ncomb)
+                       g.Hkv, rc)
     if (cnd <= 2 * TPB) INFMLLM_SELECT(2);
     else if (cnd <= 4 * TPB) INFMLLM_SELECT(4);
     else if (cnd <= 8 * TPB) INFMLLM_SELECT(8);

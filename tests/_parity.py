@@ -12,7 +12,7 @@ OUT_TOL = {torch.bfloat16: 2e-2, torch.float32: 1e-4}
 BAND = 1e-5
 
 
-def check_retained(I_gpu, I_orc, Wb, n, budget, recent):
+def check_retained(I_gpu, I_orc, Wb, n, budget, recent, band=BAND):
     """I_gpu, I_orc: [Hkv, count] int arrays.  Wb: oracle biased scores [Hkv, c] or None.
     Returns the number of (in-band) swapped keys."""
     assert I_gpu.shape == I_orc.shape, (I_gpu.shape, I_orc.shape)
@@ -33,7 +33,7 @@ def check_retained(I_gpu, I_orc, Wb, n, budget, recent):
         wr = np.sort(Wb[h])[::-1][r - 1]                      # r-th largest fp64 score
         diff = np.array(sorted(g ^ o))
         off = np.abs(Wb[h][diff] - wr)
-        assert (off <= BAND * abs(wr)).all(), (
+        assert (off <= band * abs(wr)).all(), (
             "head %d: retained sets differ outside the tie band: idx %s, |W-W_r| %s, W_r %g"
             % (h, diff[:8], off[:8], wr))
         swaps += len(diff) // 2
@@ -43,8 +43,8 @@ def check_retained(I_gpu, I_orc, Wb, n, budget, recent):
 class LockStep:
     """Drives a binding.Stream and an OracleStream with the same chunks."""
 
-    def __init__(self, gpu, oracle):
-        self.gpu, self.oracle = gpu, oracle
+    def __init__(self, gpu, oracle, band=BAND):
+        self.gpu, self.oracle, self.band = gpu, oracle, band
         self.swaps = 0
         self.max_err = 0.0
         self.steps = 0
@@ -65,7 +65,8 @@ class LockStep:
         sc = self.oracle.scores()
         I_o = self.oracle.select()
         I_g = ret_g.cpu().numpy()[:, :count]
-        self.swaps += check_retained(I_g, I_o, None if sc is None else sc[1], n, self.gpu.budget, self.gpu.recent)
+        self.swaps += check_retained(I_g, I_o, None if sc is None else sc[1], n, self.gpu.budget, self.gpu.recent,
+                                     self.band)
         if strict:
             assert (I_g == I_o).all(), "step %d: retained lists differ at %s" % (self.steps, np.argwhere(I_g != I_o)[:4])
         self.oracle.commit(I_g)
@@ -99,7 +100,8 @@ class LockStep:
         sc = self.oracle.scores()
         I_o = self.oracle.select()
         I_g = self._ret.cpu().numpy()[:, :count]
-        self.swaps += check_retained(I_g, I_o, None if sc is None else sc[1], n, self.gpu.budget, self.gpu.recent)
+        self.swaps += check_retained(I_g, I_o, None if sc is None else sc[1], n, self.gpu.budget, self.gpu.recent,
+                                     self.band)
         self.oracle.commit(I_g)
         self.steps += 1
         return I_g

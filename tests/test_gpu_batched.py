@@ -18,8 +18,7 @@ def layers(n_layers, budget, recent, heads, kv, d, dtype, bias, max_chunk, impl=
     out = []
     for _ in range(n_layers):
         gpu = B.Stream(budget, recent, heads, kv, d, dtype=DT[dtype], bias=bias, max_chunk=max_chunk, impl=impl)
-        orc = OracleStream(budget, recent, heads, kv, d, bias=float(np.float32(bias)),
-                           scale=float(np.float32(1.0 / np.sqrt(d))))
+        orc = OracleStream(budget, recent, heads, kv, d, bias=bias)
         out.append(LockStep(gpu, orc))
     return out
 

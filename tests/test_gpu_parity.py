@@ -17,14 +17,12 @@ pytestmark = pytest.mark.gpu
 DT = {"fp32": torch.float32, "bf16": torch.bfloat16}
 
 
-def pair(budget, recent, heads, kv, d, dtype, bias, max_chunk=None, impl=None, scale=None, max_decode=None):
+def pair(budget, recent, heads, kv, d, dtype, bias, max_chunk=None, impl=None, scale=None, max_decode=None,
+         attn_tile=None):
     gpu = B.Stream(budget, recent, heads, kv, d, dtype=DT[dtype], bias=bias, max_chunk=max_chunk, impl=impl, scale=scale,
-                   max_decode=max_decode)
-    orc = OracleStream(budget, recent, heads, kv, d, bias=float(np.float32(bias)),
-                       scale=None if scale is None else float(np.float32(scale)))
-    if scale is None:
-        orc_scale = float(np.float32(1.0 / np.sqrt(d)))
-        orc = OracleStream(budget, recent, heads, kv, d, bias=float(np.float32(bias)), scale=orc_scale)
+                   max_decode=max_decode, attn_tile=attn_tile)
+    # the oracle is given b and the scale as the doubles the library is given (default scale: 1/sqrt(d))
+    orc = OracleStream(budget, recent, heads, kv, d, bias=bias, scale=scale)
     return LockStep(gpu, orc)
 
 
@@ -91,10 +89,33 @@ def test_step_errors_leave_the_stream_unchanged():
     assert e.value.code == B.ECAPACITY and len(s) == 0 and s.streamed == 0
 
 
-@pytest.mark.parametrize("name,steps", [("cfg2", 10), ("cfg3", 6), ("cfg4", 13), ("cfg5", 6)])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4])
+@pytest.mark.parametrize("heads,kv,budget,recent,chunks", [
+    (4, 4, 192, 64, [64, 100, 37, 129, 192, 1, 77]),                # ragged chunks, causal tiles of every shape
+    (8, 2, 320, 128, [128, 128, 128, 45, 128]),                     # grouped heads: row blocks of one tile span heads
+])
+def test_every_attention_tile_shape(tile, heads, kv, budget, recent, chunks):
+    """INFMLLM_PARAM_ATTN_TILE forces each workgroup shape of the matrix-core attention (head_dim 128) in turn;
+    the launch normally picks one from the chunk length, so small streams would only ever reach one of them."""
+    ls = pair(budget, recent, heads, kv, 128, "bf16", 1e-3, max_chunk=max(chunks), attn_tile=tile)
+    for step, L in enumerate(chunks):
+        print("tile", tile, (heads, kv, budget, recent), "step", step, "L", L, flush=True)
+        q, k, v = random_chunk(1200 + step, L, heads, kv, 128, "bf16")
+        ls.step(q, k, v, check_state=True)
+    print("max err %.3g swaps %d" % (ls.max_err, ls.swaps))
+
+
+def test_bad_attention_tile_is_refused():
+    with pytest.raises(B.InfMLLMError) as e:
+        B.Stream(64, 16, 2, 2, 128, dtype=torch.bfloat16, attn_tile=5)
+    assert e.value.code == B.EINVAL
+
+
+@pytest.mark.parametrize("name,steps", [("cfg2", 64), ("cfg3", 17), ("cfg4", 13), ("cfg5", 6)])
 def test_full_shape_streams_lockstep(name, steps):
-    """The real layer shapes in the launch configuration the benchmark times: warm-up plus the
-    first evicting steps, every output element and every retained set against the oracle."""
+    """The real layer shapes in the launch configuration the benchmark times, every output element and every
+    retained set against the oracle: cfg2 for its whole stream of 64 chunks, cfg3 for 4 warm-up and 13 evicting
+    steps, cfg4 and cfg5 for their warm-up and first evicting steps (their later steps: the spot checks below)."""
     cfg = CONFIGS[name]
     ls = pair(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, cfg.dtype, cfg.bias, max_chunk=cfg.max_chunk)
     for step, (q, k, v) in zip(range(steps), ChunkStream(cfg)):
@@ -157,17 +178,21 @@ def test_step_properties_at_the_real_shapes(name, steps):
     print("%s: %d evicting steps checked" % (name, checked), flush=True)
 
 
-@pytest.mark.parametrize("name,skip,steps", [("cfg2", 40, 3), ("cfg4", 25, 5), ("cfg5", 47, 3)])
-def test_late_steps_spot_check(name, skip, steps):
+@pytest.mark.parametrize("name,skip,steps,layer", [("cfg2", 40, 3, 0), ("cfg3", 60, 3, 0), ("cfg4", 25, 5, 0),
+                                                   ("cfg4", 37, 4, 1), ("cfg5", 47, 3, 0), ("cfg5", 96, 3, 1)])
+def test_late_steps_spot_check(name, skip, steps, layer):
     """Steps far into a stream, which the oracle cannot reach on its own: the GPU runs `skip`
     steps alone, the oracle adopts the exported cache (bit-exact rows and positions), and the
-    next steps are compared in lock-step.  cfg5's window covers the chunk at 100 000 tokens in
-    which the recurring key bank returns; cfg4's covers a frame with a trailing text query."""
+    next steps are compared in lock-step.  cfg5's windows cover the chunks at 100 000 tokens (layer 0) and at
+    200 000 tokens (layer 1's own sub-seeded stream) in which the recurring key bank returns, and the step after
+    each; cfg4's cover frames with a trailing text query (steps 29 and 39), the second on layer 1's stream."""
     cfg = CONFIGS[name]
     ls = pair(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, cfg.dtype, cfg.bias, max_chunk=cfg.max_chunk)
-    stream = ChunkStream(cfg)
+    stream = ChunkStream(cfg, layer=layer)
     for step in range(skip):
         ls.gpu_only(*next(stream))
+        if step % 16 == 15:
+            print(name, "layer", layer, "unchecked step", step, flush=True)
     torch.cuda.synchronize()
     assert len(ls.gpu) == cfg.budget
     pos = ls.gpu.positions().cpu().numpy()
@@ -177,7 +202,7 @@ def test_late_steps_spot_check(name, skip, steps):
     for step in range(skip, skip + steps):
         print(name, "late step", step, flush=True)
         ls.step(*next(stream), check_state=(step == skip + steps - 1))
-    print("%s late: max err %.3g swaps %d" % (name, ls.max_err, ls.swaps), flush=True)
+    print("%s layer %d late: max err %.3g swaps %d" % (name, layer, ls.max_err, ls.swaps), flush=True)
 
 
 def test_more_candidates_than_fit_in_registers():
@@ -194,6 +219,35 @@ def test_more_candidates_than_fit_in_registers():
         q, k, v = random_chunk(20 + step, L, heads, kv, d, "bf16")
         ls.step(q, k, v, check_state=True)
     assert ls.gpu.last_scores().shape == (kv, budget + L - recent)
+
+
+def test_sixteen_candidates_per_thread():
+    """8192 < c <= 16384 candidates per head: the selection keeps sixteen keys per thread in registers."""
+    heads, kv, d, budget, recent, L = 2, 1, 64, 12100, 200, 128
+    ls = pair(budget, recent, heads, kv, d, "bf16", 1e-3, max_chunk=L)
+    g = torch.Generator().manual_seed(12)
+    K = torch.randn((kv, budget, d), generator=g).bfloat16()
+    V = torch.randn((kv, budget, d), generator=g).bfloat16()
+    pos = torch.arange(budget, dtype=torch.int32).repeat(kv, 1)
+    ls.gpu.load(K.cuda(), V.cuda(), pos.cuda().contiguous(), budget)
+    ls.oracle.load(K.double().numpy(), V.double().numpy(), pos.numpy(), budget)
+    for step in range(2):
+        q, k, v = random_chunk(30 + step, L, heads, kv, d, "bf16")
+        ls.step(q, k, v, check_state=True)
+    assert ls.gpu.last_scores().shape == (kv, budget + L - recent)
+
+
+@pytest.mark.parametrize("d", [128, 64])
+def test_more_scored_rows_than_the_scoring_kernel_keeps_in_lds(d):
+    """G * l_q = 8 * 1024 scored rows per kv-head: beyond 4096 the scoring kernel reads each staged row's
+    log-sum-exp from memory instead of from its LDS copy."""
+    heads, kv, budget, recent, L = 8, 1, 2048, 1024, 1024
+    ls = pair(budget, recent, heads, kv, d, "bf16", 1e-3, max_chunk=L)
+    for step in range(4):                                          # two warm-up steps, two evicting ones
+        print("direct lse d", d, "step", step, flush=True)
+        q, k, v = random_chunk(1300 + step, L, heads, kv, d, "bf16")
+        ls.step(q, k, v, check_state=(step == 3))
+    print("max err %.3g swaps %d" % (ls.max_err, ls.swaps))
 
 
 @pytest.mark.parametrize("d", [64, 128])

@@ -16,8 +16,7 @@ DT = {"fp32": torch.float32, "bf16": torch.bfloat16}
 def pair(policy, budget, recent, heads, kv, d, dtype, bias, max_chunk, impl=None, max_decode=None):
     gpu = B.Stream(budget, recent, heads, kv, d, dtype=DT[dtype], bias=bias, max_chunk=max_chunk, impl=impl,
                    policy=policy, max_decode=max_decode)
-    orc = OracleStream(budget, recent, heads, kv, d, bias=float(np.float32(bias)),
-                       scale=float(np.float32(1.0 / np.sqrt(d))), policy=policy)
+    orc = OracleStream(budget, recent, heads, kv, d, bias=bias, policy=policy)
     return LockStep(gpu, orc)
 
 

@@ -1,5 +1,7 @@
 """Cache-relative rotary position encoding (Sec. 3.4 length extrapolation) through the C ABI, in lock-step
-with the fp64 oracle, which turns keys and queries the same way and rounds them to the stream type."""
+with the fp64 oracle: once with the oracle storing its rotated q and k in the stream's element type (as a
+model stores them; usual 1e-5 band), once with the oracle keeping them exact (band widened by what that
+one rounding can do to a score, derived in the test)."""
 import numpy as np
 import pytest
 import torch
@@ -14,13 +16,38 @@ DT = {"fp32": torch.float32, "bf16": torch.bfloat16}
 BASE = 10000.0
 
 
-def pair(budget, recent, heads, kv, d, dtype, bias, max_chunk, impl=None, max_decode=None, policy=None, base=BASE):
+def pair(budget, recent, heads, kv, d, dtype, bias, max_chunk, impl=None, max_decode=None, policy=None, base=BASE,
+         exact=False, band=None):
     gpu = B.Stream(budget, recent, heads, kv, d, dtype=DT[dtype], bias=bias, max_chunk=max_chunk, impl=impl,
                    max_decode=max_decode, policy=policy, rope_base=base)
-    orc = OracleStream(budget, recent, heads, kv, d, bias=float(np.float32(bias)),
-                       scale=float(np.float32(1.0 / np.sqrt(d))), policy=policy or "infmllm",
-                       rope_base=base, rope_round=dtype)
-    return LockStep(gpu, orc)
+    orc = OracleStream(budget, recent, heads, kv, d, bias=bias, policy=policy or "infmllm",
+                       rope_base=base, rope_round=None if exact else dtype)
+    return LockStep(gpu, orc) if band is None else LockStep(gpu, orc, band=band)
+
+
+@pytest.mark.parametrize("heads,kv,d,dtype,impl,budget,recent,lens", [
+    (4, 4, 128, "bf16", 0, 192, 64, [64, 64, 64, 64, 64, 64]),
+    (8, 2, 128, "bf16", 0, 160, 48, [100, 37, 64, 1, 129, 77, 5, 160]),
+    (8, 2, 128, "bf16", 1, 160, 48, [100, 37, 64, 1, 129, 77]),
+    (4, 2, 64, "bf16", 0, 128, 32, [64, 64, 50, 64, 64]),
+    (4, 4, 64, "fp32", None, 128, 32, [64, 64, 40, 64, 64]),
+    (2, 2, 128, "fp32", None, 96, 24, [48, 48, 48, 48]),
+])
+def test_rope_streams_match_the_unrounded_oracle(heads, kv, d, dtype, impl, budget, recent, lens):
+    """Against the oracle that keeps its rotated q and k exact (no rounding to the stream type).
+    Outputs: the usual 2e-2 / 1e-4.  Retained sets: storing a rotated element in bf16 moves it by at most
+    2^-9 relative, so a logit scale * sum_i q_i k_i moves by at most 2^-8 * scale * sum_i |q_i k_i|; for the
+    N(0,1) inputs used here E|q_i k_i| = 2/pi, so that is 2^-8 * (2/pi) * sqrt(d) <= 0.029 for d = 128
+    (typically a tenth of it, the errors having random signs), i.e. a weight moves by at most
+    exp(0.029) - 1 = 2.9e-2 relative, and so does a column mean.  Band: 3e-2 relative for bf16 streams.
+    For fp32 streams the same bound with 2^-24 is 2e-6, inside the ordinary 1e-5 band."""
+    band = 3e-2 if dtype == "bf16" else 1e-5
+    ls = pair(budget, recent, heads, kv, d, dtype, 1e-3, max(lens), impl=impl, exact=True, band=band)
+    for step, L in enumerate(lens):
+        print("rope exact", (heads, kv, d, dtype, impl, budget, recent), "step", step, "L", L, flush=True)
+        q, k, v = random_chunk(700 + step, L, heads, kv, d, dtype)
+        ls.step(q, k, v, check_state=True)
+    print("max err %.3g swaps %d" % (ls.max_err, ls.swaps))
 
 
 @pytest.mark.parametrize("heads,kv,d,dtype,impl,budget,recent,lens", [

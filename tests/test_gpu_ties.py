@@ -31,14 +31,16 @@ def coded_chunk(seed, L, heads, kv, d, dtype, n_codes, t0):
     (4, 2, 128, "bf16", None, 192, 64, [100, 100, 64, 37, 128], 2),
     (4, 4, 128, "bf16", None, 192, 64, [100, 100, 64, 37, 128], 3),
     (4, 4, 128, "bf16", None, 160, 33, [97, 97, 97, 97], 7),
-    (2, 2, 64, "bf16", 0, 128, 32, [64, 64, 50, 64], 3),                 # plain-arithmetic kernels
+    (2, 2, 64, "bf16", 0, 128, 32, [64, 64, 50, 64], 3),                 # matrix-core kernels, head_dim 64
+    (2, 2, 64, "bf16", 1, 128, 32, [64, 64, 50, 64], 3),                 # plain-arithmetic kernels on a bf16 stream
+    (4, 2, 128, "bf16", 1, 192, 64, [100, 100, 64, 37, 128], 2),         # ... grouped heads, head_dim 128
     (2, 2, 64, "fp32", None, 128, 32, [64, 64, 50, 64], 2),
     (2, 2, 128, "bf16", None, 1536, 256, [1024, 1000, 512, 512], 3),     # 16 wavefronts' worth of candidates
     (2, 1, 128, "bf16", None, 3000, 200, [2048, 2048, 1111], 5),         # four keys per thread
 ])
 def test_exact_ties_go_to_the_newer_rows(heads, kv, d, dtype, impl, budget, recent, lens, n_codes):
     gpu = B.Stream(budget, recent, heads, kv, d, dtype=DT[dtype], bias=0.0, max_chunk=max(lens), impl=impl)
-    orc = OracleStream(budget, recent, heads, kv, d, bias=0.0, scale=float(np.float32(1.0 / np.sqrt(d))))
+    orc = OracleStream(budget, recent, heads, kv, d, bias=0.0)
     ls = LockStep(gpu, orc)
     t0 = 0
     for step, L in enumerate(lens):
