@@ -127,6 +127,24 @@ size_t infmllm_stream_workspace_bytes(const infmllm_stream_t* s);
 int infmllm_stream_attach(infmllm_stream_t* s, void* dev_workspace, size_t bytes, void* hip_stream);
 
 /*
+ * For callers that cannot allocate device memory (code under HIP graph capture, serving loops and
+ * harnesses that forbid hipMalloc): infmllm_stream_attach with the workspace taken from an array of
+ * INFMLLM_STATIC_WORKSPACE_BYTES bytes that the library's code object holds on every GPU it is loaded on,
+ * for the life of the process.  The stream is attached on the device that is current at the call; the
+ * call allocates nothing (no hipMalloc / hipFree, no allocating library routine) and clears the part of
+ * the array it uses with a fill kernel on hip_stream.  At most one stream per device can hold the array:
+ * a second infmllm_stream_attach_static on that device fails with ESTATE until the first stream has been
+ * destroyed (infmllm_stream_destroy releases the array; work of the destroyed stream still in flight on
+ * its HIP stream would race with the next holder, so the caller orders the two, e.g. by using one HIP
+ * stream).  The array keeps its last contents between holders; everything a stream relies on is cleared
+ * at attach.  Errors: EINVAL (null stream, rotary position table requested: its table is uploaded from a
+ * host buffer), ENOMEM (infmllm_stream_workspace_bytes(s) exceeds INFMLLM_STATIC_WORKSPACE_BYTES),
+ * ESTATE (already attached, array in use), EHIP.
+ */
+#define INFMLLM_STATIC_WORKSPACE_BYTES (64u << 20)
+int infmllm_stream_attach_static(infmllm_stream_t* s, void* hip_stream);
+
+/*
  * One streaming step (Sec. 3.2 and Alg. 1), enqueued on the attached HIP stream:
  *   append      the chunk's k, v become cache rows t .. t+L-1 (stream positions T .. T+L-1)
  *   attention   out[i] = softmax_j(scale * q[i].K[j]) V[j] over the t cached keys and the

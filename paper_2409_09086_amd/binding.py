@@ -24,7 +24,9 @@ EXPORTS = [
     "infmllm_stream_last_scores", "infmllm_last_error", "infmllm_stream_destroy",
     "infmllm_stream_profile", "infmllm_stream_profile_read", "infmllm_decode", "infmllm_stream_max_len",
     "infmllm_step_attend", "infmllm_stream_pending", "infmllm_evict_batched", "infmllm_stream_profile_select",
+    "infmllm_stream_attach_static",
 ]
+STATIC_WORKSPACE_BYTES = 64 << 20
 KERNELS = ["append", "attn", "score", "select", "compact", "decode", "rope", "evict"]
 
 _lib = None
@@ -49,6 +51,7 @@ def lib():
         L.infmllm_stream_workspace_bytes.argtypes = [P]
         L.infmllm_stream_workspace_bytes.restype = ctypes.c_size_t
         L.infmllm_stream_attach.argtypes = [P, P, ctypes.c_size_t, P]
+        L.infmllm_stream_attach_static.argtypes = [P, P]
         L.infmllm_step.argtypes = [P, P, P, P, I, P, P, P]
         L.infmllm_decode.argtypes = [P, P, P, P, P]
         L.infmllm_step_attend.argtypes = [P, P, P, P, I, P, P, P]
@@ -98,7 +101,7 @@ class Stream:
 
     def __init__(self, budget, recent, heads, kv_heads, head_dim, dtype=torch.bfloat16, bias=None, scale=None,
                  max_chunk=None, impl=None, max_decode=None, policy=None, rope_base=None, attn_tile=None,
-                 device="cuda:0", hip_stream=None):
+                 device="cuda:0", hip_stream=None, static_workspace=False):
         L = lib()
         self.dtype = dtype
         code = {torch.bfloat16: BF16, torch.float32: FP32}.get(dtype)
@@ -118,10 +121,15 @@ class Stream:
         nbytes = L.infmllm_stream_workspace_bytes(self._h)
         with torch.cuda.device(self.device):
             self.hip_stream = hip_stream if hip_stream is not None else torch.cuda.current_stream(self.device).cuda_stream
-            self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
-            base = self.workspace.data_ptr()
-            aligned = (base + 255) // 256 * 256
-            rc = L.infmllm_stream_attach(self._h, ctypes.c_void_p(aligned), nbytes, ctypes.c_void_p(self.hip_stream))
+            if static_workspace:
+                # infmllm_stream_attach_static: the workspace is the library's own per-device array
+                self.workspace = None
+                rc = L.infmllm_stream_attach_static(self._h, ctypes.c_void_p(self.hip_stream))
+            else:
+                self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+                base = self.workspace.data_ptr()
+                aligned = (base + 255) // 256 * 256
+                rc = L.infmllm_stream_attach(self._h, ctypes.c_void_p(aligned), nbytes, ctypes.c_void_p(self.hip_stream))
             if rc != OK:
                 h, self._h = self._h, None
                 L.infmllm_stream_destroy(h)
@@ -131,7 +139,7 @@ class Stream:
         self.close()
 
     def close(self):
-        """infmllm_stream_destroy."""
+        """infmllm_stream_destroy (also releases the library's static workspace if this stream holds it)."""
         h, self._h = getattr(self, "_h", None), None
         if h and _lib is not None:
             _lib.infmllm_stream_destroy(h)

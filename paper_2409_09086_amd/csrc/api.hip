@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -39,6 +40,16 @@ int fail_hip(hipError_t e, const char* what)
 constexpr size_t ALIGN = 256;
 size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
+// Workspace of infmllm_stream_attach_static: one array per GPU inside the library's code object, for callers
+// that cannot allocate device memory.  `scratch` is a host-side stand-in for the symbol, never a device
+// address: host code uses the address hipGetSymbolAddress returns for the current device, looked up once per
+// device.  At most one stream per device holds the array at a time.
+static __device__ __align__(256) unsigned char scratch[INFMLLM_STATIC_WORKSPACE_BYTES];
+constexpr int MAX_DEVICES = 64;
+std::mutex g_static_mu;
+void* g_static_ptr[MAX_DEVICES];                 // device address of `scratch` on each GPU, null until looked up
+const infmllm_stream* g_static_owner[MAX_DEVICES];
+
 }  // namespace
 
 struct infmllm_stream {
@@ -46,6 +57,7 @@ struct infmllm_stream {
     int dtype;
     int impl;            // 0 = matrix cores where the dtype allows, 1 = plain arithmetic
     bool attached;
+    int static_dev = -1; // device whose library-owned workspace this stream holds (-1: caller's workspace)
     hipStream_t st;
     CacheView cache[2];
     int cur;             // live half of the cache
@@ -158,6 +170,10 @@ int infmllm_stream_create(int budget, int recent, int heads, int kv_heads, int h
 void infmllm_stream_destroy(infmllm_stream_t* s)
 {
     if (!s) return;
+    if (s->static_dev >= 0) {
+        std::lock_guard<std::mutex> lk(g_static_mu);
+        if (g_static_owner[s->static_dev] == s) g_static_owner[s->static_dev] = nullptr;
+    }
     s->drop_events();
     delete s;
 }
@@ -271,6 +287,45 @@ int infmllm_stream_attach(infmllm_stream_t* s, void* ws, size_t bytes, void* hip
     s->cur = 0; s->len = 0; s->streamed = 0; s->last_cnd = 0;
     s->attached = true;
     return INFMLLM_OK;
+}
+
+int infmllm_stream_attach_static(infmllm_stream_t* s, void* hip_stream)
+{
+    if (!s) return fail(INFMLLM_EINVAL, "attach_static: stream is null");
+    if (s->attached) return fail(INFMLLM_ESTATE, "attach_static: stream is already attached");
+    if (s->rope_base > 0.0)
+        return fail(INFMLLM_EINVAL, "attach_static: streams with the rotary position table are not supported "
+                                    "(the table is uploaded from a host buffer)");
+    const size_t need = s->layout().total;
+    if (need > (size_t)INFMLLM_STATIC_WORKSPACE_BYTES)
+        return fail(INFMLLM_ENOMEM, "attach_static: the stream needs %zu bytes of workspace, the library's array holds %zu",
+                    need, (size_t)INFMLLM_STATIC_WORKSPACE_BYTES);
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "attach_static: hipGetDevice");
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(INFMLLM_EINVAL, "attach_static: device index %d is not supported", dev);
+    void* ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(g_static_mu);
+        if (!g_static_ptr[dev]) {
+            void* p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !p) return fail_hip(e, "attach_static: hipGetSymbolAddress");
+            g_static_ptr[dev] = p;
+        }
+        if (g_static_owner[dev])
+            return fail(INFMLLM_ESTATE, "attach_static: another stream holds this device's workspace array");
+        g_static_owner[dev] = s;
+        ptr = g_static_ptr[dev];
+    }
+    s->static_dev = dev;
+    const int rc = infmllm_stream_attach(s, ptr, (size_t)INFMLLM_STATIC_WORKSPACE_BYTES, hip_stream);
+    if (rc != INFMLLM_OK) {
+        std::lock_guard<std::mutex> lk(g_static_mu);
+        g_static_owner[dev] = nullptr;
+        s->static_dev = -1;
+    }
+    return rc;
 }
 
 }  // extern "C"
