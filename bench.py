@@ -36,13 +36,19 @@ def algorithmic_work(cfg, L, t):
     pairs = L * t + L * (L + 1) // 2                         # visible (query, key) pairs per head
     c, lq, r = n - R, min(R, L), B - R
     row = 2 * (2 * d * elt) + 16                            # K and V read + written, position and score
+    # Rows an eviction actually moves in steady state: the retained rows that are not already inside physical
+    # rows 0..B-1, i.e. the chunk's survivors.  With L <= R (all five workloads) every chunk row is inside the
+    # recent window, so that is exactly L rows per kv-head; the r + R - L retained cached rows stay in place.
+    moved = min(L, R)
     return {
         "attn": {"flops": 4.0 * d * pairs * Hq, "bytes": elt * d * (2 * n * Hkv + 2 * L * Hq)},
         "score": {"flops": 2.0 * d * lq * c * Hq, "bytes": elt * d * (c * Hkv + lq * Hq) + 4 * c * Hkv},
         "append": {"bytes": 2 * (2 * L * Hkv * d * elt) + 8 * L * Hkv},
-        # the select launch also moves the R recent rows (always kept) on workgroups of its own
-        "select": {"bytes": 4 * c * Hkv + 4 * B * Hkv + row * R * Hkv},
-        "compact": {"bytes": row * r * Hkv},
+        # selection launch: W' read, the index list written twice (stream scratch and the caller's), and the
+        # placement plan: old row table read, rank / new row table / score written for the rows that stay
+        "select": {"bytes": (4 * c + 8 * B + 16 * (B - moved) + 12 * moved) * Hkv},
+        # placement launch: the moved rows' K and V read and written, their table entries
+        "compact": {"bytes": (row + 12 + 12) * moved * Hkv, "rows_moved": moved * Hkv},
         # position-encoding pre-pass: every cached key, the chunk's keys and the queries read and written once
         "rope": {"bytes": 2 * elt * d * (n * Hkv + L * Hq)},
     }

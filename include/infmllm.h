@@ -90,7 +90,7 @@ enum {
 /*
  * Creates a stream (Alg. 1 inputs: retrieval/recent window, number of relevant tokens,
  * given here as budget = r + recent).  Host-only: touches no device.
- *   budget   > 0   rows kept after every step (B)
+ *   budget   1..131072  rows kept after every step (B)
  *   recent   0..budget  newest rows that are always kept (R); r = budget - recent
  *   heads    query heads; kv_heads divides heads (grouped-query attention pools the
  *            heads/kv_heads query heads of a group by their mean before ranking)
@@ -119,9 +119,10 @@ size_t infmllm_stream_workspace_bytes(const infmllm_stream_t* s);
  * Hands the stream its device workspace (256-byte aligned, at least
  * infmllm_stream_workspace_bytes(s) bytes, caller-owned) and the HIP stream (a
  * hipStream_t passed as void*, null for the default stream) all later work is enqueued
- * on.  The workspace holds the cache (two copies of K and V of budget + max_chunk rows per
- * kv-head, stream positions and scores) and per-step temporaries; attach enqueues a clear of
- * the whole workspace on that stream.  The cache starts empty.  Errors: EINVAL (null/misaligned workspace),
+ * on.  The workspace holds the cache (one copy of K and V of budget + max_decode + max_chunk rows per
+ * kv-head, stream positions, scores and the two tables that map physical rows to stream order and back:
+ * an eviction leaves the retained rows where they are and only moves the chunk's survivors into the rows
+ * it frees) and per-step temporaries; attach enqueues a clear of the whole workspace on that stream.  The cache starts empty.  Errors: EINVAL (null/misaligned workspace),
  * ENOMEM (too small), ESTATE (already attached), EHIP.
  */
 int infmllm_stream_attach(infmllm_stream_t* s, void* dev_workspace, size_t bytes, void* hip_stream);

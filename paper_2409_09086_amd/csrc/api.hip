@@ -1,6 +1,6 @@
 // Host side of the C ABI declared in include/infmllm.h: argument checks, workspace carving,
-// the host bookkeeping of one stream (cached length, tokens streamed, which half of the
-// double-buffered cache is live) and the sequence of kernel launches that makes up one
+// the host bookkeeping of one stream (cached length, tokens streamed, which of the two
+// stream-order tables is live) and the sequence of kernel launches that makes up one
 // streaming step.  No device memory is allocated here and nothing synchronises.
 #include "../../include/infmllm.h"
 
@@ -59,8 +59,8 @@ struct infmllm_stream {
     bool attached;
     int static_dev = -1; // device whose library-owned workspace this stream holds (-1: caller's workspace)
     hipStream_t st;
-    CacheView cache[2];
-    int cur;             // live half of the cache
+    CacheView cache;     // cache.row is the live stream-order table, cache.row_next the one an eviction writes
+    MoveList mv;         // retained rows the pending or running eviction moves
     int len;             // rows cached
     int64_t streamed;    // tokens streamed so far
     int last_cnd;        // candidates of the most recent evicting step (0 = none)
@@ -102,7 +102,8 @@ struct infmllm_stream {
     }
 
     struct Layout {
-        size_t K[2], V[2], pos[2], score[2], lse, Wb, I, score_part, dec_part, K_rot, kc_rot, q_rot, rope_tab, total;
+        size_t K, V, pos, score, rank, row[2], lse, Wb, I, mv_src, mv_dst, mv_x, mv_count, score_part, dec_part, K_rot,
+            kc_rot, q_rot, rope_tab, total;
     };
     Layout layout() const
     {
@@ -110,15 +111,21 @@ struct infmllm_stream {
         size_t off = 0;
         const size_t kv = up(((size_t)g.Hkv * g.cap + CACHE_PAD_ROWS) * g.d * g.elt);
         const size_t ps = up((size_t)g.Hkv * g.cap * 4);
-        for (int i = 0; i < 2; ++i) {
-            L.K[i] = off; off += kv;
-            L.V[i] = off; off += kv;
-            L.pos[i] = off; off += ps;
-            L.score[i] = off; off += ps;
-        }
+        L.K = off; off += kv;
+        L.V = off; off += kv;
+        L.pos = off; off += ps;
+        L.score = off; off += ps;
+        L.rank = off; off += ps;
+        L.row[0] = off; off += ps;
+        L.row[1] = off; off += ps;
         L.lse = off; off += up((size_t)g.Hq * g.max_chunk * 4);
         L.Wb = off; off += ps;
         L.I = off; off += up((size_t)g.Hkv * g.B * 4);
+        const size_t ml = up((size_t)g.Hkv * (g.max_chunk + g.max_decode) * 4);
+        L.mv_src = off; off += ml;
+        L.mv_dst = off; off += ml;
+        L.mv_x = off; off += ml;
+        L.mv_count = off; off += up((size_t)g.Hkv * 4);
         // row-split scoring (bf16 streams): partial column sums and arrival counters
         L.score_part = off; off += up(g.elt == 2 ? (size_t)SCORE_SPLIT_WGS * (256 + 1) * 4 : 0);
         L.dec_part = off; off += up(g.max_decode > 0 ? (size_t)g.Hq * DECODE_MAX_SPLIT * (g.d + 2) * 4 + (size_t)g.Hkv * 4 : 0);
@@ -150,8 +157,8 @@ int infmllm_stream_create(int budget, int recent, int heads, int kv_heads, int h
         return fail(INFMLLM_EINVAL, "create: head_dim must be 64 or 128 (got %d)", head_dim);
     if (dtype != INFMLLM_BF16 && dtype != INFMLLM_FP32)
         return fail(INFMLLM_EINVAL, "create: unknown dtype %d", dtype);
-    if ((long)budget * 2 > (1L << 24))
-        return fail(INFMLLM_EINVAL, "create: budget %d is beyond the supported 8M rows", budget);
+    if (budget > 131072)
+        return fail(INFMLLM_EINVAL, "create: budget %d is beyond the supported 131072 rows", budget);
     infmllm_stream* s = new (std::nothrow) infmllm_stream();
     if (!s) return fail(INFMLLM_ENOMEM, "create: out of host memory");
     s->g.B = budget; s->g.R = recent; s->g.Hq = heads; s->g.Hkv = kv_heads; s->g.G = heads / kv_heads;
@@ -161,7 +168,7 @@ int infmllm_stream_create(int budget, int recent, int heads, int kv_heads, int h
     s->g.bias = 1e-4;
     s->g.policy = POLICY_INFMLLM;
     s->g.attn_tile = 0;
-    s->dtype = dtype; s->impl = 0; s->attached = false; s->st = nullptr; s->cur = 0; s->len = 0;
+    s->dtype = dtype; s->impl = 0; s->attached = false; s->st = nullptr; s->len = 0;
     s->streamed = 0; s->last_cnd = 0; s->lse = nullptr; s->Wb = nullptr; s->I = nullptr;
     *out = s;
     return INFMLLM_OK;
@@ -247,12 +254,18 @@ int infmllm_stream_attach(infmllm_stream_t* s, void* ws, size_t bytes, void* hip
         hipError_t e = launch_zero(ws, L.total, (hipStream_t)hip_stream);
         if (e != hipSuccess) return fail_hip(e, "attach: clearing the workspace");
     }
-    for (int i = 0; i < 2; ++i) {
-        s->cache[i].K = base + L.K[i];
-        s->cache[i].V = base + L.V[i];
-        s->cache[i].pos = (int32_t*)(base + L.pos[i]);
-        s->cache[i].score = (float*)(base + L.score[i]);
-    }
+    s->cache.K = base + L.K;
+    s->cache.V = base + L.V;
+    s->cache.pos = (int32_t*)(base + L.pos);
+    s->cache.score = (float*)(base + L.score);
+    s->cache.rank = (int32_t*)(base + L.rank);
+    s->cache.row = (int32_t*)(base + L.row[0]);
+    s->cache.row_next = (int32_t*)(base + L.row[1]);
+    s->mv.src = (int32_t*)(base + L.mv_src);
+    s->mv.dst = (int32_t*)(base + L.mv_dst);
+    s->mv.x = (int32_t*)(base + L.mv_x);
+    s->mv.count = (int32_t*)(base + L.mv_count);
+    s->mv.max = s->g.max_chunk + s->g.max_decode;
     s->lse = (float*)(base + L.lse);
     s->Wb = (float*)(base + L.Wb);
     s->I = (int32_t*)(base + L.I);
@@ -284,7 +297,7 @@ int infmllm_stream_attach(infmllm_stream_t* s, void* ws, size_t bytes, void* hip
         if (e != hipSuccess) return fail_hip(e, "attach: position table");
     }
     s->st = (hipStream_t)hip_stream;
-    s->cur = 0; s->len = 0; s->streamed = 0; s->last_cnd = 0;
+    s->len = 0; s->streamed = 0; s->last_cnd = 0;
     s->attached = true;
     return INFMLLM_OK;
 }
@@ -349,13 +362,13 @@ int step_front(infmllm_stream* s, const void* q, const void* k, const void* v, i
         return fail(INFMLLM_ECAPACITY, "%s: stream positions would exceed 2^31-1", who);
 
     const Geometry& g = s->g;
-    const CacheView& cur = s->cache[s->cur];
+    const CacheView& cur = s->cache;
     const int t = s->len, n = t + L;
     const bool mfma = (s->dtype == INFMLLM_BF16 && s->impl == 0);
     hipError_t e;
 
-    // An evicting step on the matrix-core path never appends: attention, scoring and the gather
-    // read the chunk's rows in place and the gather writes the survivors into the other half.
+    // An evicting step on the matrix-core path never appends: attention and scoring read the chunk's
+    // rows in place and the placement writes the survivors into the rows the eviction frees.
     const bool in_place = mfma && n > g.B;
     const KeySource ks = in_place ? KeySource{t, k, v} : KeySource{n, nullptr, nullptr};
     if (!in_place) {
@@ -371,8 +384,8 @@ int step_front(infmllm_stream* s, const void* q, const void* k, const void* v, i
     if (s->rope_base > 0.0) {
         s->mark(INFMLLM_K_ROPE, 0);
         const int have = s->rot_rows < t ? s->rot_rows : t;
-        e = launch_rope(g, cur.K, s->K_rot, have, in_place ? t : n, in_place ? k : nullptr, s->kc_rot, q, s->q_rot, t, L,
-                        s->rope_tab, s->st);
+        e = launch_rope(g, cur.K, s->K_rot, cur.rank, have, in_place ? t : n, in_place ? k : nullptr, s->kc_rot, q,
+                        s->q_rot, t, L, s->rope_tab, s->st);
         if (e != hipSuccess) return fail_hip(e, "position encoding");
         s->mark(INFMLLM_K_ROPE, 1);
         att.K = s->K_rot;
@@ -411,12 +424,12 @@ int step_front(infmllm_stream* s, const void* q, const void* k, const void* v, i
 // host bookkeeping once a5-a7 of a step of L tokens (n keys before eviction) have been launched
 void step_done(infmllm_stream* s, int n, int L)
 {
-    s->cur ^= 1;
+    std::swap(s->cache.row, s->cache.row_next);
     s->len = s->g.B;
     s->last_cnd = n - s->g.R;
     s->streamed += L;
     s->pending = false;
-    s->rot_rows = 0;                                          // the rows have moved: their turned copies are stale
+    s->rot_rows = 0;                                          // every row has a new stream-order index: the turned copies are stale
     if (s->prof_steps < s->prof_cap) ++s->prof_steps;
 }
 
@@ -432,16 +445,17 @@ int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* 
     const int rc = step_front(s, q, k, v, L, out, retained, n_retained, &evict, &ks, "step");
     if (rc != INFMLLM_OK || !evict) return rc;
     const Geometry& g = s->g;
-    const CacheView& cur = s->cache[s->cur];
-    const CacheView& nxt = s->cache[s->cur ^ 1];
     const int n = s->len + L;
     hipError_t e;
     s->mark(INFMLLM_K_SELECT, 0);
-    if ((e = launch_select(g, s->Wb, n, s->I, retained, n_retained, cur, ks, s->streamed, nxt, s->st)) != hipSuccess)
+    if ((e = launch_select(g, s->Wb, n, ks.rows, s->I, retained, n_retained, s->cache, s->mv, s->st)) != hipSuccess)
         return fail_hip(e, "step: select");
     s->mark(INFMLLM_K_SELECT, 1);
     s->mark(INFMLLM_K_COMPACT, 0);
-    if ((e = launch_compact(g, cur, ks, s->streamed, nxt, s->I, s->Wb, n, s->st)) != hipSuccess) return fail_hip(e, "step: compact");
+    // rows that can need a new home: the chunk rows read in place and the cached rows at or above the budget
+    const int nmax = (n - ks.rows) + (ks.rows > g.B ? ks.rows - g.B : 0);
+    if ((e = launch_place(g, s->cache, ks, s->streamed, s->mv, s->Wb, nmax, s->st)) != hipSuccess)
+        return fail_hip(e, "step: placement");
     s->mark(INFMLLM_K_COMPACT, 1);
     step_done(s, n, L);
     return INFMLLM_OK;
@@ -476,29 +490,32 @@ int infmllm_evict_batched(infmllm_stream_t* const* streams, int count, int32_t* 
             if (streams[j] == s) return fail(INFMLLM_EINVAL, "evict_batched: stream %d appears twice", i);
         const Geometry &a = s->g, &b = s0->g;
         if (a.B != b.B || a.R != b.R || a.Hq != b.Hq || a.Hkv != b.Hkv || a.d != b.d || a.cap != b.cap ||
-            a.elt != b.elt || s->st != s0->st)
+            a.elt != b.elt || a.max_chunk != b.max_chunk || a.max_decode != b.max_decode || s->st != s0->st)
             return fail(INFMLLM_EINVAL, "evict_batched: stream %d differs from stream 0 in geometry or HIP stream", i);
     }
     infmllm_stream* lead = streams[0];
     for (int base = 0; base < count; base += EVICT_MAX_JOBS) {
         EvictBatch eb{};
         eb.count = count - base < EVICT_MAX_JOBS ? count - base : EVICT_MAX_JOBS;
+        int nmax = 0;
         for (int j = 0; j < eb.count; ++j) {
             infmllm_stream* s = streams[base + j];
             EvictJob& job = eb.job[j];
             job.Wb = s->Wb; job.I = s->I;
             job.user_I = retained ? retained[base + j] : nullptr;
             job.user_count = n_retained ? n_retained[base + j] : nullptr;
-            job.src = s->cache[s->cur]; job.dst = s->cache[s->cur ^ 1];
+            job.c = s->cache; job.mv = s->mv;
             job.kc = s->pend_ks.k; job.vc = s->pend_ks.v;
             job.tc = s->pend_ks.rows; job.pos0 = (int)s->streamed; job.n = s->pend_n;
+            const int m = (job.n - job.tc) + (job.tc > s->g.B ? job.tc - s->g.B : 0);
+            nmax = m > nmax ? m : nmax;
         }
         hipError_t e;
         lead->mark(INFMLLM_K_SELECT, 0);
         if ((e = launch_select_batch(lead->g, eb, lead->st)) != hipSuccess) return fail_hip(e, "evict_batched: select");
         lead->mark(INFMLLM_K_SELECT, 1);
         lead->mark(INFMLLM_K_COMPACT, 0);
-        if ((e = launch_compact_batch(lead->g, eb, lead->st)) != hipSuccess) return fail_hip(e, "evict_batched: compact");
+        if ((e = launch_place_batch(lead->g, eb, nmax, lead->st)) != hipSuccess) return fail_hip(e, "evict_batched: placement");
         lead->mark(INFMLLM_K_COMPACT, 1);
         for (int j = 0; j < eb.count; ++j) step_done(streams[base + j], streams[base + j]->pend_n, streams[base + j]->pend_L);
     }
@@ -573,18 +590,18 @@ int infmllm_decode(infmllm_stream_t* s, const void* q, const void* k, const void
     if (s->rope_base > 0.0) {
         // the token's row enters the cache as given; the decoding kernels see the turned copies (and put the
         // turned key at row t of K_rot themselves)
-        const CacheView& cur = s->cache[s->cur];
+        const CacheView& cur = s->cache;
         const int t = s->len;
         if ((e = launch_append(s->g, cur, k, v, t, 1, s->streamed, s->st)) != hipSuccess) return fail_hip(e, "decode: append");
-        e = launch_rope(s->g, cur.K, s->K_rot, s->rot_rows < t ? s->rot_rows : t, t, k, s->kc_rot, q, s->q_rot, t, 1,
-                        s->rope_tab, s->st);
+        e = launch_rope(s->g, cur.K, s->K_rot, cur.rank, s->rot_rows < t ? s->rot_rows : t, t, k, s->kc_rot, q, s->q_rot,
+                        t, 1, s->rope_tab, s->st);
         if (e != hipSuccess) return fail_hip(e, "decode: position encoding");
         CacheView att = cur;
         att.K = s->K_rot;
         e = launch_decode(s->g, att, s->q_rot, s->kc_rot, v, t, s->streamed, out, s->dec_part, DECODE_MAX_SPLIT, s->st);
         s->rot_rows = t + 1;
     } else {
-        e = launch_decode(s->g, s->cache[s->cur], q, k, v, s->len, s->streamed, out, s->dec_part, DECODE_MAX_SPLIT, s->st);
+        e = launch_decode(s->g, s->cache, q, k, v, s->len, s->streamed, out, s->dec_part, DECODE_MAX_SPLIT, s->st);
     }
     if (e != hipSuccess) return fail_hip(e, "decode");
     s->mark(INFMLLM_K_DECODE, 1);
@@ -614,8 +631,8 @@ int infmllm_stream_positions(infmllm_stream_t* s, int32_t* pos)
     if (!s || !pos) return fail(INFMLLM_EINVAL, "positions: null argument");
     if (!s->attached) return fail(INFMLLM_ESTATE, "positions: stream has no workspace attached");
     if (s->pending) return fail(INFMLLM_ESTATE, "positions: an eviction is pending on this stream");
-    return copy_rows(s, pos, (size_t)(s->g.B + s->g.max_decode) * 4, s->cache[s->cur].pos, (size_t)s->g.cap * 4, (size_t)s->len * 4,
-                     "positions: copy");
+    hipError_t e = launch_export(s->g, s->cache, s->len, nullptr, nullptr, pos, nullptr, s->g.B + s->g.max_decode, s->st);
+    return e == hipSuccess ? INFMLLM_OK : fail_hip(e, "positions");
 }
 
 int infmllm_stream_export(infmllm_stream_t* s, void* K, void* V, int32_t* pos, float* score)
@@ -623,17 +640,8 @@ int infmllm_stream_export(infmllm_stream_t* s, void* K, void* V, int32_t* pos, f
     if (!s) return fail(INFMLLM_EINVAL, "export: stream is null");
     if (!s->attached) return fail(INFMLLM_ESTATE, "export: stream has no workspace attached");
     if (s->pending) return fail(INFMLLM_ESTATE, "export: an eviction is pending on this stream");
-    const Geometry& g = s->g;
-    const CacheView& c = s->cache[s->cur];
-    const size_t row = (size_t)g.d * g.elt;
-    int rc = INFMLLM_OK;
-    if (K && rc == INFMLLM_OK) rc = copy_rows(s, K, s->len * row, c.K, g.cap * row, s->len * row, "export: K");
-    if (V && rc == INFMLLM_OK) rc = copy_rows(s, V, s->len * row, c.V, g.cap * row, s->len * row, "export: V");
-    if (pos && rc == INFMLLM_OK)
-        rc = copy_rows(s, pos, (size_t)s->len * 4, c.pos, (size_t)g.cap * 4, (size_t)s->len * 4, "export: pos");
-    if (score && rc == INFMLLM_OK)
-        rc = copy_rows(s, score, (size_t)s->len * 4, c.score, (size_t)g.cap * 4, (size_t)s->len * 4, "export: score");
-    return rc;
+    hipError_t e = launch_export(s->g, s->cache, s->len, K, V, pos, score, s->len, s->st);
+    return e == hipSuccess ? INFMLLM_OK : fail_hip(e, "export");
 }
 
 int infmllm_stream_import(infmllm_stream_t* s, const void* K, const void* V, const int32_t* pos, int len,
@@ -647,7 +655,7 @@ int infmllm_stream_import(infmllm_stream_t* s, const void* K, const void* V, con
     if (len > 0 && (!K || !V || !pos)) return fail(INFMLLM_EINVAL, "import: K, V and pos must not be null");
     if (streamed < len || streamed > (int64_t)INT32_MAX) return fail(INFMLLM_EINVAL, "import: bad streamed count");
     const Geometry& g = s->g;
-    const CacheView& c = s->cache[s->cur];
+    const CacheView& c = s->cache;
     const size_t row = (size_t)g.d * g.elt;
     int rc = INFMLLM_OK;
     if (len > 0) {
@@ -655,8 +663,9 @@ int infmllm_stream_import(infmllm_stream_t* s, const void* K, const void* V, con
         if (rc == INFMLLM_OK) rc = copy_rows(s, c.V, g.cap * row, V, len * row, len * row, "import: V");
         if (rc == INFMLLM_OK) rc = copy_rows(s, c.pos, (size_t)g.cap * 4, pos, (size_t)len * 4, (size_t)len * 4, "import: pos");
         if (rc == INFMLLM_OK) {
-            hipError_t e = launch_fill_inf(g, c.score, len, s->st);
-            if (e != hipSuccess) rc = fail_hip(e, "import: score");
+            // the imported rows are in stream order: physical row = stream-order index
+            hipError_t e = launch_reset_tables(g, c, len, s->st);
+            if (e != hipSuccess) rc = fail_hip(e, "import: tables");
         }
         if (rc != INFMLLM_OK) return rc;
     }

@@ -373,6 +373,9 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
 // ---------------------------------------------------------------------------------------------
 // score: W'[h][j] = (1/(G lq)) sum_{g in group h} sum_{i = L-lq}^{L-1} exp2(c q_i.k_j - lse2_i)
 //                   - (cnd-1-j) b / cnd
+// A column is a physical cache row (col < tc; its stream-order index j is rank[col]) or a chunk row
+// (col >= tc, j = col).  Columns 0 .. ncol-1 are swept, ncol = max(tc, cnd): any cached row may be a
+// candidate; W' is written at index j, for the columns with j < cnd.
 // Workgroup = 8 wavefronts: 4 column groups (32*CB key columns each, held in registers) x 2 row
 // groups that take alternate 32-row query blocks and add their partial column sums through LDS
 // at the end.  Query blocks are double-buffered in LDS.  Every scored row sees every candidate
@@ -381,7 +384,8 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
 template <int D, int CB>
 __global__ void __launch_bounds__(512)
 score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ kc, int tc,
-             const float* __restrict__ lse2, const float* __restrict__ carry, float* __restrict__ Wb, int L, int lq, int Hq, int Hkv, int G, int cap, int max_chunk, int cnd,
+             const float* __restrict__ lse2, const float* __restrict__ carry, const int32_t* __restrict__ rank,
+             float* __restrict__ Wb, int L, int lq, int Hq, int Hkv, int G, int cap, int max_chunk, int cnd, int ncol,
              int nxb, float c, float dstep /* b / c, Alg. 1 l.2 */, int rsplit, float* __restrict__ spart)
 {
     constexpr int QP = D * 2 + 16;                            // pitch of a staged query row
@@ -509,7 +513,7 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
         for (int u = 0; u < KLD; ++u) {
             const int ch = tid + u * 512, r = ch / CPR;
             const int col = bx * KROWS + r;
-            const bool ok = col < cnd;
+            const bool ok = col < ncol;
             const int cc = ok ? col : 0;
             const uint16_t* kp = (cc < tc ? K + ((size_t)h * cap + cc) * D : kc + ((size_t)(cc - tc) * Hkv + h) * D) + (ch % CPR) * 8;
             kt[u] = *(const u32x4*)kp;
@@ -618,7 +622,8 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
             const int col = col0 + 32 * cb + l32;
-            if (col < cnd) {
+            const int j = col < tc ? (col < ncol ? rank[(size_t)h * cap + col] : cnd) : col;   // stream-order index
+            if (j < cnd) {
                 float tot = sum[cb] + s_part[(cg * CB + cb) * 32 + l32];
                 if (rsplit > 1) {
                     // fixed order over the slices, whichever workgroup does the adding
@@ -627,14 +632,14 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
                         tot += __hip_atomic_load(my_part + (sp - rs) * nxb * 256 + cg * 32 * CB + 32 * cb + l32,
                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
-                float w = tot * norm - (float)(cnd - 1 - col) * dstep;                     // Alg. 1 l.1, l.3-4
+                float w = tot * norm - (float)(cnd - 1 - j) * dstep;                       // Alg. 1 l.1, l.3-4
                 if (carry) {
                     // cumulative policy: this step's S on top of what the row has gathered, no bias; the
                     // chunk's own rows (read in place, col >= tc) and rows never ranked (+inf) carry nothing
                     const float a = col < tc ? carry[(size_t)h * cap + col] : 0.f;
                     w = tot * norm + (a < __builtin_inff() ? a : 0.f);
                 }
-                Wb[(size_t)h * cap + col] = w;
+                Wb[(size_t)h * cap + j] = w;
             }
         }
     }
@@ -679,11 +684,12 @@ hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySou
 {
     const int n = t + L, cnd = n - g.R, lq = g.R < L ? g.R : L;
     if (cnd <= 0) return hipSuccess;
+    const int ncol = ks.rows > cnd ? ks.rows : cnd;          // every cached row, and the chunk rows below cnd
     const float cc = (float)(g.scale * (double)LOG2E);
     // 256 columns per workgroup.  Where that leaves CUs without one, the scored rows of a column block are
     // shared out over up to four workgroups (whose sums the last to finish adds up); where there are too few
     // rows for that, a workgroup takes 128 columns.
-    const int nx256 = (cnd + 255) / 256;
+    const int nx256 = (ncol + 255) / 256;
     const long wgs256 = (long)nx256 * g.Hkv;
     const int niter = (g.G * ((lq + 31) / 32) + 3) / 4;       // iterations of the kernel's row loop
     int rsplit = 1;
@@ -694,14 +700,14 @@ hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySou
         if (rsplit < 1 || !sc.score_part || wgs256 * rsplit > SCORE_SPLIT_WGS) rsplit = 1;
     }
     const bool wide = wgs256 >= 200 || rsplit > 1;
-    const int nxb = wide ? nx256 : (cnd + 127) / 128;
+    const int nxb = wide ? nx256 : (ncol + 127) / 128;
     const dim3 grid(nxb * g.Hkv * rsplit), block(512);
 #define INFMLLM_SCORE(DD, CB)                                                                              \
     hipLaunchKernelGGL((score_kernel<DD, CB>), grid, block, 0, st, (const uint16_t*)q, (const uint16_t*)c.K, \
                        (const uint16_t*)ks.k, ks.rows, lse,                                                  \
-                       g.policy == POLICY_CUMULATIVE ? c.score : nullptr, Wb, L, lq, g.Hq, g.Hkv, g.G, g.cap, \
+                       g.policy == POLICY_CUMULATIVE ? c.score : nullptr, c.rank, Wb, L, lq, g.Hq, g.Hkv, g.G, g.cap, \
                        g.max_chunk,                                                                          \
-                       cnd, nxb, cc, (float)(g.bias / (double)cnd), rsplit, sc.score_part)
+                       cnd, ncol, nxb, cc, (float)(g.bias / (double)cnd), rsplit, sc.score_part)
     if (g.d == 128 && wide) INFMLLM_SCORE(128, 2);
     else if (g.d == 128) INFMLLM_SCORE(128, 1);
     else if (g.d == 64 && wide) INFMLLM_SCORE(64, 2);

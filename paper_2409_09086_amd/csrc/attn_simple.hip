@@ -147,14 +147,15 @@ attn_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const T* __
     if (threadIdx.x == 0) lse[(size_t)g * max_chunk + i] = mx + logf(sum);
 }
 
-// grid (ceil(cnd/64), Hkv), 256 threads = 64 candidate columns x 4 slices of the scored rows (a slice is a
-// wavefront).  Thread = (column j, slice): the key row lives in registers, the thread sums the weights of
-// every fourth scored row, and the four slices are added in slice order.
+// grid (ceil(n/64), Hkv), 256 threads = 64 columns x 4 slices of the scored rows (a slice is a
+// wavefront).  Thread = (column, slice): a column is a physical cache row p (all n rows are cached on this
+// path), a candidate if its stream-order index j = rank[p] is below cnd; the key row lives in registers, the
+// thread sums the weights of every fourth scored row, and the four slices are added in slice order.
 template <typename T, int D>
 __global__ void __launch_bounds__(256)
 score_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const float* __restrict__ lse,
-                    const float* __restrict__ carry, float* __restrict__ Wb, int L, int lq, int Hq, int G, int cap,
-                    int max_chunk, int cnd, float scale, float dstep /* b / c, Alg. 1 l.2 */)
+                    const float* __restrict__ carry, const int32_t* __restrict__ rank, float* __restrict__ Wb, int L,
+                    int lq, int Hq, int G, int cap, int max_chunk, int cnd, int n, float scale, float dstep /* b / c, Alg. 1 l.2 */)
 {
     constexpr int RT = 16, NS = 4;               // query rows staged per round, row slices
     constexpr int CPT = (RT * D / 4 + 255) / 256; // 16-byte chunks of a round per thread
@@ -164,11 +165,12 @@ score_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const floa
 
     const int h = blockIdx.y;
     const int col = threadIdx.x & 63, slice = threadIdx.x >> 6;
-    const int j = blockIdx.x * 64 + col;
+    const int p = blockIdx.x * 64 + col;                                   // physical row
+    const int j = p < n ? rank[(size_t)h * cap + p] : cnd;                 // stream-order index
     const bool live = j < cnd;
     float kr[D];
     {
-        const T* kj = K + ((size_t)h * cap + (live ? j : 0)) * D;
+        const T* kj = K + ((size_t)h * cap + (live ? p : 0)) * D;
 #pragma unroll
         for (int x = 0; x < D; x += 4) {
             const f32x4 kv = Elt<T>::load4(kj + x);
@@ -221,7 +223,7 @@ score_simple_kernel(const T* __restrict__ q, const T* __restrict__ K, const floa
         const float S = (lq > 0) ? tot / (float)(G * lq) : 0.f;        // Alg. 1 l.1, pooled over the group
         float w = S - (float)(cnd - 1 - j) * dstep;                    // Alg. 1 l.3-4
         if (carry) {                                                   // cumulative policy: total so far, no bias
-            const float a = carry[(size_t)h * cap + j];
+            const float a = carry[(size_t)h * cap + p];
             w = S + (a < __builtin_inff() ? a : 0.f);                  // +inf marks a row never ranked
         }
         Wb[(size_t)h * cap + j] = w;
@@ -260,11 +262,11 @@ hipError_t launch_score_simple(const Geometry& g, const CacheView& c, const void
 {
     const int n = t + L, cnd = n - g.R, lq = g.R < L ? g.R : L;
     if (cnd <= 0) return hipSuccess;
-    const dim3 grid((cnd + 63) / 64, g.Hkv), block(256);
+    const dim3 grid((n + 63) / 64, g.Hkv), block(256);
 #define INFMLLM_SCORE(TT, DD)                                                                           \
     hipLaunchKernelGGL((score_simple_kernel<TT, DD>), grid, block, 0, st, (const TT*)q, (const TT*)c.K, \
-                       lse, g.policy == POLICY_CUMULATIVE ? c.score : nullptr, Wb, L, lq, g.Hq, g.G, g.cap,     \
-                       g.max_chunk, cnd, (float)g.scale, (float)(g.bias / (double)cnd))
+                       lse, g.policy == POLICY_CUMULATIVE ? c.score : nullptr, c.rank, Wb, L, lq, g.Hq, g.G, g.cap, \
+                       g.max_chunk, cnd, n, (float)g.scale, (float)(g.bias / (double)cnd))
     if (g.elt == 4 && g.d == 64) INFMLLM_SCORE(float, 64);
     else if (g.elt == 4 && g.d == 128) INFMLLM_SCORE(float, 128);
     else if (g.elt == 2 && g.d == 64) INFMLLM_SCORE(uint16_t, 64);

@@ -1,7 +1,9 @@
 // Cache maintenance kernels for gfx950: append (Sec. 3.2, first paragraph), the warm-up index
-// list, and the gather that compresses the cache (Alg. 1 l.8).  All three are pure data
-// movement and HBM-bound: every thread moves 16-byte vectors, a row of head_dim elements is
-// covered by consecutive lanes so that each wavefront touches whole rows.
+// list, the placement that completes an eviction (Alg. 1 l.8: only the retained rows that are not
+// already inside physical rows 0..B-1 are moved, into the rows the eviction frees) and the export of
+// the cache in stream order.  All are pure data movement and HBM-bound: every thread moves 16-byte
+// vectors, a row of head_dim elements is covered by consecutive lanes so that each wavefront touches
+// whole rows.
 #include "launch.h"
 
 namespace infmllm {
@@ -13,8 +15,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // chunk k/v [L][Hkv][d]  ->  cache rows [h][t+i][d]
 __global__ void __launch_bounds__(256)
 append_kernel(const u32x4* __restrict__ k, const u32x4* __restrict__ v, u32x4* __restrict__ K,
-              u32x4* __restrict__ V, int32_t* __restrict__ pos, float* __restrict__ score, int t, int L,
-              int Hkv, int cap, int vec_per_row, int pos0)
+              u32x4* __restrict__ V, int32_t* __restrict__ pos, float* __restrict__ score,
+              int32_t* __restrict__ rank, int32_t* __restrict__ row, int t, int L, int Hkv, int cap, int vec_per_row,
+              int pos0)
 {
     const long total = (long)L * Hkv * vec_per_row;
     for (long idx = (long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
@@ -29,6 +32,8 @@ append_kernel(const u32x4* __restrict__ k, const u32x4* __restrict__ v, u32x4* _
         if (x == 0) {
             pos[(long)h * cap + t + i] = pos0 + i;
             score[(long)h * cap + t + i] = __builtin_inff();
+            rank[(long)h * cap + t + i] = t + i;          // the cached rows fill physical rows 0..t-1, so the
+            row[(long)h * cap + t + i] = t + i;           // next stream-order index and the next free row agree
         }
     }
 }
@@ -62,56 +67,70 @@ rank_score_kernel(float* __restrict__ Wb, int cnd, int Hkv, int cap, float sign)
 }
 
 __global__ void __launch_bounds__(256)
-fill_inf_kernel(float* __restrict__ score, int len, int Hkv, int cap)
+reset_tables_kernel(float* __restrict__ score, int32_t* __restrict__ rank, int32_t* __restrict__ row, int len, int Hkv,
+                    int cap)
 {
     const int total = len * Hkv;
     for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += gridDim.x * blockDim.x) {
         const int h = idx / len, j = idx - h * len;
         score[(long)h * cap + j] = __builtin_inff();
+        rank[(long)h * cap + j] = j;
+        row[(long)h * cap + j] = j;
     }
 }
 
-// dst[h][x] <- src[h][I[h][x]] for x < rows (the relevant rows; I has row stride B).  One thread per
-// 16-byte vector of a row of K and V.
+// Entry k of a head's move list: the token with stream-order index src[k] goes to physical row dst[k] and
+// has stream-order index x[k] from now on.  One thread per 16-byte vector of a row of K and V, two rows in
+// flight per thread.  A source row is either a cache row at or above B (never a destination, so no row is
+// read after it has been overwritten) or a row of the chunk tensors.
 template <int VPR>
-__device__ __forceinline__ void compact_body(const u32x4* __restrict__ Ks, const u32x4* __restrict__ Vs,
-                                             const int32_t* __restrict__ ps, const u32x4* __restrict__ kc,
-                                             const u32x4* __restrict__ vc, int tc, int pos0, int Hkv,
-                                             u32x4* __restrict__ Kd, u32x4* __restrict__ Vd,
-                                             int32_t* __restrict__ pd, float* __restrict__ sd,
-                                             const int32_t* __restrict__ I, const float* __restrict__ Wb, int B,
-                                             int rows, int cap)
+__device__ __forceinline__ void place_body(u32x4* __restrict__ K, u32x4* __restrict__ V, int32_t* __restrict__ pos,
+                                           float* __restrict__ score, int32_t* __restrict__ rank,
+                                           const int32_t* __restrict__ row_old, int32_t* __restrict__ row_new,
+                                           const u32x4* __restrict__ kc, const u32x4* __restrict__ vc, int tc, int pos0,
+                                           int Hkv, int r, int cap, const float* __restrict__ Wb,
+                                           const int32_t* __restrict__ mv_src, const int32_t* __restrict__ mv_dst,
+                                           const int32_t* __restrict__ mv_x, const int32_t* __restrict__ mv_count,
+                                           int mv_max)
 {
-    constexpr int ROWS = 256 / VPR;               // rows per block pass
+    constexpr int ROWS = 256 / VPR, U = 2;        // rows per block pass, passes in flight
     const int h = blockIdx.y;
-    const int lane_row = threadIdx.x / VPR, x = threadIdx.x % VPR;
+    const int lane_row = threadIdx.x / VPR, xv = threadIdx.x % VPR;
     const long hb = (long)h * cap;
-    for (int row0 = blockIdx.x * ROWS * 4; row0 < rows; row0 += gridDim.x * ROWS * 4) {
-        int src[4];
-        u32x4 kk[4], vv[4];
+    const int count = mv_count[h];
+    const int32_t* src = mv_src + (long)h * mv_max;
+    const int32_t* dst = mv_dst + (long)h * mv_max;
+    const int32_t* nx = mv_x + (long)h * mv_max;
+    for (int k0 = blockIdx.x * ROWS * U; k0 < count; k0 += gridDim.x * ROWS * U) {
+        int j[U], p[U], sp[U];
+        u32x4 kk[U], vv[U];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int r = row0 + u * ROWS + lane_row;
-            src[u] = (r < rows) ? I[(long)h * B + r] : -1;
+        for (int u = 0; u < U; ++u) {
+            const int k = k0 + u * ROWS + lane_row;
+            j[u] = (k < count) ? src[k] : -1;
+            p[u] = (k < count) ? dst[k] : 0;
+            sp[u] = (j[u] >= 0 && j[u] < tc) ? row_old[hb + j[u]] : -1;
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (src[u] >= 0) {
-                const bool cached = src[u] < tc;          // else the row is still in the chunk tensors
-                const long off = cached ? (hb + src[u]) * VPR + x : ((long)(src[u] - tc) * Hkv + h) * VPR + x;
-                kk[u] = __builtin_nontemporal_load((cached ? Ks : kc) + off);
-                vv[u] = __builtin_nontemporal_load((cached ? Vs : vc) + off);
+        for (int u = 0; u < U; ++u) {
+            if (j[u] >= 0) {
+                const long off = sp[u] >= 0 ? (hb + sp[u]) * VPR + xv : ((long)(j[u] - tc) * Hkv + h) * VPR + xv;
+                kk[u] = __builtin_nontemporal_load((sp[u] >= 0 ? (const u32x4*)K : kc) + off);
+                vv[u] = __builtin_nontemporal_load((sp[u] >= 0 ? (const u32x4*)V : vc) + off);
             }
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int r = row0 + u * ROWS + lane_row;
-            if (src[u] >= 0) {
-                __builtin_nontemporal_store(kk[u], &Kd[(hb + r) * VPR + x]);
-                __builtin_nontemporal_store(vv[u], &Vd[(hb + r) * VPR + x]);
-                if (x == 0) {
-                    pd[hb + r] = (src[u] < tc) ? ps[hb + src[u]] : pos0 + (src[u] - tc);
-                    sd[hb + r] = Wb[(long)h * cap + src[u]];
+        for (int u = 0; u < U; ++u) {
+            if (j[u] >= 0) {
+                K[(hb + p[u]) * VPR + xv] = kk[u];
+                V[(hb + p[u]) * VPR + xv] = vv[u];
+                if (xv == 0) {
+                    const int k = k0 + u * ROWS + lane_row;
+                    const int x = nx[k];
+                    pos[hb + p[u]] = sp[u] >= 0 ? pos[hb + sp[u]] : pos0 + (j[u] - tc);
+                    rank[hb + p[u]] = x;
+                    row_new[hb + x] = p[u];
+                    score[hb + p[u]] = x < r ? Wb[hb + j[u]] : __builtin_inff();
                 }
             }
         }
@@ -120,24 +139,53 @@ __device__ __forceinline__ void compact_body(const u32x4* __restrict__ Ks, const
 
 template <int VPR>
 __global__ void __launch_bounds__(256)
-compact_kernel(const u32x4* __restrict__ Ks, const u32x4* __restrict__ Vs, const int32_t* __restrict__ ps,
-               const u32x4* __restrict__ kc, const u32x4* __restrict__ vc, int tc, int pos0, int Hkv,
-               u32x4* __restrict__ Kd, u32x4* __restrict__ Vd, int32_t* __restrict__ pd,
-               float* __restrict__ sd, const int32_t* __restrict__ I, const float* __restrict__ Wb,
-               int B, int rows, int cap)
+place_kernel(u32x4* __restrict__ K, u32x4* __restrict__ V, int32_t* __restrict__ pos, float* __restrict__ score,
+             int32_t* __restrict__ rank, const int32_t* __restrict__ row_old, int32_t* __restrict__ row_new,
+             const u32x4* __restrict__ kc, const u32x4* __restrict__ vc, int tc, int pos0, int Hkv, int r, int cap,
+             const float* __restrict__ Wb, const int32_t* __restrict__ mv_src, const int32_t* __restrict__ mv_dst,
+             const int32_t* __restrict__ mv_x, const int32_t* __restrict__ mv_count, int mv_max)
 {
-    compact_body<VPR>(Ks, Vs, ps, kc, vc, tc, pos0, Hkv, Kd, Vd, pd, sd, I, Wb, B, rows, cap);
+    place_body<VPR>(K, V, pos, score, rank, row_old, row_new, kc, vc, tc, pos0, Hkv, r, cap, Wb, mv_src, mv_dst, mv_x,
+                    mv_count, mv_max);
 }
 
 // blockIdx.z = stream of the batch
 template <int VPR>
 __global__ void __launch_bounds__(256)
-compact_batch_kernel(EvictBatch eb, int Hkv, int B, int rows, int cap)
+place_batch_kernel(EvictBatch eb, int Hkv, int r, int cap)
 {
     const EvictJob& j = eb.job[blockIdx.z];
-    compact_body<VPR>((const u32x4*)j.src.K, (const u32x4*)j.src.V, j.src.pos, (const u32x4*)j.kc, (const u32x4*)j.vc,
-                      j.tc, j.pos0, Hkv, (u32x4*)j.dst.K, (u32x4*)j.dst.V, j.dst.pos, j.dst.score, j.I, j.Wb, B, rows,
-                      cap);
+    place_body<VPR>((u32x4*)j.c.K, (u32x4*)j.c.V, j.c.pos, j.c.score, j.c.rank, j.c.row, j.c.row_next,
+                    (const u32x4*)j.kc, (const u32x4*)j.vc, j.tc, j.pos0, Hkv, r, cap, j.Wb, j.mv.src, j.mv.dst, j.mv.x,
+                    j.mv.count, j.mv.max);
+}
+
+// out row j of head h <- physical row row[h][j]: the cache in stream order.
+template <int VPR>
+__global__ void __launch_bounds__(256)
+export_rows_kernel(const u32x4* __restrict__ K, const u32x4* __restrict__ V, const int32_t* __restrict__ row,
+                   u32x4* __restrict__ Kout, u32x4* __restrict__ Vout, int len, int cap)
+{
+    constexpr int ROWS = 256 / VPR;
+    const int h = blockIdx.y, lane_row = threadIdx.x / VPR, xv = threadIdx.x % VPR;
+    for (int j = blockIdx.x * ROWS + lane_row; j < len; j += gridDim.x * ROWS) {
+        const long src = ((long)h * cap + row[(long)h * cap + j]) * VPR + xv, dst = ((long)h * len + j) * VPR + xv;
+        if (Kout) Kout[dst] = K[src];
+        if (Vout) Vout[dst] = V[src];
+    }
+}
+
+__global__ void __launch_bounds__(256)
+export_scalars_kernel(const int32_t* __restrict__ pos, const float* __restrict__ score, const int32_t* __restrict__ row,
+                      int32_t* __restrict__ pos_out, float* __restrict__ score_out, int len, int Hkv, int cap, int pitch)
+{
+    const int total = len * Hkv;
+    for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += gridDim.x * blockDim.x) {
+        const int h = idx / len, j = idx - h * len;
+        const long p = (long)h * cap + row[(long)h * cap + j];
+        if (pos_out) pos_out[(long)h * pitch + j] = pos[p];
+        if (score_out) score_out[(long)h * pitch + j] = score[p];
+    }
 }
 
 }  // namespace
@@ -150,7 +198,7 @@ hipError_t launch_append(const Geometry& g, const CacheView& c, const void* k, c
     int blocks = (int)((total + 255) / 256);
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(append_kernel, dim3(blocks), dim3(256), 0, st, (const u32x4*)k, (const u32x4*)v,
-                       (u32x4*)c.K, (u32x4*)c.V, c.pos, c.score, t, L, g.Hkv, g.cap, vpr, (int)T);
+                       (u32x4*)c.K, (u32x4*)c.V, c.pos, c.score, c.rank, c.row, t, L, g.Hkv, g.cap, vpr, (int)T);
     return hipGetLastError();
 }
 
@@ -183,52 +231,78 @@ hipError_t launch_rank_scores(const Geometry& g, float* Wb, int cnd, float sign,
     return hipGetLastError();
 }
 
-hipError_t launch_fill_inf(const Geometry& g, float* score, int len, hipStream_t st)
+hipError_t launch_reset_tables(const Geometry& g, const CacheView& c, int len, hipStream_t st)
 {
     if (len <= 0) return hipSuccess;
     int blocks = (len * g.Hkv + 255) / 256;
     if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL(fill_inf_kernel, dim3(blocks), dim3(256), 0, st, score, len, g.Hkv, g.cap);
+    hipLaunchKernelGGL(reset_tables_kernel, dim3(blocks), dim3(256), 0, st, c.score, c.rank, c.row, len, g.Hkv, g.cap);
     return hipGetLastError();
 }
 
-hipError_t launch_compact(const Geometry& g, const CacheView& src, const KeySource& ks, int64_t T,
-                          const CacheView& dst, const int32_t* I, const float* Wb, int n, hipStream_t st)
+hipError_t launch_place(const Geometry& g, const CacheView& c, const KeySource& ks, int64_t T, const MoveList& mv,
+                        const float* Wb, int nmax, hipStream_t st)
 {
     const int vpr = g.d * g.elt / 16;             // 8 (d=64 bf16), 16 (d=128 bf16 / d=64 fp32), 32 (d=128 fp32)
-    const int rows_per_pass = (256 / vpr) * 4;
-    const int rows = g.B - g.R;                   // the recent rows have been moved already
-    (void)n;
-    if (rows <= 0) return hipSuccess;
-    int bx = (rows + rows_per_pass - 1) / rows_per_pass;
-    const dim3 grid(bx, g.Hkv), block(256);
-#define INFMLLM_COMPACT(VPR)                                                                          \
-    hipLaunchKernelGGL(compact_kernel<VPR>, grid, block, 0, st, (const u32x4*)src.K, (const u32x4*)src.V, \
-                       src.pos, (const u32x4*)ks.k, (const u32x4*)ks.v, ks.rows, (int)T, g.Hkv, (u32x4*)dst.K,  \
-                       (u32x4*)dst.V, dst.pos, dst.score, I, Wb, g.B, rows, g.cap)
+    const int rows_per_pass = (256 / vpr) * 2;
+    if (nmax <= 0) return hipSuccess;
+    if (nmax > mv.max) return hipErrorInvalidValue;
+    const dim3 grid((nmax + rows_per_pass - 1) / rows_per_pass, g.Hkv), block(256);
+#define INFMLLM_PLACE(VPR)                                                                                      \
+    hipLaunchKernelGGL(place_kernel<VPR>, grid, block, 0, st, (u32x4*)c.K, (u32x4*)c.V, c.pos, c.score, c.rank, c.row, \
+                       c.row_next, (const u32x4*)ks.k, (const u32x4*)ks.v, ks.rows, (int)T, g.Hkv, g.B - g.R, g.cap, \
+                       Wb, mv.src, mv.dst, mv.x, mv.count, mv.max)
     switch (vpr) {
-        case 8: INFMLLM_COMPACT(8); break;
-        case 16: INFMLLM_COMPACT(16); break;
-        case 32: INFMLLM_COMPACT(32); break;
+        case 8: INFMLLM_PLACE(8); break;
+        case 16: INFMLLM_PLACE(16); break;
+        case 32: INFMLLM_PLACE(32); break;
         default: return hipErrorInvalidValue;
     }
-#undef INFMLLM_COMPACT
+#undef INFMLLM_PLACE
     return hipGetLastError();
 }
 
-hipError_t launch_compact_batch(const Geometry& g, const EvictBatch& eb, hipStream_t st)
+hipError_t launch_place_batch(const Geometry& g, const EvictBatch& eb, int nmax, hipStream_t st)
 {
     if (eb.count < 1 || eb.count > EVICT_MAX_JOBS) return hipErrorInvalidValue;
     const int vpr = g.d * g.elt / 16;
-    const int rows_per_pass = (256 / vpr) * 4;
-    const int rows = g.B - g.R;
-    if (rows <= 0) return hipSuccess;
-    const dim3 grid((rows + rows_per_pass - 1) / rows_per_pass, g.Hkv, eb.count), block(256);
+    const int rows_per_pass = (256 / vpr) * 2;
+    if (nmax <= 0) return hipSuccess;
+    const dim3 grid((nmax + rows_per_pass - 1) / rows_per_pass, g.Hkv, eb.count), block(256);
+    const int r = g.B - g.R;
     switch (vpr) {
-        case 8: hipLaunchKernelGGL(compact_batch_kernel<8>, grid, block, 0, st, eb, g.Hkv, g.B, rows, g.cap); break;
-        case 16: hipLaunchKernelGGL(compact_batch_kernel<16>, grid, block, 0, st, eb, g.Hkv, g.B, rows, g.cap); break;
-        case 32: hipLaunchKernelGGL(compact_batch_kernel<32>, grid, block, 0, st, eb, g.Hkv, g.B, rows, g.cap); break;
+        case 8: hipLaunchKernelGGL(place_batch_kernel<8>, grid, block, 0, st, eb, g.Hkv, r, g.cap); break;
+        case 16: hipLaunchKernelGGL(place_batch_kernel<16>, grid, block, 0, st, eb, g.Hkv, r, g.cap); break;
+        case 32: hipLaunchKernelGGL(place_batch_kernel<32>, grid, block, 0, st, eb, g.Hkv, r, g.cap); break;
         default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_export(const Geometry& g, const CacheView& c, int len, void* Kout, void* Vout, int32_t* pos_out,
+                         float* score_out, int pitch, hipStream_t st)
+{
+    if (len <= 0) return hipSuccess;
+    const int vpr = g.d * g.elt / 16;
+    if (Kout || Vout) {
+        const int rows = 256 / vpr;
+        int bx = (len + rows - 1) / rows;
+        if (bx > 2048) bx = 2048;
+        const dim3 grid(bx, g.Hkv), block(256);
+        switch (vpr) {
+            case 8: hipLaunchKernelGGL(export_rows_kernel<8>, grid, block, 0, st, (const u32x4*)c.K, (const u32x4*)c.V, c.row, (u32x4*)Kout, (u32x4*)Vout, len, g.cap); break;
+            case 16: hipLaunchKernelGGL(export_rows_kernel<16>, grid, block, 0, st, (const u32x4*)c.K, (const u32x4*)c.V, c.row, (u32x4*)Kout, (u32x4*)Vout, len, g.cap); break;
+            case 32: hipLaunchKernelGGL(export_rows_kernel<32>, grid, block, 0, st, (const u32x4*)c.K, (const u32x4*)c.V, c.row, (u32x4*)Kout, (u32x4*)Vout, len, g.cap); break;
+            default: return hipErrorInvalidValue;
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (pos_out || score_out) {
+        int blocks = (len * g.Hkv + 255) / 256;
+        if (blocks > 1024) blocks = 1024;
+        hipLaunchKernelGGL(export_scalars_kernel, dim3(blocks), dim3(256), 0, st, c.pos, c.score, c.row, pos_out,
+                           score_out, len, g.Hkv, g.cap, pitch);
     }
     return hipGetLastError();
 }

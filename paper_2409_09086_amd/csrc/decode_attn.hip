@@ -70,7 +70,7 @@ template <typename T, int D, int NG>
 __global__ void __launch_bounds__(DEC_THREADS)
 decode_partial_kernel(const T* __restrict__ q, const T* __restrict__ knew, const T* __restrict__ vnew,
                       T* __restrict__ K, T* __restrict__ V, int32_t* __restrict__ pos, float* __restrict__ score,
-                      float* __restrict__ part, int* __restrict__ arrived, T* __restrict__ out, int t, int G, int cap,
+                      int32_t* __restrict__ rank, int32_t* __restrict__ row, float* __restrict__ part, int* __restrict__ arrived, T* __restrict__ out, int t, int G, int cap,
                       int nsplit, int pos_new, float c)
 {
     using VT = Vec16<T>;
@@ -179,6 +179,8 @@ decode_partial_kernel(const T* __restrict__ q, const T* __restrict__ knew, const
         if (tid == 0) {
             pos[(size_t)h * cap + t] = pos_new;
             score[(size_t)h * cap + t] = __builtin_inff();
+            rank[(size_t)h * cap + t] = t;                     // the newest token, in the first free physical row
+            row[(size_t)h * cap + t] = t;
         }
     }
     // The workgroup of this kv-head that arrives last merges the splits: every workgroup waits until its own
@@ -239,7 +241,7 @@ hipError_t launch_decode(const Geometry& g, const CacheView& c, const void* q, c
     const dim3 grid(nsplit, g.Hkv);
 #define INFMLLM_DECODE_NG(TT, DD, NG)                                                                            \
     hipLaunchKernelGGL((decode_partial_kernel<TT, DD, NG>), grid, dim3(DEC_THREADS), 0, st, (const TT*)q,        \
-                       (const TT*)k, (const TT*)v, (TT*)c.K, (TT*)c.V, c.pos, c.score, part, arrived, (TT*)out, t, \
+                       (const TT*)k, (const TT*)v, (TT*)c.K, (TT*)c.V, c.pos, c.score, c.rank, c.row, part, arrived, (TT*)out, t, \
                        g.G, g.cap, nsplit, (int)T, cc)
 #define INFMLLM_DECODE(TT, DD)                                                                                   \
     do {                                                                                                         \

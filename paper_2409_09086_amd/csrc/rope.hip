@@ -53,11 +53,12 @@ template <> struct Oct<float> {
 };
 
 // One thread = one (row, group of 8 pairs, group of HPT heads): the table entries are loaded once and the
-// HPT heads of that row are turned with them; blockIdx.y picks the group of heads.  Rows: cache rows [j0, j1) (position j), then the chunk's L key rows
+// HPT heads of that row are turned with them; blockIdx.y picks the group of heads.  Rows: physical cache rows
+// [j0, j1) (position = the row's stream-order index rank[h][p], looked up per head), then the chunk's L key rows
 // (position t + i, if kc is given), then the L query rows (position t + i).
 template <typename T, int D>
 __global__ void __launch_bounds__(256)
-rope_kernel(const T* __restrict__ K, T* __restrict__ Krot, int j0, int j1, int cap, int Hkv,
+rope_kernel(const T* __restrict__ K, T* __restrict__ Krot, const int32_t* __restrict__ rank, int j0, int j1, int cap, int Hkv,
             const T* __restrict__ kc, T* __restrict__ kcrot, const T* __restrict__ q, T* __restrict__ qrot, int Hq,
             int t, int L, const double2* __restrict__ tab)
 {
@@ -66,13 +67,16 @@ rope_kernel(const T* __restrict__ K, T* __restrict__ Krot, int j0, int j1, int c
     const long idx = (long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (long)(nA + nB + nC) * GPR) return;
     const int item = (int)(idx / GPR), cc = (int)(idx % GPR);
-    int pos, heads;
+    int pos = 0, heads;
     const T* src;
     T* dst;
     long hstride;                                             // elements between two heads of the same row
-    if (item < nA) {
-        pos = j0 + item; heads = Hkv; hstride = (long)cap * D;
-        src = K + (long)pos * D; dst = Krot + (long)pos * D;
+    const bool cache_row = item < nA;
+    if (cache_row) {
+        const int p = j0 + item;                              // physical row; its position differs from head to head
+        heads = Hkv; hstride = (long)cap * D;
+        src = K + (long)p * D; dst = Krot + (long)p * D;
+        rank += p;
     } else if (item < nA + nB) {
         const int i = item - nA;
         pos = t + i; heads = Hkv; hstride = D;
@@ -83,11 +87,13 @@ rope_kernel(const T* __restrict__ K, T* __restrict__ Krot, int j0, int j1, int c
         src = q + (long)i * Hq * D; dst = qrot + (long)i * Hq * D;
     }
     double cs[8], sn[8];
+    auto table = [&](int at) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const double2 v = tab[(long)pos * (D / 2) + e * GPR + cc];   // lanes of a row read consecutive entries
-        cs[e] = v.x; sn[e] = v.y;
-    }
+        for (int e = 0; e < 8; ++e) {
+            const double2 v = tab[(long)at * (D / 2) + e * GPR + cc];   // lanes of a row read consecutive entries
+            cs[e] = v.x; sn[e] = v.y;
+        }
+    };
     const int h0 = blockIdx.y * ROPE_HPT, h1 = min(heads, h0 + ROPE_HPT);
     auto turn = [&](const Oct<T>& a, const Oct<T>& b, T* out) {
         Oct<T> ra, rb;
@@ -100,6 +106,18 @@ rope_kernel(const T* __restrict__ K, T* __restrict__ Krot, int j0, int j1, int c
         ra.store(out + 8 * cc);
         rb.store(out + D / 2 + 8 * cc);
     };
+    if (cache_row) {
+        // a cached row's position is its stream-order index in its own head's cache
+        for (int h = h0; h < h1; ++h) {
+            Oct<T> a, b;
+            a.load(src + h * hstride + 8 * cc);
+            b.load(src + h * hstride + D / 2 + 8 * cc);
+            table(rank[(long)h * cap]);
+            turn(a, b, dst + h * hstride);
+        }
+        return;
+    }
+    table(pos);
     if (h1 - h0 == ROPE_HPT) {
         // a full group of heads: every load is requested before the first value is used
         Oct<T> a[ROPE_HPT], b[ROPE_HPT];                      // x[8cc .. 8cc+8) and x[d/2 + 8cc .. +8)
@@ -122,8 +140,9 @@ rope_kernel(const T* __restrict__ K, T* __restrict__ Krot, int j0, int j1, int c
 
 }  // namespace
 
-hipError_t launch_rope(const Geometry& g, const void* K, void* Krot, int j0, int j1, const void* kc, void* kcrot,
-                       const void* q, void* qrot, int t, int L, const double* tab, hipStream_t st)
+hipError_t launch_rope(const Geometry& g, const void* K, void* Krot, const int32_t* rank, int j0, int j1,
+                       const void* kc, void* kcrot, const void* q, void* qrot, int t, int L, const double* tab,
+                       hipStream_t st)
 {
     if (j1 < j0) j1 = j0;
     const long items = (long)(j1 - j0) + (kc ? L : 0) + (q ? L : 0);
@@ -132,7 +151,7 @@ hipError_t launch_rope(const Geometry& g, const void* K, void* Krot, int j0, int
     const int hmax = g.Hq > g.Hkv ? g.Hq : g.Hkv;
     const dim3 grid((unsigned)((threads + 255) / 256), (unsigned)((hmax + ROPE_HPT - 1) / ROPE_HPT)), block(256);
 #define INFMLLM_ROPE(TT, DD)                                                                                  \
-    hipLaunchKernelGGL((rope_kernel<TT, DD>), grid, block, 0, st, (const TT*)K, (TT*)Krot, j0, j1, g.cap, g.Hkv, \
+    hipLaunchKernelGGL((rope_kernel<TT, DD>), grid, block, 0, st, (const TT*)K, (TT*)Krot, rank, j0, j1, g.cap, g.Hkv, \
                        (const TT*)kc, (TT*)kcrot, (const TT*)q, (TT*)qrot, g.Hq, t, L, (const double2*)tab)
     if (g.elt == 2 && g.d == 128) INFMLLM_ROPE(uint16_t, 128);
     else if (g.elt == 2 && g.d == 64) INFMLLM_ROPE(uint16_t, 64);

@@ -1,5 +1,6 @@
-// Device code of the per-head top-r selection (Alg. 1 l.5-7) and of the recent-window move, templated
-// on TPB, the threads of the calling workgroup.
+// Device code of the per-head top-r selection (Alg. 1 l.5-7) and of the placement plan that follows it
+// (which retained rows stay where they are, which move where), templated on TPB, the threads of the
+// calling workgroup.
 #pragma once
 #include "launch.h"
 
@@ -72,39 +73,101 @@ __device__ __forceinline__ uint32_t wave_extreme_to_last_lane(uint32_t x)
     return x;
 }
 
-// The recent window [c, n) is kept whatever the scores say (Alg. 1 l.6), so its rows can move to
-// their final place, rows r .. B-1 of the other cache half, while the selection is still being
-// worked out.  The selection occupies one workgroup per kv-head; the workgroups with
-// blockIdx.x >= Hkv of the same launch do this copy on the CUs the selection leaves idle.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-struct RecentCopy {
-    const u32x4* Ks; const u32x4* Vs; const int32_t* ps;      // live cache half
-    const u32x4* kc; const u32x4* vc;                         // chunk tensors (rows >= tc), may be null
-    u32x4* Kd; u32x4* Vd; int32_t* pd; float* sd;             // other half
-    int tc, pos0, vpr, ncopy;                                 // vpr = 16-byte vectors per row
+// Largest budget the placement plan keeps its two bit maps for (one bit per retained slot, one per
+// physical row below B) in LDS.
+constexpr int PLAN_MAX_B = 131072;
+
+// Exclusive prefix sum of v over the TPB threads of the workgroup (all of them call it); *total = the sum.
+template <int TPB>
+__device__ __forceinline__ uint32_t block_exclusive_sum(uint32_t v, uint32_t* wsum /* [TPB/64] in LDS */, uint32_t* total)
+{
+    constexpr int NW = TPB / 64;
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    const uint32_t incl = wave_inclusive_sum(v);
+    if (l == 63) wsum[w] = incl;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (int x = 0; x < NW; ++x) {
+        const uint32_t s = wsum[x];
+        before += x < w ? s : 0u;
+        all += s;
+    }
+    __syncthreads();                                          // wsum may be reused by the next call
+    *total = all;
+    return before + incl - v;
+}
+
+// The tables of one kv-head that the placement plan reads and writes (see CacheView).
+struct PlanTables {
+    const int32_t* row_old;    // [cap] physical row of each stream-order index before the eviction
+    int32_t* row_new;          // [cap] ... after it
+    int32_t* rank;             // [cap] stream-order index of each physical row (rewritten for rows 0..B-1)
+    float* score;              // [cap]
+    int32_t* mv_src;           // [mv_max] move list of this head
+    int32_t* mv_dst;
+    int32_t* mv_x;
+    int32_t* mv_count;         // one int
 };
 
+// Alg. 1 l.8 without moving the rows that stay.  Ih[0..B) is the retained list (stream-order indices,
+// ascending).  A retained token that is cached in a physical row below B keeps that row: its new index x
+// goes into rank / row_new, its score entry becomes W'[j] (+inf inside the recent window).  Every other
+// retained token (a chunk row, or a cached row at or above B) is a mover; the physical rows below B
+// that no retained token occupies are exactly as many, and the k-th mover (by x) is paired with the k-th
+// free row (ascending), which makes the layout a function of the retained list alone.  The K/V copies and
+// the movers' table entries are left to the placement launch.
 template <int TPB>
-__device__ __forceinline__ void copy_recent(const RecentCopy& rc, int wg, int Hkv, int cnd, int r, int R, int cap)
+__device__ __forceinline__ void plan_moves(const int32_t* __restrict__ Ih, const float* __restrict__ W, int tc, int B,
+                                           int r, const PlanTables& pt)
 {
-    const long total = (long)Hkv * R * rc.vpr;
-    for (long idx = (long)wg * TPB + threadIdx.x; idx < total; idx += (long)rc.ncopy * TPB) {
-        const int x = (int)(idx % rc.vpr);
-        const long hr = idx / rc.vpr;
-        const int row = (int)(hr % R), h = (int)(hr / R);
-        const int src = cnd + row, dst = r + row;
-        const bool cached = src < rc.tc;
-        const long so = cached ? ((long)h * cap + src) * rc.vpr + x : ((long)(src - rc.tc) * Hkv + h) * rc.vpr + x;
-        const long dof = ((long)h * cap + dst) * rc.vpr + x;
-        const u32x4 kk = __builtin_nontemporal_load((cached ? rc.Ks : rc.kc) + so);
-        const u32x4 vv = __builtin_nontemporal_load((cached ? rc.Vs : rc.vc) + so);
-        __builtin_nontemporal_store(kk, rc.Kd + dof);
-        __builtin_nontemporal_store(vv, rc.Vd + dof);
-        if (x == 0) {
-            rc.pd[(long)h * cap + dst] = cached ? rc.ps[(long)h * cap + src] : rc.pos0 + (src - rc.tc);
-            rc.sd[(long)h * cap + dst] = __builtin_inff();
+    __shared__ uint32_t occ[PLAN_MAX_B / 32], mov[PLAN_MAX_B / 32];
+    __shared__ uint32_t wsum[TPB / 64];
+    const int tid = threadIdx.x;
+    const int words = (B + 31) / 32;
+    for (int w = tid; w < words; w += TPB) { occ[w] = 0u; mov[w] = 0u; }
+    __syncthreads();                                          // also: Ih as written by this workgroup is visible
+    for (int x = tid; x < B; x += TPB) {
+        const int j = Ih[x];
+        const int p = j < tc ? pt.row_old[j] : -1;
+        if (p >= 0 && p < B) {
+            atomicOr(&occ[p >> 5], 1u << (p & 31));
+            pt.rank[p] = x;
+            pt.row_new[x] = p;
+            pt.score[p] = x < r ? W[j] : __builtin_inff();
+        } else {
+            atomicOr(&mov[x >> 5], 1u << (x & 31));
         }
     }
+    __syncthreads();
+    uint32_t fbase = 0, mbase = 0;                            // free rows / movers listed so far (uniform)
+    for (int w0 = 0; w0 < words; w0 += TPB) {
+        const int w = w0 + tid;
+        uint32_t f = 0u, m = 0u;
+        if (w < words) {
+            f = ~occ[w];
+            if (32 * w + 32 > B) f &= (1u << (B - 32 * w)) - 1u;   // only rows below B
+            m = mov[w];
+        }
+        uint32_t ftot, mtot;
+        uint32_t fo = fbase + block_exclusive_sum<TPB>((uint32_t)__popc(f), wsum, &ftot);
+        uint32_t mo = mbase + block_exclusive_sum<TPB>((uint32_t)__popc(m), wsum, &mtot);
+        while (f) {
+            const int b = __ffs((int)f) - 1;
+            f &= f - 1u;
+            pt.mv_dst[fo++] = 32 * w + b;
+        }
+        while (m) {
+            const int b = __ffs((int)m) - 1;
+            m &= m - 1u;
+            const int x = 32 * w + b;
+            pt.mv_src[mo] = Ih[x];
+            pt.mv_x[mo++] = x;
+        }
+        fbase += ftot;
+        mbase += mtot;
+    }
+    if (tid == 0) *pt.mv_count = (int32_t)mbase;               // = fbase: B rows are retained, B rows lie below B
 }
 
 // Same selection with the candidates of a head held in registers (KPT keys per thread, key

@@ -7,7 +7,8 @@
 // histograms are built from wavefront ballots of the candidates that still match the prefix.
 // The kept set {key > T} U {the newest ties of key == T} is then written in ascending index
 // order through block-wide ballot/popcount scans, followed by the recent window [c, n), which
-// is kept unconditionally.  Ties go to the larger index (the newer key).
+// is kept unconditionally.  Ties go to the larger index (the newer key).  The same workgroup then
+// plans the placement of the retained rows (select_body.h: plan_moves).
 #include "launch.h"
 #include "select_body.h"
 
@@ -126,58 +127,48 @@ __device__ __forceinline__ void select_body(const float* Wb, int32_t* I, int32_t
     else select_reg_body<KPT, TPB>(Wb, I, userI, user_count, h, cnd, r, R, B, cap);
 }
 
-// One stream: workgroups [0, Hkv) select, the next rc.ncopy move the recent window.
+// One workgroup per kv-head: selection, then the placement plan.
 template <int KPT>
 __global__ void __launch_bounds__(TPB)
 select_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __restrict__ userI,
-              int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap, int Hkv, RecentCopy rc)
+              int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap, int tc, CacheView c, MoveList mv)
 {
-    if ((int)blockIdx.x >= Hkv) { copy_recent<TPB>(rc, blockIdx.x - Hkv, Hkv, cnd, r, R, cap); return; }
-    select_body<KPT>(Wb, I, userI, user_count, blockIdx.x, cnd, r, R, B, cap);
+    const int h = blockIdx.x;
+    select_body<KPT>(Wb, I, userI, user_count, h, cnd, r, R, B, cap);
+    const size_t hb = (size_t)h * cap;
+    const PlanTables pt{c.row + hb, c.row_next + hb, c.rank + hb, c.score + hb, mv.src + (size_t)h * mv.max,
+                        mv.dst + (size_t)h * mv.max, mv.x + (size_t)h * mv.max, mv.count + h};
+    plan_moves<TPB>(I + (size_t)h * B, Wb + hb, tc, B, r, pt);
 }
 
 // Several streams of one geometry (the layers of a model, Alg. 1 Input note): stream j owns
-// workgroups [j * (Hkv + ncopy), (j + 1) * (Hkv + ncopy)) with the same split into selecting
-// and copying workgroups.
+// workgroups [j * Hkv, (j + 1) * Hkv).
 template <int KPT>
 __global__ void __launch_bounds__(TPB)
-select_batch_kernel(EvictBatch eb, int r, int R, int B, int cap, int Hkv, int vpr, int ncopy)
+select_batch_kernel(EvictBatch eb, int r, int R, int B, int cap, int Hkv)
 {
-    const int per = Hkv + ncopy, j = blockIdx.x / per, b = blockIdx.x % per;
+    const int j = blockIdx.x / Hkv, h = blockIdx.x % Hkv;
     const EvictJob& job = eb.job[j];
     const int cnd = job.n - R;
-    if (b >= Hkv) {
-        RecentCopy rc;
-        rc.Ks = (const u32x4*)job.src.K; rc.Vs = (const u32x4*)job.src.V; rc.ps = job.src.pos;
-        rc.kc = (const u32x4*)job.kc; rc.vc = (const u32x4*)job.vc;
-        rc.Kd = (u32x4*)job.dst.K; rc.Vd = (u32x4*)job.dst.V; rc.pd = job.dst.pos; rc.sd = job.dst.score;
-        rc.tc = job.tc; rc.pos0 = job.pos0; rc.vpr = vpr; rc.ncopy = ncopy;
-        copy_recent<TPB>(rc, b - Hkv, Hkv, cnd, r, R, cap);
-        return;
-    }
-    select_body<KPT>(job.Wb, job.I, job.user_I, job.user_count, b, cnd, r, R, B, cap);
+    select_body<KPT>(job.Wb, job.I, job.user_I, job.user_count, h, cnd, r, R, B, cap);
+    const size_t hb = (size_t)h * cap;
+    const PlanTables pt{job.c.row + hb, job.c.row_next + hb, job.c.rank + hb, job.c.score + hb,
+                        job.mv.src + (size_t)h * job.mv.max, job.mv.dst + (size_t)h * job.mv.max,
+                        job.mv.x + (size_t)h * job.mv.max, job.mv.count + h};
+    plan_moves<TPB>(job.I + (size_t)h * B, job.Wb + hb, job.tc, B, r, pt);
 }
 
 }  // namespace
 
-hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, int32_t* user_I,
-                         int32_t* user_count, const CacheView& src, const KeySource& ks, int64_t T,
-                         const CacheView& dst, hipStream_t st)
+hipError_t launch_select(const Geometry& g, const float* Wb, int n, int tc, int32_t* I, int32_t* user_I,
+                         int32_t* user_count, const CacheView& c, const MoveList& mv, hipStream_t st)
 {
     const int cnd = n - g.R, r = g.B - g.R;
-    RecentCopy rc;
-    rc.Ks = (const u32x4*)src.K; rc.Vs = (const u32x4*)src.V; rc.ps = src.pos;
-    rc.kc = (const u32x4*)ks.k; rc.vc = (const u32x4*)ks.v;
-    rc.Kd = (u32x4*)dst.K; rc.Vd = (u32x4*)dst.V; rc.pd = dst.pos; rc.sd = dst.score;
-    rc.tc = ks.rows; rc.pos0 = (int)T; rc.vpr = g.d * g.elt / 16;
-    // enough copy workgroups to cover the recent rows once with a few vectors per thread
-    const long vecs = (long)g.Hkv * g.R * rc.vpr;
-    long want = (vecs + 4 * TPB - 1) / (4 * TPB);
-    rc.ncopy = (int)(want > 448 ? 448 : want);
-    const dim3 grid(g.Hkv + rc.ncopy);
+    if (g.B > PLAN_MAX_B) return hipErrorInvalidValue;
+    const dim3 grid(g.Hkv);
 #define INFMLLM_SELECT(KPT)                                                                                \
     hipLaunchKernelGGL(select_kernel<KPT>, grid, dim3(TPB), 0, st, Wb, I, user_I, user_count, cnd, r, g.R, g.B, g.cap, \
-                       g.Hkv, rc)
+                       tc, c, mv)
     if (cnd <= 2 * TPB) INFMLLM_SELECT(2);
     else if (cnd <= 4 * TPB) INFMLLM_SELECT(4);
     else if (cnd <= 8 * TPB) INFMLLM_SELECT(8);
@@ -189,16 +180,13 @@ hipError_t launch_select(const Geometry& g, const float* Wb, int n, int32_t* I, 
 
 hipError_t launch_select_batch(const Geometry& g, const EvictBatch& eb, hipStream_t st)
 {
-    if (eb.count < 1 || eb.count > EVICT_MAX_JOBS) return hipErrorInvalidValue;
-    const int r = g.B - g.R, vpr = g.d * g.elt / 16;
+    if (eb.count < 1 || eb.count > EVICT_MAX_JOBS || g.B > PLAN_MAX_B) return hipErrorInvalidValue;
+    const int r = g.B - g.R;
     int cnd = 0;
     for (int j = 0; j < eb.count; ++j) cnd = eb.job[j].n - g.R > cnd ? eb.job[j].n - g.R : cnd;
-    const long vecs = (long)g.Hkv * g.R * vpr;
-    long want = (vecs + 4 * TPB - 1) / (4 * TPB);
-    const int ncopy = (int)(want > 448 ? 448 : want);
-    const dim3 grid((g.Hkv + ncopy) * eb.count);
+    const dim3 grid(g.Hkv * eb.count);
 #define INFMLLM_SELECT(KPT) \
-    hipLaunchKernelGGL(select_batch_kernel<KPT>, grid, dim3(TPB), 0, st, eb, r, g.R, g.B, g.cap, g.Hkv, vpr, ncopy)
+    hipLaunchKernelGGL(select_batch_kernel<KPT>, grid, dim3(TPB), 0, st, eb, r, g.R, g.B, g.cap, g.Hkv)
     if (cnd <= 2 * TPB) INFMLLM_SELECT(2);
     else if (cnd <= 4 * TPB) INFMLLM_SELECT(4);
     else if (cnd <= 8 * TPB) INFMLLM_SELECT(8);
