@@ -83,8 +83,8 @@ enum {
     INFMLLM_PARAM_ATTN_TILE = 7  /* debug/test, head_dim 128 on the matrix cores: 0 (default) = the
                                     attention launch picks its workgroup shape from the chunk length;
                                     1 = 128 query rows x 2 key ways x 64 keys, 2 = 64 rows x 4 ways x 32,
-                                    3 = 128 rows x 2 ways x 32, 4 = 128 rows x 1 way x 64.  Results are
-                                    the same up to the rounding order of the key-way merge          */
+                                    3 = 128 rows x 2 ways x 32, 4 = 128 rows x 1 way x 64, 5 = 256 rows with
+                                    64 rows per wavefront.  Results are the same up to rounding order  */
 };
 
 /*
@@ -122,8 +122,9 @@ size_t infmllm_stream_workspace_bytes(const infmllm_stream_t* s);
  * on.  The workspace holds the cache (one copy of K and V of budget + max_decode + max_chunk rows per
  * kv-head, stream positions, scores and the two tables that map physical rows to stream order and back:
  * an eviction leaves the retained rows where they are and only moves the chunk's survivors into the rows
- * it frees) and per-step temporaries; attach enqueues a clear of the whole workspace on that stream.  The cache starts empty.  Errors: EINVAL (null/misaligned workspace),
- * ENOMEM (too small), ESTATE (already attached), EHIP.
+ * it frees) and per-step temporaries; attach enqueues a clear of the whole workspace on that stream.
+ * The cache starts empty.  Errors: EINVAL (null/misaligned workspace; budget + max_decode + max_chunk - recent
+ * above 131072, the most candidates a step can rank), ENOMEM (too small), ESTATE (already attached), EHIP.
  */
 int infmllm_stream_attach(infmllm_stream_t* s, void* dev_workspace, size_t bytes, void* hip_stream);
 

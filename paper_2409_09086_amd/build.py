@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libinfmllm.so")
-SOURCES = ["api.hip", "cache_kernels.hip", "attn_simple.hip", "attn_mfma.hip", "decode_attn.hip", "rope.hip", "select_kernel.hip"]
+SOURCES = ["api.hip", "cache_kernels.hip", "attn_simple.hip", "attn_mfma.hip", "attn_mfma64.hip", "decode_attn.hip", "rope.hip", "select_kernel.hip"]
 # packed-fp32 instructions are switched off for every device pass
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -1,7 +1,6 @@
 // Host side of the C ABI declared in include/infmllm.h: argument checks, workspace carving,
-// the host bookkeeping of one stream (cached length, tokens streamed, which of the two
-// stream-order tables is live) and the sequence of kernel launches that makes up one
-// streaming step.  No device memory is allocated here and nothing synchronises.
+// the host bookkeeping of one stream (cached length, tokens streamed) and the sequence of
+// kernel launches that makes up one streaming step.  No device memory is allocated here and nothing synchronises.
 #include "../../include/infmllm.h"
 
 #include <algorithm>
@@ -59,7 +58,7 @@ struct infmllm_stream {
     bool attached;
     int static_dev = -1; // device whose library-owned workspace this stream holds (-1: caller's workspace)
     hipStream_t st;
-    CacheView cache;     // cache.row is the live stream-order table, cache.row_next the one an eviction writes
+    CacheView cache;
     MoveList mv;         // retained rows the pending or running eviction moves
     int len;             // rows cached
     int64_t streamed;    // tokens streamed so far
@@ -102,7 +101,7 @@ struct infmllm_stream {
     }
 
     struct Layout {
-        size_t K, V, pos, score, rank, row[2], lse, Wb, I, mv_src, mv_dst, mv_x, mv_count, score_part, dec_part, K_rot,
+        size_t K, V, pos, score, rank, row, lse, Wb, I, mv_src, mv_dst, mv_x, mv_score, mv_count, score_part, dec_part, K_rot,
             kc_rot, q_rot, rope_tab, total;
     };
     Layout layout() const
@@ -116,8 +115,7 @@ struct infmllm_stream {
         L.pos = off; off += ps;
         L.score = off; off += ps;
         L.rank = off; off += ps;
-        L.row[0] = off; off += ps;
-        L.row[1] = off; off += ps;
+        L.row = off; off += ps;
         L.lse = off; off += up((size_t)g.Hq * g.max_chunk * 4);
         L.Wb = off; off += ps;
         L.I = off; off += up((size_t)g.Hkv * g.B * 4);
@@ -125,6 +123,7 @@ struct infmllm_stream {
         L.mv_src = off; off += ml;
         L.mv_dst = off; off += ml;
         L.mv_x = off; off += ml;
+        L.mv_score = off; off += ml;
         L.mv_count = off; off += up((size_t)g.Hkv * 4);
         // row-split scoring (bf16 streams): partial column sums and arrival counters
         L.score_part = off; off += up(g.elt == 2 ? (size_t)SCORE_SPLIT_WGS * (256 + 1) * 4 : 0);
@@ -225,8 +224,8 @@ int infmllm_stream_set_param(infmllm_stream_t* s, int which, double value)
             s->impl = (int)value;
             return INFMLLM_OK;
         case INFMLLM_PARAM_ATTN_TILE:
-            if (value != 0 && value != 1 && value != 2 && value != 3 && value != 4)
-                return fail(INFMLLM_EINVAL, "set_param: attn_tile must be 0..4");
+            if (value != 0 && value != 1 && value != 2 && value != 3 && value != 4 && value != 5)
+                return fail(INFMLLM_EINVAL, "set_param: attn_tile must be 0..5");
             s->g.attn_tile = (int)value;
             return INFMLLM_OK;
         default:
@@ -248,6 +247,9 @@ int infmllm_stream_attach(infmllm_stream_t* s, void* ws, size_t bytes, void* hip
     if ((size_t)s->g.cap * 4 > 150 * 1024 && (s->dtype == INFMLLM_FP32 || s->impl == 1))
         return fail(INFMLLM_EINVAL, "attach: budget + max_chunk = %d rows is beyond what the plain-arithmetic "
                                     "attention kernel keeps in LDS (38400)", s->g.cap);
+    if (s->g.cap - s->g.R > 131072)
+        return fail(INFMLLM_EINVAL, "attach: budget + max_decode + max_chunk - recent = %d exceeds the 131072 candidates "
+                                    "a step can rank", s->g.cap - s->g.R);
     char* base = (char*)ws;
     {
         // kernels that read whole key tiles rely on every byte of the cache being finite
@@ -259,11 +261,11 @@ int infmllm_stream_attach(infmllm_stream_t* s, void* ws, size_t bytes, void* hip
     s->cache.pos = (int32_t*)(base + L.pos);
     s->cache.score = (float*)(base + L.score);
     s->cache.rank = (int32_t*)(base + L.rank);
-    s->cache.row = (int32_t*)(base + L.row[0]);
-    s->cache.row_next = (int32_t*)(base + L.row[1]);
+    s->cache.row = (int32_t*)(base + L.row);
     s->mv.src = (int32_t*)(base + L.mv_src);
     s->mv.dst = (int32_t*)(base + L.mv_dst);
     s->mv.x = (int32_t*)(base + L.mv_x);
+    s->mv.score = (float*)(base + L.mv_score);
     s->mv.count = (int32_t*)(base + L.mv_count);
     s->mv.max = s->g.max_chunk + s->g.max_decode;
     s->lse = (float*)(base + L.lse);
@@ -424,7 +426,6 @@ int step_front(infmllm_stream* s, const void* q, const void* k, const void* v, i
 // host bookkeeping once a5-a7 of a step of L tokens (n keys before eviction) have been launched
 void step_done(infmllm_stream* s, int n, int L)
 {
-    std::swap(s->cache.row, s->cache.row_next);
     s->len = s->g.B;
     s->last_cnd = n - s->g.R;
     s->streamed += L;
@@ -454,7 +455,7 @@ int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* 
     s->mark(INFMLLM_K_COMPACT, 0);
     // rows that can need a new home: the chunk rows read in place and the cached rows at or above the budget
     const int nmax = (n - ks.rows) + (ks.rows > g.B ? ks.rows - g.B : 0);
-    if ((e = launch_place(g, s->cache, ks, s->streamed, s->mv, s->Wb, nmax, s->st)) != hipSuccess)
+    if ((e = launch_place(g, s->cache, ks, s->streamed, s->mv, nmax, s->st)) != hipSuccess)
         return fail_hip(e, "step: placement");
     s->mark(INFMLLM_K_COMPACT, 1);
     step_done(s, n, L);

@@ -672,6 +672,7 @@ hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const KeySour
     const int wgs128 = g.Hq * ((L + 31) / 32) / 4;
     const int v = g.attn_tile > 0 ? g.attn_tile : (wgs128 >= 140 ? 1 : 2);
     switch (v) {
+        case 5: return launch_attn_mfma64(g, c, ks, q, t, L, out, lse, st);
         case 1: return launch_fwd_cfg<128, 4, 2, 2>(g, c, ks, q, t, L, out, lse, st);
         case 2: return launch_fwd_cfg<128, 2, 4, 1>(g, c, ks, q, t, L, out, lse, st);
         case 3: return launch_fwd_cfg<128, 4, 2, 1>(g, c, ks, q, t, L, out, lse, st);

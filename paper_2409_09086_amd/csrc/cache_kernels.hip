@@ -79,58 +79,54 @@ reset_tables_kernel(float* __restrict__ score, int32_t* __restrict__ rank, int32
     }
 }
 
-// Entry k of a head's move list: the token with stream-order index src[k] goes to physical row dst[k] and
-// has stream-order index x[k] from now on.  One thread per 16-byte vector of a row of K and V, two rows in
-// flight per thread.  A source row is either a cache row at or above B (never a destination, so no row is
-// read after it has been overwritten) or a row of the chunk tensors.
+// Entry k of a head's move list: the token in src[k] (a physical cache row at or above B, or a row of the
+// chunk tensors) goes to physical row dst[k] (below B) and has stream-order index x[k] from now on.  One
+// thread per 16-byte vector of a row of K and V, two rows in flight per thread.  Sources lie at or above B,
+// destinations below it, so no row is read after it has been overwritten.
 template <int VPR>
 __device__ __forceinline__ void place_body(u32x4* __restrict__ K, u32x4* __restrict__ V, int32_t* __restrict__ pos,
                                            float* __restrict__ score, int32_t* __restrict__ rank,
-                                           const int32_t* __restrict__ row_old, int32_t* __restrict__ row_new,
-                                           const u32x4* __restrict__ kc, const u32x4* __restrict__ vc, int tc, int pos0,
-                                           int Hkv, int r, int cap, const float* __restrict__ Wb,
+                                           int32_t* __restrict__ row, const u32x4* __restrict__ kc,
+                                           const u32x4* __restrict__ vc, int tc, int pos0, int Hkv, int cap,
                                            const int32_t* __restrict__ mv_src, const int32_t* __restrict__ mv_dst,
-                                           const int32_t* __restrict__ mv_x, const int32_t* __restrict__ mv_count,
-                                           int mv_max)
+                                           const int32_t* __restrict__ mv_x, const float* __restrict__ mv_score,
+                                           const int32_t* __restrict__ mv_count, int mv_max)
 {
     constexpr int ROWS = 256 / VPR, U = 2;        // rows per block pass, passes in flight
     const int h = blockIdx.y;
     const int lane_row = threadIdx.x / VPR, xv = threadIdx.x % VPR;
-    const long hb = (long)h * cap;
+    const long hb = (long)h * cap, mb = (long)h * mv_max;
     const int count = mv_count[h];
-    const int32_t* src = mv_src + (long)h * mv_max;
-    const int32_t* dst = mv_dst + (long)h * mv_max;
-    const int32_t* nx = mv_x + (long)h * mv_max;
     for (int k0 = blockIdx.x * ROWS * U; k0 < count; k0 += gridDim.x * ROWS * U) {
-        int j[U], p[U], sp[U];
+        int sp[U], p[U];
         u32x4 kk[U], vv[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int k = k0 + u * ROWS + lane_row;
-            j[u] = (k < count) ? src[k] : -1;
-            p[u] = (k < count) ? dst[k] : 0;
-            sp[u] = (j[u] >= 0 && j[u] < tc) ? row_old[hb + j[u]] : -1;
+            sp[u] = (k < count) ? mv_src[mb + k] : -1;
+            p[u] = (k < count) ? mv_dst[mb + k] : 0;
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (j[u] >= 0) {
-                const long off = sp[u] >= 0 ? (hb + sp[u]) * VPR + xv : ((long)(j[u] - tc) * Hkv + h) * VPR + xv;
-                kk[u] = __builtin_nontemporal_load((sp[u] >= 0 ? (const u32x4*)K : kc) + off);
-                vv[u] = __builtin_nontemporal_load((sp[u] >= 0 ? (const u32x4*)V : vc) + off);
+            if (sp[u] >= 0) {
+                const bool cached = sp[u] < tc;
+                const long off = cached ? (hb + sp[u]) * VPR + xv : ((long)(sp[u] - tc) * Hkv + h) * VPR + xv;
+                kk[u] = __builtin_nontemporal_load((cached ? (const u32x4*)K : kc) + off);
+                vv[u] = __builtin_nontemporal_load((cached ? (const u32x4*)V : vc) + off);
             }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (j[u] >= 0) {
+            if (sp[u] >= 0) {
                 K[(hb + p[u]) * VPR + xv] = kk[u];
                 V[(hb + p[u]) * VPR + xv] = vv[u];
                 if (xv == 0) {
                     const int k = k0 + u * ROWS + lane_row;
-                    const int x = nx[k];
-                    pos[hb + p[u]] = sp[u] >= 0 ? pos[hb + sp[u]] : pos0 + (j[u] - tc);
+                    const int x = mv_x[mb + k];
+                    pos[hb + p[u]] = sp[u] < tc ? pos[hb + sp[u]] : pos0 + (sp[u] - tc);
                     rank[hb + p[u]] = x;
-                    row_new[hb + x] = p[u];
-                    score[hb + p[u]] = x < r ? Wb[hb + j[u]] : __builtin_inff();
+                    row[hb + x] = p[u];
+                    score[hb + p[u]] = mv_score[mb + k];
                 }
             }
         }
@@ -140,24 +136,24 @@ __device__ __forceinline__ void place_body(u32x4* __restrict__ K, u32x4* __restr
 template <int VPR>
 __global__ void __launch_bounds__(256)
 place_kernel(u32x4* __restrict__ K, u32x4* __restrict__ V, int32_t* __restrict__ pos, float* __restrict__ score,
-             int32_t* __restrict__ rank, const int32_t* __restrict__ row_old, int32_t* __restrict__ row_new,
-             const u32x4* __restrict__ kc, const u32x4* __restrict__ vc, int tc, int pos0, int Hkv, int r, int cap,
-             const float* __restrict__ Wb, const int32_t* __restrict__ mv_src, const int32_t* __restrict__ mv_dst,
-             const int32_t* __restrict__ mv_x, const int32_t* __restrict__ mv_count, int mv_max)
+             int32_t* __restrict__ rank, int32_t* __restrict__ row, const u32x4* __restrict__ kc,
+             const u32x4* __restrict__ vc, int tc, int pos0, int Hkv, int cap, const int32_t* __restrict__ mv_src,
+             const int32_t* __restrict__ mv_dst, const int32_t* __restrict__ mv_x, const float* __restrict__ mv_score,
+             const int32_t* __restrict__ mv_count, int mv_max)
 {
-    place_body<VPR>(K, V, pos, score, rank, row_old, row_new, kc, vc, tc, pos0, Hkv, r, cap, Wb, mv_src, mv_dst, mv_x,
-                    mv_count, mv_max);
+    place_body<VPR>(K, V, pos, score, rank, row, kc, vc, tc, pos0, Hkv, cap, mv_src, mv_dst, mv_x, mv_score, mv_count,
+                    mv_max);
 }
 
 // blockIdx.z = stream of the batch
 template <int VPR>
 __global__ void __launch_bounds__(256)
-place_batch_kernel(EvictBatch eb, int Hkv, int r, int cap)
+place_batch_kernel(EvictBatch eb, int Hkv, int cap)
 {
     const EvictJob& j = eb.job[blockIdx.z];
-    place_body<VPR>((u32x4*)j.c.K, (u32x4*)j.c.V, j.c.pos, j.c.score, j.c.rank, j.c.row, j.c.row_next,
-                    (const u32x4*)j.kc, (const u32x4*)j.vc, j.tc, j.pos0, Hkv, r, cap, j.Wb, j.mv.src, j.mv.dst, j.mv.x,
-                    j.mv.count, j.mv.max);
+    place_body<VPR>((u32x4*)j.c.K, (u32x4*)j.c.V, j.c.pos, j.c.score, j.c.rank, j.c.row, (const u32x4*)j.kc,
+                    (const u32x4*)j.vc, j.tc, j.pos0, Hkv, cap, j.mv.src, j.mv.dst, j.mv.x, j.mv.score, j.mv.count,
+                    j.mv.max);
 }
 
 // out row j of head h <- physical row row[h][j]: the cache in stream order.
@@ -241,7 +237,7 @@ hipError_t launch_reset_tables(const Geometry& g, const CacheView& c, int len, h
 }
 
 hipError_t launch_place(const Geometry& g, const CacheView& c, const KeySource& ks, int64_t T, const MoveList& mv,
-                        const float* Wb, int nmax, hipStream_t st)
+                        int nmax, hipStream_t st)
 {
     const int vpr = g.d * g.elt / 16;             // 8 (d=64 bf16), 16 (d=128 bf16 / d=64 fp32), 32 (d=128 fp32)
     const int rows_per_pass = (256 / vpr) * 2;
@@ -250,8 +246,8 @@ hipError_t launch_place(const Geometry& g, const CacheView& c, const KeySource& 
     const dim3 grid((nmax + rows_per_pass - 1) / rows_per_pass, g.Hkv), block(256);
 #define INFMLLM_PLACE(VPR)                                                                                      \
     hipLaunchKernelGGL(place_kernel<VPR>, grid, block, 0, st, (u32x4*)c.K, (u32x4*)c.V, c.pos, c.score, c.rank, c.row, \
-                       c.row_next, (const u32x4*)ks.k, (const u32x4*)ks.v, ks.rows, (int)T, g.Hkv, g.B - g.R, g.cap, \
-                       Wb, mv.src, mv.dst, mv.x, mv.count, mv.max)
+                       (const u32x4*)ks.k, (const u32x4*)ks.v, ks.rows, (int)T, g.Hkv, g.cap, mv.src, mv.dst, mv.x,     \
+                       mv.score, mv.count, mv.max)
     switch (vpr) {
         case 8: INFMLLM_PLACE(8); break;
         case 16: INFMLLM_PLACE(16); break;
@@ -269,11 +265,10 @@ hipError_t launch_place_batch(const Geometry& g, const EvictBatch& eb, int nmax,
     const int rows_per_pass = (256 / vpr) * 2;
     if (nmax <= 0) return hipSuccess;
     const dim3 grid((nmax + rows_per_pass - 1) / rows_per_pass, g.Hkv, eb.count), block(256);
-    const int r = g.B - g.R;
     switch (vpr) {
-        case 8: hipLaunchKernelGGL(place_batch_kernel<8>, grid, block, 0, st, eb, g.Hkv, r, g.cap); break;
-        case 16: hipLaunchKernelGGL(place_batch_kernel<16>, grid, block, 0, st, eb, g.Hkv, r, g.cap); break;
-        case 32: hipLaunchKernelGGL(place_batch_kernel<32>, grid, block, 0, st, eb, g.Hkv, r, g.cap); break;
+        case 8: hipLaunchKernelGGL(place_batch_kernel<8>, grid, block, 0, st, eb, g.Hkv, g.cap); break;
+        case 16: hipLaunchKernelGGL(place_batch_kernel<16>, grid, block, 0, st, eb, g.Hkv, g.cap); break;
+        case 32: hipLaunchKernelGGL(place_batch_kernel<32>, grid, block, 0, st, eb, g.Hkv, g.cap); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -43,17 +43,18 @@ struct CacheView {
     float* score;       // [Hkv][cap]      W' the row was last retained with (+inf: never ranked)
     int32_t* rank;      // [Hkv][cap]      stream-order index (0 = oldest cached token) of each physical row
     int32_t* row;       // [Hkv][cap]      physical row of each stream-order index (inverse of rank)
-    int32_t* row_next;  // [Hkv][cap]      the table an eviction writes; the host swaps the two afterwards
 };
 
-// Retained rows an eviction has to move, per kv-head: entry k says that the token with stream-order
-// index src[k] (a cached row if < the cached length, else chunk row src[k] - cached length) becomes
-// physical row dst[k] with the new stream-order index x[k].  Written by the selection launch, read by
-// the placement launch.  max = max_chunk + max_decode entries per head.
+// Retained rows an eviction has to move, per kv-head: entry k says that the token in src[k] (physical
+// cache row src[k] if src[k] < tc, the rows in the cache; else row src[k] - tc of the chunk tensors)
+// becomes physical row dst[k] with the new stream-order index x[k] and the score entry score[k].
+// Written by the selection launch, read by the placement launch.  max = max_chunk + max_decode entries
+// per head.
 struct MoveList {
     int32_t* src;       // [Hkv][max]
     int32_t* dst;       // [Hkv][max]
     int32_t* x;         // [Hkv][max]
+    float* score;       // [Hkv][max]
     int32_t* count;     // [Hkv]
     int max;
 };
@@ -95,6 +96,11 @@ struct KeySource {
 hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q, int t, int L,
                             void* out, float* lse, hipStream_t st);
 
+// The same for head_dim 128 with 64 query rows per wavefront (one wavefront per SIMD, 256-row workgroups):
+// the shape for long key ranges and grids that fill the chip; launch_attn_mfma picks it by itself.
+hipError_t launch_attn_mfma64(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q, int t, int L,
+                              void* out, float* lse, hipStream_t st);
+
 // a3+a4 on bf16 MFMA (bf16 streams only).
 hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySource& ks, const void* q,
                              const float* lse, const FwdScratch& sc, int t, int L, float* Wb, hipStream_t st);
@@ -102,16 +108,16 @@ hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySou
 // a5+a6: I[h] = sort_asc(top-r of W'[h][0..cnd)) ++ [cnd, n), in stream-order indices.  I has row
 // stride B.  user_I (row stride B) and user_count may be null.  The same workgroup then plans the
 // placement (Alg. 1 l.8 without moving the rows that stay): a retained token whose physical row is
-// below B keeps it and gets its new rank, row_next and score entries here; the others go into the move
+// below B keeps it and gets its new rank, row and score entries here; the others go into the move
 // list, paired in order with the physical rows the eviction frees.  tc = rows in the cache (stream-order
 // indices from tc on are chunk rows read in place).
 hipError_t launch_select(const Geometry& g, const float* Wb, int n, int tc, int32_t* I, int32_t* user_I,
                          int32_t* user_count, const CacheView& c, const MoveList& mv, hipStream_t st);
 
 // a7: copies the K and V rows of the move list to their new physical rows and writes their pos, rank,
-// row_next and score entries.  nmax = most entries a head's list can hold in this step.
+// row and score entries.  nmax = most entries a head's list can hold in this step.
 hipError_t launch_place(const Geometry& g, const CacheView& c, const KeySource& ks, int64_t T, const MoveList& mv,
-                        const float* Wb, int nmax, hipStream_t st);
+                        int nmax, hipStream_t st);
 
 // One stream's share of a batched eviction (a5-a7 for the layers of a model in one launch each,
 // Alg. 1 Input note).  All streams of a batch have the same geometry.

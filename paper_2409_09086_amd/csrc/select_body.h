@@ -73,101 +73,117 @@ __device__ __forceinline__ uint32_t wave_extreme_to_last_lane(uint32_t x)
     return x;
 }
 
-// Largest budget the placement plan keeps its two bit maps for (one bit per retained slot, one per
-// physical row below B) in LDS.
-constexpr int PLAN_MAX_B = 131072;
+// What the selection leaves in LDS for the placement plan: for every segment of 64 candidates (stream-order
+// indices 64 s .. 64 s + 63) which of them are retained, and how many retained candidates precede the
+// segment.  The new stream-order index of a retained candidate j is base[j / 64] plus the retained ones below
+// it in its segment; a token of the recent window (j >= c) is retained with index r + (j - c).
+constexpr int PLAN_MAX_C = 131072;                            // most candidates (n - R) a step may have
+struct KeptMap {
+    uint64_t bits[PLAN_MAX_C / 64];
+    uint32_t base[PLAN_MAX_C / 64];
+};
 
-// Exclusive prefix sum of v over the TPB threads of the workgroup (all of them call it); *total = the sum.
-template <int TPB>
-__device__ __forceinline__ uint32_t block_exclusive_sum(uint32_t v, uint32_t* wsum /* [TPB/64] in LDS */, uint32_t* total)
-{
-    constexpr int NW = TPB / 64;
-    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
-    const uint32_t incl = wave_inclusive_sum(v);
-    if (l == 63) wsum[w] = incl;
-    __syncthreads();
-    uint32_t before = 0, all = 0;
-#pragma unroll
-    for (int x = 0; x < NW; ++x) {
-        const uint32_t s = wsum[x];
-        before += x < w ? s : 0u;
-        all += s;
-    }
-    __syncthreads();                                          // wsum may be reused by the next call
-    *total = all;
-    return before + incl - v;
-}
-
-// The tables of one kv-head that the placement plan reads and writes (see CacheView).
+// The tables of one kv-head that the placement plan reads and writes (see CacheView, MoveList).
 struct PlanTables {
-    const int32_t* row_old;    // [cap] physical row of each stream-order index before the eviction
-    int32_t* row_new;          // [cap] ... after it
-    int32_t* rank;             // [cap] stream-order index of each physical row (rewritten for rows 0..B-1)
+    int32_t* rank;             // [cap] stream-order index of each physical row: read, and rewritten for the rows that stay
+    int32_t* row;              // [cap] physical row of each stream-order index: written for the rows that stay
     float* score;              // [cap]
     int32_t* mv_src;           // [mv_max] move list of this head
     int32_t* mv_dst;
     int32_t* mv_x;
+    float* mv_score;
     int32_t* mv_count;         // one int
 };
 
-// Alg. 1 l.8 without moving the rows that stay.  Ih[0..B) is the retained list (stream-order indices,
-// ascending).  A retained token that is cached in a physical row below B keeps that row: its new index x
-// goes into rank / row_new, its score entry becomes W'[j] (+inf inside the recent window).  Every other
-// retained token (a chunk row, or a cached row at or above B) is a mover; the physical rows below B
-// that no retained token occupies are exactly as many, and the k-th mover (by x) is paired with the k-th
-// free row (ascending), which makes the layout a function of the retained list alone.  The K/V copies and
-// the movers' table entries are left to the placement launch.
+// Alg. 1 l.8 without moving the rows that stay.  Every physical row below max(tc, B) and every chunk row is
+// looked at once, 64 consecutive ones per wavefront, so that all table traffic is coalesced and the two lists
+// are compacted with ballots: a cached row whose token is retained and that lies below B keeps its place (its
+// new index goes into rank / row, its score entry becomes W'[j], +inf inside the recent window); a retained
+// token in a row at or above B, or in the chunk, is a mover; a row below B whose token is evicted (or that is
+// empty) is free.  There are exactly as many movers as free rows, and the k-th mover is paired with the k-th
+// free row, both in ascending order, which makes the layout a function of the retained set alone.  The K/V
+// copies and the movers' table entries are left to the placement launch.
 template <int TPB>
-__device__ __forceinline__ void plan_moves(const int32_t* __restrict__ Ih, const float* __restrict__ W, int tc, int B,
-                                           int r, const PlanTables& pt)
+__device__ __forceinline__ void plan_moves(const KeptMap& km, const float* __restrict__ W, int n, int tc, int cnd,
+                                           int B, int r, const PlanTables& pt)
 {
-    __shared__ uint32_t occ[PLAN_MAX_B / 32], mov[PLAN_MAX_B / 32];
-    __shared__ uint32_t wsum[TPB / 64];
-    const int tid = threadIdx.x;
-    const int words = (B + 31) / 32;
-    for (int w = tid; w < words; w += TPB) { occ[w] = 0u; mov[w] = 0u; }
-    __syncthreads();                                          // also: Ih as written by this workgroup is visible
-    for (int x = tid; x < B; x += TPB) {
-        const int j = Ih[x];
-        const int p = j < tc ? pt.row_old[j] : -1;
-        if (p >= 0 && p < B) {
-            atomicOr(&occ[p >> 5], 1u << (p & 31));
-            pt.rank[p] = x;
-            pt.row_new[x] = p;
-            pt.score[p] = x < r ? W[j] : __builtin_inff();
-        } else {
-            atomicOr(&mov[x >> 5], 1u << (x & 31));
-        }
-    }
-    __syncthreads();
+    constexpr int NW = TPB / 64, CH = 64 / NW;                 // CH passes of TPB items share one table of 64 counts
+    __shared__ uint32_t cnt_free[64], cnt_mov[64];
+    __shared__ uint32_t tot_free, tot_mov;
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
+    const uint64_t below = (l == 0) ? 0ull : (~0ull >> (64 - l));
+    const int P1 = tc > B ? tc : B;                           // physical rows looked at
+    const int nitems = P1 + (n - tc);                         // ... then the chunk rows read in place
+    // new index of token j, or -1 if it is evicted
+    auto new_index = [&](int j) -> int {
+        if (j >= cnd) return r + (j - cnd);
+        const uint64_t bits = km.bits[j >> 6];
+        if (!((bits >> (j & 63)) & 1ull)) return -1;
+        return (int)km.base[j >> 6] + __popcll(bits & ((1ull << (j & 63)) - 1ull));
+    };
     uint32_t fbase = 0, mbase = 0;                            // free rows / movers listed so far (uniform)
-    for (int w0 = 0; w0 < words; w0 += TPB) {
-        const int w = w0 + tid;
-        uint32_t f = 0u, m = 0u;
-        if (w < words) {
-            f = ~occ[w];
-            if (32 * w + 32 > B) f &= (1u << (B - 32 * w)) - 1u;   // only rows below B
-            m = mov[w];
+    __syncthreads();                                          // the kept map is complete
+    for (int q0 = 0; q0 < nitems; q0 += CH * TPB) {
+        int jj[CH], xs[CH], src[CH];
+        uint64_t bfree[CH], bmov[CH];
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {                        // every table load of the pass before any is used
+            const int q = q0 + u * TPB + tid;
+            jj[u] = q < tc ? pt.rank[q] : (q >= P1 && q < nitems ? tc + (q - P1) : -1);
         }
-        uint32_t ftot, mtot;
-        uint32_t fo = fbase + block_exclusive_sum<TPB>((uint32_t)__popc(f), wsum, &ftot);
-        uint32_t mo = mbase + block_exclusive_sum<TPB>((uint32_t)__popc(m), wsum, &mtot);
-        while (f) {
-            const int b = __ffs((int)f) - 1;
-            f &= f - 1u;
-            pt.mv_dst[fo++] = 32 * w + b;
+        float sc[CH];
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            xs[u] = jj[u] >= 0 ? new_index(jj[u]) : -1;
+            sc[u] = (xs[u] >= 0 && xs[u] < r) ? W[jj[u]] : __builtin_inff();
         }
-        while (m) {
-            const int b = __ffs((int)m) - 1;
-            m &= m - 1u;
-            const int x = 32 * w + b;
-            pt.mv_src[mo] = Ih[x];
-            pt.mv_x[mo++] = x;
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const int q = q0 + u * TPB + tid;
+            const bool kept = xs[u] >= 0;
+            const bool stays = kept && q < tc && q < B;
+            const bool moves = kept && !stays;
+            const bool is_free = !kept && q < B;
+            src[u] = q < P1 ? q : jj[u];                      // a cache row below tc, or tc + chunk row
+            if (stays) {
+                pt.rank[q] = xs[u];
+                pt.row[xs[u]] = q;
+                pt.score[q] = sc[u];
+            }
+            bfree[u] = __ballot(is_free);
+            bmov[u] = __ballot(moves);
+            if (l == 0) {
+                cnt_free[u * NW + w] = (uint32_t)__popcll(bfree[u]);
+                cnt_mov[u * NW + w] = (uint32_t)__popcll(bmov[u]);
+            }
         }
-        fbase += ftot;
-        mbase += mtot;
+        __syncthreads();
+        if (w == 0) {
+            const uint32_t v = cnt_free[l], incl = wave_inclusive_sum(v);
+            cnt_free[l] = incl - v;
+            if (l == 63) tot_free = incl;
+        } else if (w == 1) {
+            const uint32_t v = cnt_mov[l], incl = wave_inclusive_sum(v);
+            cnt_mov[l] = incl - v;
+            if (l == 63) tot_mov = incl;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const int q = q0 + u * TPB + tid;
+            if ((bfree[u] >> l) & 1ull) pt.mv_dst[fbase + cnt_free[u * NW + w] + (uint32_t)__popcll(bfree[u] & below)] = q;
+            if ((bmov[u] >> l) & 1ull) {
+                const uint32_t k = mbase + cnt_mov[u * NW + w] + (uint32_t)__popcll(bmov[u] & below);
+                pt.mv_src[k] = src[u];
+                pt.mv_x[k] = xs[u];
+                pt.mv_score[k] = sc[u];
+            }
+        }
+        fbase += tot_free;
+        mbase += tot_mov;
+        __syncthreads();                                      // the count tables are rewritten by the next pass
     }
-    if (tid == 0) *pt.mv_count = (int32_t)mbase;               // = fbase: B rows are retained, B rows lie below B
+    if (tid == 0) *pt.mv_count = (int32_t)mbase;               // = fbase: B tokens are retained, B rows lie below B
 }
 
 // Same selection with the candidates of a head held in registers (KPT keys per thread, key
@@ -181,7 +197,7 @@ __device__ __forceinline__ void plan_moves(const int32_t* __restrict__ Ih, const
 template <int KPT, int TPB>
 __device__ __forceinline__ void select_reg_body(const float* __restrict__ Wb, int32_t* __restrict__ I,
                                                 int32_t* __restrict__ userI, int32_t* __restrict__ user_count,
-                                                int h, int cnd, int r, int R, int B, int cap)
+                                                int h, int cnd, int r, int R, int B, int cap, KeptMap& km)
 {
     constexpr int NW = TPB / 64;
     static_assert(TPB >= 512, "one wavefront searches the bins while four others clear the next histogram");
@@ -278,15 +294,22 @@ __device__ __forceinline__ void select_reg_body(const float* __restrict__ Wb, in
             const uint32_t eq_rank = eq_before + (uint32_t)__popcll(beq[k] & below);
             const bool keep_eq = ((beq[k] >> l) & 1ull) && eq_rank >= skip_eq;
             const uint64_t bke = __ballot(keep_eq);
+            // kept before this segment: every greater key, and the ties past the dropped ones
+            const uint32_t seg_base = tab_gt[k * NW + w] + (eq_before > skip_eq ? eq_before - skip_eq : 0u);
+            if (l == 0) {                                     // for the placement plan
+                km.bits[k * NW + w] = bgt[k] | bke;
+                km.base[k * NW + w] = seg_base;
+            }
             if (keep_eq || ((bgt[k] >> l) & 1ull)) {
-                // kept before this segment: every greater key, and the ties past the dropped ones
-                const uint32_t dst = tab_gt[k * NW + w] + (eq_before > skip_eq ? eq_before - skip_eq : 0u)
-                                   + (uint32_t)__popcll((bgt[k] | bke) & below);
+                const uint32_t dst = seg_base + (uint32_t)__popcll((bgt[k] | bke) & below);
                 const int j = k * TPB + tid;
                 Ih[dst] = j;
                 if (Uh) Uh[dst] = j;
             }
         }
+    }
+    else {
+        for (int sgm = tid; sgm < (cnd + 63) / 64; sgm += TPB) { km.bits[sgm] = 0ull; km.base[sgm] = 0u; }   // nothing ranked
     }
     for (int x = tid; x < R; x += TPB) {                      // recent window: [c, n)
         Ih[r + x] = cnd + x;

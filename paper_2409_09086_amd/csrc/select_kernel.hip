@@ -22,7 +22,7 @@ constexpr int NW = TPB / 64;
 // Selection of kv-head h by one workgroup, candidates re-read from memory in every pass.
 __device__ __forceinline__ void select_mem_body(const float* __restrict__ Wb, int32_t* __restrict__ I,
                                                 int32_t* __restrict__ userI, int32_t* __restrict__ user_count,
-                                                int h, int cnd, int r, int R, int B, int cap)
+                                                int h, int cnd, int r, int R, int B, int cap, KeptMap& km)
 {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_prefix, s_remaining, s_ties;
@@ -93,8 +93,13 @@ __device__ __forceinline__ void select_mem_body(const float* __restrict__ Wb, in
             const uint64_t bk = __ballot(keep);
             if (l == 0) wave_keep[w] = (uint32_t)__popcll(bk);
             __syncthreads();
-            uint32_t dst = run_keep + (uint32_t)__popcll(bk & below);
-            for (int x = 0; x < w; ++x) dst += wave_keep[x];
+            uint32_t seg_base = run_keep;
+            for (int x = 0; x < w; ++x) seg_base += wave_keep[x];
+            if (l == 0) {                                     // for the placement plan
+                km.bits[j0 / 64 + w] = bk;
+                km.base[j0 / 64 + w] = seg_base;
+            }
+            const uint32_t dst = seg_base + (uint32_t)__popcll(bk & below);
             if (keep) {
                 Ih[dst] = j;
                 if (Uh) Uh[dst] = j;
@@ -109,6 +114,9 @@ __device__ __forceinline__ void select_mem_body(const float* __restrict__ Wb, in
             __syncthreads();
         }
     }
+    else {
+        for (int sgm = threadIdx.x; sgm < (cnd + 63) / 64; sgm += TPB) { km.bits[sgm] = 0ull; km.base[sgm] = 0u; }
+    }
     // ---- recent window: [c, n) -------------------------------------------------------------
     for (int x = threadIdx.x; x < R; x += TPB) {
         Ih[r + x] = cnd + x;
@@ -121,10 +129,10 @@ __device__ __forceinline__ void select_mem_body(const float* __restrict__ Wb, in
 // KPT = 0: candidates stay in memory.
 template <int KPT>
 __device__ __forceinline__ void select_body(const float* Wb, int32_t* I, int32_t* userI, int32_t* user_count, int h,
-                                            int cnd, int r, int R, int B, int cap)
+                                            int cnd, int r, int R, int B, int cap, KeptMap& km)
 {
-    if constexpr (KPT == 0) select_mem_body(Wb, I, userI, user_count, h, cnd, r, R, B, cap);
-    else select_reg_body<KPT, TPB>(Wb, I, userI, user_count, h, cnd, r, R, B, cap);
+    if constexpr (KPT == 0) select_mem_body(Wb, I, userI, user_count, h, cnd, r, R, B, cap, km);
+    else select_reg_body<KPT, TPB>(Wb, I, userI, user_count, h, cnd, r, R, B, cap, km);
 }
 
 // One workgroup per kv-head: selection, then the placement plan.
@@ -133,12 +141,13 @@ __global__ void __launch_bounds__(TPB)
 select_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __restrict__ userI,
               int32_t* __restrict__ user_count, int cnd, int r, int R, int B, int cap, int tc, CacheView c, MoveList mv)
 {
+    __shared__ KeptMap km;
     const int h = blockIdx.x;
-    select_body<KPT>(Wb, I, userI, user_count, h, cnd, r, R, B, cap);
-    const size_t hb = (size_t)h * cap;
-    const PlanTables pt{c.row + hb, c.row_next + hb, c.rank + hb, c.score + hb, mv.src + (size_t)h * mv.max,
-                        mv.dst + (size_t)h * mv.max, mv.x + (size_t)h * mv.max, mv.count + h};
-    plan_moves<TPB>(I + (size_t)h * B, Wb + hb, tc, B, r, pt);
+    select_body<KPT>(Wb, I, userI, user_count, h, cnd, r, R, B, cap, km);
+    const size_t hb = (size_t)h * cap, mb = (size_t)h * mv.max;
+    const PlanTables pt{c.rank + hb, c.row + hb, c.score + hb, mv.src + mb, mv.dst + mb, mv.x + mb, mv.score + mb,
+                        mv.count + h};
+    plan_moves<TPB>(km, Wb + hb, cnd + R, tc, cnd, B, r, pt);
 }
 
 // Several streams of one geometry (the layers of a model, Alg. 1 Input note): stream j owns
@@ -149,13 +158,13 @@ select_batch_kernel(EvictBatch eb, int r, int R, int B, int cap, int Hkv)
 {
     const int j = blockIdx.x / Hkv, h = blockIdx.x % Hkv;
     const EvictJob& job = eb.job[j];
+    __shared__ KeptMap km;
     const int cnd = job.n - R;
-    select_body<KPT>(job.Wb, job.I, job.user_I, job.user_count, h, cnd, r, R, B, cap);
-    const size_t hb = (size_t)h * cap;
-    const PlanTables pt{job.c.row + hb, job.c.row_next + hb, job.c.rank + hb, job.c.score + hb,
-                        job.mv.src + (size_t)h * job.mv.max, job.mv.dst + (size_t)h * job.mv.max,
-                        job.mv.x + (size_t)h * job.mv.max, job.mv.count + h};
-    plan_moves<TPB>(job.I + (size_t)h * B, job.Wb + hb, job.tc, B, r, pt);
+    select_body<KPT>(job.Wb, job.I, job.user_I, job.user_count, h, cnd, r, R, B, cap, km);
+    const size_t hb = (size_t)h * cap, mb = (size_t)h * job.mv.max;
+    const PlanTables pt{job.c.rank + hb, job.c.row + hb, job.c.score + hb, job.mv.src + mb, job.mv.dst + mb,
+                        job.mv.x + mb, job.mv.score + mb, job.mv.count + h};
+    plan_moves<TPB>(km, job.Wb + hb, job.n, job.tc, cnd, B, r, pt);
 }
 
 }  // namespace
@@ -164,7 +173,7 @@ hipError_t launch_select(const Geometry& g, const float* Wb, int n, int tc, int3
                          int32_t* user_count, const CacheView& c, const MoveList& mv, hipStream_t st)
 {
     const int cnd = n - g.R, r = g.B - g.R;
-    if (g.B > PLAN_MAX_B) return hipErrorInvalidValue;
+    if (cnd > PLAN_MAX_C) return hipErrorInvalidValue;
     const dim3 grid(g.Hkv);
 #define INFMLLM_SELECT(KPT)                                                                                \
     hipLaunchKernelGGL(select_kernel<KPT>, grid, dim3(TPB), 0, st, Wb, I, user_I, user_count, cnd, r, g.R, g.B, g.cap, \
@@ -180,10 +189,11 @@ hipError_t launch_select(const Geometry& g, const float* Wb, int n, int tc, int3
 
 hipError_t launch_select_batch(const Geometry& g, const EvictBatch& eb, hipStream_t st)
 {
-    if (eb.count < 1 || eb.count > EVICT_MAX_JOBS || g.B > PLAN_MAX_B) return hipErrorInvalidValue;
+    if (eb.count < 1 || eb.count > EVICT_MAX_JOBS) return hipErrorInvalidValue;
     const int r = g.B - g.R;
     int cnd = 0;
     for (int j = 0; j < eb.count; ++j) cnd = eb.job[j].n - g.R > cnd ? eb.job[j].n - g.R : cnd;
+    if (cnd > PLAN_MAX_C) return hipErrorInvalidValue;
     const dim3 grid(g.Hkv * eb.count);
 #define INFMLLM_SELECT(KPT) \
     hipLaunchKernelGGL(select_batch_kernel<KPT>, grid, dim3(TPB), 0, st, eb, r, g.R, g.B, g.cap, g.Hkv)

@@ -89,7 +89,7 @@ def test_step_errors_leave_the_stream_unchanged():
     assert e.value.code == B.ECAPACITY and len(s) == 0 and s.streamed == 0
 
 
-@pytest.mark.parametrize("tile", [1, 2, 3, 4])
+@pytest.mark.parametrize("tile", [1, 2, 3, 4, 5])
 @pytest.mark.parametrize("heads,kv,budget,recent,chunks", [
     (4, 4, 192, 64, [64, 100, 37, 129, 192, 1, 77]),                # ragged chunks, causal tiles of every shape
     (8, 2, 320, 128, [128, 128, 128, 45, 128]),                     # grouped heads: row blocks of one tile span heads
@@ -107,7 +107,7 @@ def test_every_attention_tile_shape(tile, heads, kv, budget, recent, chunks):
 
 def test_bad_attention_tile_is_refused():
     with pytest.raises(B.InfMLLMError) as e:
-        B.Stream(64, 16, 2, 2, 128, dtype=torch.bfloat16, attn_tile=5)
+        B.Stream(64, 16, 2, 2, 128, dtype=torch.bfloat16, attn_tile=6)
     assert e.value.code == B.EINVAL
 
 
