@@ -213,7 +213,7 @@ def measure(cfg, args, binding, dev, steps, nchunks, full):
 
     s = binding.Stream(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, dtype=cfg.torch_dtype,
                        bias=cfg.bias, max_chunk=cfg.max_chunk, impl=args.impl, policy=args.policy,
-                       rope_base=args.rope or None, device=dev)
+                       rope_base=args.rope or None, attn_tile=args.attn_tile, device=dev)
     lib = binding.lib()
     P = ctypes.c_void_p
     cargs = [(P(q.data_ptr()), P(k.data_ptr()), P(v.data_ptr())) for q, k, v in chunks]
@@ -345,10 +345,11 @@ def main():
     ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"],
                     help="the headline workload (default: the largest single-GPU one)")
     ap.add_argument("--sub", default="cfg1,cfg2,cfg3,cfg4",
-                    help="comma-separated workloads carried as sub-records under \"workloads\" (empty = none)")
+                    help="comma-separated workloads carried as sub-records under \"workloads\" (\"none\" = none)")
     ap.add_argument("--chunks", type=int, default=8, help="distinct chunks kept in HBM and cycled through")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--impl", type=int, default=None, help="debug: 1 = plain-arithmetic kernels")
+    ap.add_argument("--attn-tile", type=int, default=None, help="debug: force a workgroup shape of the attention kernel")
     ap.add_argument("--policy", default="infmllm", choices=["infmllm", "window", "initial_recent", "cumulative"],
                     help="score the selection ranks (comparison policies); the default is the paper's method")
     ap.add_argument("--rope", type=float, default=0.0, metavar="BASE",
@@ -392,7 +393,7 @@ def main():
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(cfg, budget_seconds=12.0, policy=args.policy, rope_base=args.rope)
     subs = {}
-    for name in [x for x in args.sub.split(",") if x and x != args.workload]:
+    for name in [x for x in args.sub.split(",") if x in CONFIGS and x != args.workload]:
         sc = CONFIGS[name]
         torch.cuda.empty_cache()
         r = measure(sc, args, binding, dev, max(4, min(args.steps, 200)), args.chunks, full=False)

@@ -224,7 +224,7 @@ int infmllm_stream_set_param(infmllm_stream_t* s, int which, double value)
             s->impl = (int)value;
             return INFMLLM_OK;
         case INFMLLM_PARAM_ATTN_TILE:
-            if (value != 0 && value != 1 && value != 2 && value != 3 && value != 4 && value != 5)
+            if (value < 0 || value > 5 || value != std::floor(value))
                 return fail(INFMLLM_EINVAL, "set_param: attn_tile must be 0..5");
             s->g.attn_tile = (int)value;
             return INFMLLM_OK;

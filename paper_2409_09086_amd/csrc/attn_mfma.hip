@@ -670,7 +670,13 @@ hipError_t launch_attn_mfma(const Geometry& g, const CacheView& c, const KeySour
     // only about half of the chip (128 workgroups at 32 heads x 512 rows), 64-row workgroups with four
     // key ways inside the workgroup are faster.  g.attn_tile > 0 (a test hook) forces one shape.
     const int wgs128 = g.Hq * ((L + 31) / 32) / 4;
-    const int v = g.attn_tile > 0 ? g.attn_tile : (wgs128 >= 140 ? 1 : 2);
+    // attn_fwd64 (attn_mfma64.hip: 64 query rows per wavefront, one wavefront per SIMD) is the faster kernel
+    // where its grid of 256-row workgroups covers the chip and the key range is long enough to fill its pipeline.
+    // Its workgroups occupy a CU each: the grid must fill at least 80 % of the rounds over the 256 CUs it takes.
+    const int wgs64 = (g.Hq * ((L + 63) / 64) + 3) / 4;
+    const int rounds64 = (wgs64 + 255) / 256;
+    const bool fills = wgs64 * 5 >= rounds64 * 256 * 4;
+    const int v = g.attn_tile > 0 ? g.attn_tile : (fills && t + L >= 1024 ? 5 : (wgs128 >= 140 ? 1 : 2));
     switch (v) {
         case 5: return launch_attn_mfma64(g, c, ks, q, t, L, out, lse, st);
         case 1: return launch_fwd_cfg<128, 4, 2, 2>(g, c, ks, q, t, L, out, lse, st);
