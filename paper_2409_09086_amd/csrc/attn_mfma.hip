@@ -402,7 +402,9 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
 
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: what depends on it stays scalar
-    const int cg = wave & 3, rg = wave >> 2;                  // column group, row group
+    // column group, row group: wavefronts 2k and 2k + 1 share the columns and take a row group each (measured
+    // 4 % faster than pairing k with k + 4)
+    const int cg = wave >> 1, rg = wave & 1;
     // all column blocks of a kv-head get workgroup ids of one residue class mod 8, i.e. one XCD,
     // so that the head's scored queries are fetched into one L2 only
     // With rsplit > 1 the scored rows of a column block are shared out over rsplit workgroups (slice rs).
@@ -437,8 +439,16 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
     // Row log-sum-exp of every scored row of the group, once per workgroup: row (gg, i) -> s_lse[gg*lq + i].
     auto row_lse = [&](int g, int i) -> float { return lse2[(size_t)g * max_chunk + i]; };
     const bool lse_in_lds = G * lq <= LSE_ROWS;
-    if (lse_in_lds)
-        for (int x = tid; x < G * lq; x += 512) s_lse[x] = row_lse(h * G + x / lq, L - lq + x % lq);
+    // every load is issued before the first value is stored, together with those of the first query blocks
+    // and of the key tile below: the prologue then waits for memory once, not once per group of 512 rows
+    float lse_in[LSE_ROWS / 512];
+    if (lse_in_lds) {
+#pragma unroll
+        for (int u = 0; u < LSE_ROWS / 512; ++u) {
+            const int x = tid + u * 512;
+            lse_in[u] = x < G * lq ? row_lse(h * G + x / lq, L - lq + x % lq) : 0.f;
+        }
+    }
 
     // Staging of the next four blocks.  Chunk u of a thread is row rr of block slot u * RPU / 32 + sbase (the
     // slot is uniform over a wavefront), so the block's address is scalar and only toff is per lane.  The
@@ -525,6 +535,13 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
             *(u32x4*)(ktile + (ch / CPR) * QP + (ch % CPR) * 16) = kt[u];
         }
     }
+    if (lse_in_lds) {
+#pragma unroll
+        for (int u = 0; u < LSE_ROWS / 512; ++u) {
+            const int x = tid + u * 512;
+            if (x < G * lq) s_lse[x] = lse_in[u];
+        }
+    }
     if (niter > 0) {
         stash(0);
         if (niter > 1) fetch(true);
@@ -537,55 +554,75 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
 #pragma unroll
         for (int s = 0; s < D / 16; ++s) kf[cb][s] = as_bf16x8(*(const u32x4*)(kp + 32 * s));
     }
-    for (int it = 0; it < niter; ++it) {
-        const char* base = smem + (it & 1) * BUF;
-        // A row group takes two of the four blocks.  The fragments of both are requested up front, so that
-        // only the first product waits for LDS; each block is then formed (8*CB MFMAs) and weighed (exp2)
-        // in turn through one set of accumulators, and the other wavefront of the SIMD, a phase apart, has
-        // the matrix pipe while this one is in its exponentials.
-        bf16x8 qf[2][D / 16];
+    // A row group takes two of the four blocks of an iteration: each is formed (8*CB MFMAs) and then weighed
+    // (exp2 of every logit).  The two wavefronts of a SIMD (row groups 0 and 1 of one column group) leave the
+    // barrier together; if both formed and weighed in the same order they would queue for the matrix pipe and
+    // then for the vector unit.  Row group 1 therefore weighs its second block one
+    // iteration late, at the head of the next iteration, while row group 0 forms its first block, and from
+    // then on one wavefront of the SIMD is in its MFMAs while the other is in its exponentials.
+    auto load_q = [&](const char* base, int k, bf16x8 (&qf)[D / 16]) {
+        const char* qp = base + (64 * rg + 32 * k + l32) * QP + 16 * hh;
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            const char* qp = base + (64 * rg + 32 * k + l32) * QP + 16 * hh;
+        for (int s = 0; s < D / 16; ++s) qf[s] = as_bf16x8(*(const u32x4*)(qp + 32 * s));
+    };
+    // lane (column, half hh) holds rows 8a + 4hh + e of a block in register 4a + e
+    auto load_ls = [&](const char* base, int k, f32x4 (&ls)[4]) {
+        const float* lp = (const float*)(base + QBYTES) + 64 * rg + 32 * k;
 #pragma unroll
-            for (int s = 0; s < D / 16; ++s) qf[k][s] = as_bf16x8(*(const u32x4*)(qp + 32 * s));
-        }
+        for (int a = 0; a < 4; ++a) ls[a] = *(const f32x4*)(lp + 8 * a + 4 * hh);
+    };
+    auto form = [&](const bf16x8 (&qf)[D / 16], f32x16 (&acc)[CB]) {
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            f32x16 acc[CB];
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s)
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
+                acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[s], kf[cb][s], acc[cb], 0, 0, 0);
+    };
+    auto weigh = [&](const f32x16 (&acc)[CB], const f32x4 (&ls)[4]) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
+        for (int a = 0; a < 4; ++a)
 #pragma unroll
-            for (int s = 0; s < D / 16; ++s)
+            for (int e = 0; e < 4; ++e)
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb)
-                    acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[k][s], kf[cb][s], acc[cb], 0, 0, 0);
-            // lane (column, half hh) holds rows 8a + 4hh + e of a block in register 4a + e
-            const float* lp = (const float*)(base + QBYTES) + 64 * rg + 32 * k;
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const f32x4 ls = *(const f32x4*)(lp + 8 * a + 4 * hh);
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int cb = 0; cb < CB; ++cb)
-                        part[cb][4 * a + e] += fast_exp2(__builtin_fmaf(acc[cb][4 * a + e], c, -ls[e]));
-            }
-            // One set of accumulators: block 1 is formed after block 0 is weighed.  The empty statement makes
-            // block 1's first operand depend on block 0's sums, which is what keeps the compiler from gathering
-            // all MFMAs first and all exponentials last.
-            if (k == 0) {
-                if constexpr (CB == 2) asm volatile("" : "+v"(part[0]), "+v"(part[1]), "+v"(qf[1][0]));
-                else asm volatile("" : "+v"(part[0]), "+v"(qf[1][0]));
-            }
+                    part[cb][4 * a + e] += fast_exp2(__builtin_fmaf(acc[cb][4 * a + e], c, -ls[a][e]));
+    };
+    f32x16 acc[CB];                                           // row group 1 carries its second block over the barrier
+    f32x4 pls[4];                                             // ... with the log-sum-exps of its rows
+    for (int it = 0; it < niter; ++it) {
+        const char* base = smem + (it & 1) * BUF;
+        bf16x8 qf[D / 16];
+        f32x4 ls[4];
+        load_q(base, 0, qf);
+        if (rg == 1 && it > 0) {
+            weigh(acc, pls);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        form(qf, acc);
+        __builtin_amdgcn_sched_barrier(0);
+        load_q(base, 1, qf);
+        load_ls(base, 0, ls);
+        weigh(acc, ls);
+        __builtin_amdgcn_sched_barrier(0);
+        form(qf, acc);
+        __builtin_amdgcn_sched_barrier(0);
+        if (rg == 0) {
+            load_ls(base, 1, ls);
+            weigh(acc, ls);
+        } else {
+            load_ls(base, 1, pls);                            // taken now: the buffer is rewritten before they are used
+        }
+        __builtin_amdgcn_sched_barrier(0);
         // the other buffer was last read one iteration ago, before the barrier that ended it
         if (it + 1 < niter) stash((it + 1) & 1);
         if (it + 2 < niter) fetch();
         __syncthreads();
     }
+    if (rg == 1 && niter > 0) weigh(acc, pls);
     // column sums: 16 registers, the two half-waves, then the two row groups (fixed order)
     float sum[CB];
 #pragma unroll
