@@ -99,6 +99,52 @@ def cpu_baseline(cfg, budget_seconds=12.0, policy="infmllm", rope_base=0.0, max_
             "ms_per_step": 1e3 * spent / steps}
 
 
+def retention_leg(cfg, binding, dev, impl):
+    """Sanity figure: what becomes of the keys the stream generator planted (cfg2: 1 % of the tokens carry a shared
+    offset on every key dimension; cfg5: a bank of 128 keys recurs every 100 000 tokens).  A short untimed stream is
+    run and the positions still cached are compared with the planted ones, counting only tokens that have left the
+    recent window (inside it everything is kept).  None for workloads that plant nothing."""
+    import numpy as np
+    from paper_2409_09086_amd.workloads import ChunkStream
+    if not (cfg.heavy_frac or cfg.recur_period):
+        return None
+    fill = -(-cfg.budget // cfg.chunk)
+    if cfg.recur_period:
+        hit_step = cfg.recur_period // cfg.chunk             # the step in which the bank arrives a second time
+        stream, steps = ChunkStream(cfg, start_step=hit_step - fill), fill + 6
+    else:
+        stream, steps = ChunkStream(cfg), fill + 12
+    first = stream.tokens
+    s = binding.Stream(cfg.budget, cfg.recent, cfg.heads, cfg.kv_heads, cfg.head_dim, dtype=cfg.torch_dtype,
+                       bias=cfg.bias, max_chunk=cfg.max_chunk, impl=impl, device=dev)
+    planted = []
+    for _ in range(steps):
+        q, k, v = next(stream)
+        planted.append(stream.last_planted)
+        s.step(q.to(dev), k.to(dev), v.to(dev), report=False)
+    planted = np.concatenate(planted)
+    total = planted.shape[0]
+    pos = s.positions().cpu().numpy()                        # [Hkv][B] stream positions, counted from this stream's start
+    old = np.arange(total) < total - cfg.recent              # tokens outside the recent window
+    kept = np.zeros((cfg.kv_heads, total), dtype=bool)
+    for h in range(cfg.kv_heads):
+        kept[h, pos[h]] = True
+    n_pl = int((planted & old).sum())
+    return {"steps": steps, "first_token": first, "planted_tokens_outside_recent_window": n_pl,
+            "planted_kept_frac": round(float(kept[:, planted & old].mean()), 4) if n_pl else None,
+            "all_kept_frac": round(float(kept[:, old].mean()), 4)}
+
+
+def attn_kernel_name(cfg, L, mfma):
+    """Which attention kernel the library's launch picks for this shape (the rule of launch_attn_mfma)."""
+    if not mfma:
+        return "attn_simple"
+    wgs64 = (cfg.heads * (-(-L // 64)) + 3) // 4
+    rounds = -(-wgs64 // 256)
+    fills = wgs64 * 5 >= rounds * 256 * 4
+    return "attn_fwd64" if cfg.head_dim == 128 and fills and cfg.budget + L >= 1024 else "attn_fwd"
+
+
 def decode_leg(cfg, binding, chunks, dev, impl, ntok=64):
     """Secondary figure: decoding steps (one token, no eviction) on the same layer with the cache full."""
     import torch
@@ -303,7 +349,7 @@ def measure(cfg, args, binding, dev, steps, nchunks, full):
     mfma = cfg.dtype == "bf16" and args.impl != 1
     peak = PEAK_BF16_TFLOPS if mfma else PEAK_FP32_TFLOPS
     ctr = read_counters("attn_fwd_%s_pmc.txt" % cfg.name)
-    roofline = {"kernel": "attn_fwd" if mfma else "attn_simple", "bound": "mfma" if mfma else "alu",
+    roofline = {"kernel": attn_kernel_name(cfg, L, mfma), "bound": "mfma" if mfma else "alu",
                 "achieved": attn["tflops"], "peak": peak, "unit": "TFLOP/s", "frac": round(attn["tflops"] / peak, 4),
                 "traffic": ctr["traffic"], "mfma_busy_counter": ctr["mfma_busy"], "counters_from": ctr["source"],
                 "algorithmic_flops_per_launch": work["attn"]["flops"], "avg_us": attn["us"]}
@@ -328,6 +374,10 @@ def measure(cfg, args, binding, dev, steps, nchunks, full):
         rec["step_latency_us"] = latency
     rec["decode"] = decode_leg(cfg, binding, chunks, dev, args.impl)
     del s
+    if args.policy == "infmllm" and not args.rope:
+        ret = retention_leg(cfg, binding, dev, args.impl)
+        if ret:
+            rec["planted_key_retention"] = ret
     if full and args.layers > 0:
         rec["layer_batched"] = layer_batched_leg(cfg, binding, chunks, dev, args.impl, args.layers,
                                                  max(4, min(steps, 2000 // args.layers)))
@@ -388,6 +438,8 @@ def main():
         "roofline": rec["roofline"], "evict_roofline": rec["evict_roofline"], "kernels": rec["kernels"],
         "step_latency_us": rec.get("step_latency_us"), "decode": rec["decode"],
     }
+    if "planted_key_retention" in rec:
+        result["planted_key_retention"] = rec["planted_key_retention"]
     if "layer_batched" in rec:
         result["layer_batched"] = rec["layer_batched"]
     if not args.no_cpu:
@@ -400,6 +452,8 @@ def main():
         sub = {"tokens_per_s": r["value"], "us_per_step": round(1e3 * r["ms_per_step"], 3), "steps": r["steps"],
                "dtype": r["dtype"], "workload": r["config"]["workload"], "roofline": r["roofline"],
                "evict_roofline": r["evict_roofline"], "kernels": r["kernels"], "decode": r["decode"]}
+        if "planted_key_retention" in r:
+            sub["planted_key_retention"] = r["planted_key_retention"]
         if not args.no_cpu:
             sub["cpu_baseline"] = cpu_baseline(sc, budget_seconds=3.0, policy=args.policy, rope_base=args.rope, max_steps=16)
         subs[name] = sub

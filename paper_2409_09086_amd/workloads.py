@@ -123,9 +123,11 @@ class ChunkStream:
             tk = cfg.sigma * _normal(rng, (extra, cfg.kv_heads, cfg.head_dim))
             tv = cfg.sigma * _normal(rng, (extra, cfg.kv_heads, cfg.head_dim))
             q, k, v = np.concatenate([q, tq]), np.concatenate([k, tk]), np.concatenate([v, tv])
+        planted = np.zeros(L, dtype=bool)                   # tokens whose key was planted (offset or bank)
         if cfg.heavy_frac:
             heavy = rng.random(L) < cfg.heavy_frac          # per token, shared by all heads
             k = k + np.float32(cfg.heavy_offset) * heavy[:, None, None].astype(np.float32)
+            planted |= heavy
         if cfg.recur_period:
             pos = self.tokens + np.arange(L)
             off = pos % cfg.recur_period
@@ -133,6 +135,8 @@ class ChunkStream:
             if hit.any():
                 k = k.copy()
                 k[hit] = self._bank[off[hit]]
+                planted |= hit
+        self.last_planted = planted                         # for whoever wants to report what became of them
         self.step += 1
         self.tokens += L
         dt = cfg.torch_dtype
