@@ -185,6 +185,18 @@ int infmllm_step(infmllm_stream_t* s, const void* q, const void* k, const void* 
 int infmllm_decode(infmllm_stream_t* s, const void* q, const void* k, const void* v, void* out);
 
 /*
+ * n_tokens decoding steps (Sec. 3.2, last paragraph) enqueued by one call, for callers whose per-call host
+ * cost would exceed a token's kernels (a drafted continuation being verified, teacher-forced decoding):
+ * token i is decoded exactly as by the i-th of n_tokens calls of infmllm_decode, so it attends the rows
+ * cached before the call and tokens 0 .. i of the call.
+ *   q      device, [n_tokens, heads, head_dim];  k, v  device, [n_tokens, kv_heads, head_dim];  read-only
+ *   out    device, [n_tokens, heads, head_dim], written
+ * Errors: EINVAL (null pointer, n_tokens < 1), ECAPACITY (the cache would exceed budget + max_decode
+ * rows: nothing is enqueued), ESTATE (not attached), EHIP.
+ */
+int infmllm_decode_n(infmllm_stream_t* s, const void* q, const void* k, const void* v, void* out, int n_tokens);
+
+/*
  * Layer-batched eviction (Alg. 1, note under "Input": the method treats the caches of all
  * layers at once).  A model's layers attend one after the other, but their evictions do not
  * depend on each other, so they can share launches:

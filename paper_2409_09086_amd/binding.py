@@ -22,7 +22,7 @@ EXPORTS = [
     "infmllm_stream_attach", "infmllm_step", "infmllm_stream_len", "infmllm_stream_streamed",
     "infmllm_stream_positions", "infmllm_stream_export", "infmllm_stream_import",
     "infmllm_stream_last_scores", "infmllm_last_error", "infmllm_stream_destroy",
-    "infmllm_stream_profile", "infmllm_stream_profile_read", "infmllm_decode", "infmllm_stream_max_len",
+    "infmllm_stream_profile", "infmllm_stream_profile_read", "infmllm_decode", "infmllm_decode_n", "infmllm_stream_max_len",
     "infmllm_step_attend", "infmllm_stream_pending", "infmllm_evict_batched", "infmllm_stream_profile_select",
     "infmllm_stream_attach_static",
 ]
@@ -54,6 +54,7 @@ def lib():
         L.infmllm_stream_attach_static.argtypes = [P, P]
         L.infmllm_step.argtypes = [P, P, P, P, I, P, P, P]
         L.infmllm_decode.argtypes = [P, P, P, P, P]
+        L.infmllm_decode_n.argtypes = [P, P, P, P, P, ctypes.c_int]
         L.infmllm_step_attend.argtypes = [P, P, P, P, I, P, P, P]
         L.infmllm_stream_pending.argtypes = [P]
         L.infmllm_evict_batched.argtypes = [ctypes.POINTER(P), I, ctypes.POINTER(P), ctypes.POINTER(P)]
@@ -205,6 +206,18 @@ class Stream:
             out = torch.empty_like(q)
         _check(lib().infmllm_decode(self._h, _dev_ptr(q), _dev_ptr(k), _dev_ptr(v),
                                     _dev_ptr(out, self.dtype, q.shape, "out")))
+        return out
+
+    def decode_n(self, q, k, v, out=None):
+        """infmllm_decode_n: q [n,heads,d], k/v [n,kv_heads,d], one decoding step per row.  Returns out [n,heads,d]."""
+        n = q.shape[0]
+        _dev_ptr(q, self.dtype, (n, self.heads, self.head_dim), "q")
+        _dev_ptr(k, self.dtype, (n, self.kv_heads, self.head_dim), "k")
+        _dev_ptr(v, self.dtype, (n, self.kv_heads, self.head_dim), "v")
+        if out is None:
+            out = torch.empty_like(q)
+        _check(lib().infmllm_decode_n(self._h, _dev_ptr(q), _dev_ptr(k), _dev_ptr(v),
+                                      _dev_ptr(out, self.dtype, q.shape, "out"), n))
         return out
 
     def decode_ptrs(self, q, k, v, out):

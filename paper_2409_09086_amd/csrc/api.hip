@@ -575,17 +575,9 @@ int infmllm_stream_profile_read(infmllm_stream_t* s, float* ms, int* launches)
     return INFMLLM_OK;
 }
 
-int infmllm_decode(infmllm_stream_t* s, const void* q, const void* k, const void* v, void* out)
+// One decoding step on a stream whose state has been checked: launches, then the host-side counters.
+static int decode_one(infmllm_stream* s, const void* q, const void* k, const void* v, void* out)
 {
-    if (!s) return fail(INFMLLM_EINVAL, "decode: stream is null");
-    if (!s->attached) return fail(INFMLLM_ESTATE, "decode: stream has no workspace attached");
-    if (s->pending) return fail(INFMLLM_ESTATE, "decode: an eviction is pending on this stream");
-    if (!q || !k || !v || !out) return fail(INFMLLM_EINVAL, "decode: q, k, v and out must not be null");
-    if (s->len >= s->g.B + s->g.max_decode)
-        return fail(INFMLLM_ECAPACITY, "decode: the cache already holds budget + max_decode = %d rows",
-                    s->g.B + s->g.max_decode);
-    if (s->streamed + 1 > (int64_t)INT32_MAX)
-        return fail(INFMLLM_ECAPACITY, "decode: stream positions would exceed 2^31-1");
     s->mark(INFMLLM_K_DECODE, 0);
     hipError_t e;
     if (s->rope_base > 0.0) {
@@ -611,6 +603,32 @@ int infmllm_decode(infmllm_stream_t* s, const void* q, const void* k, const void
     s->last_cnd = 0;
     if (s->prof_steps < s->prof_cap) ++s->prof_steps;
     return INFMLLM_OK;
+}
+
+int infmllm_decode_n(infmllm_stream_t* s, const void* q, const void* k, const void* v, void* out, int n_tokens)
+{
+    if (!s) return fail(INFMLLM_EINVAL, "decode: stream is null");
+    if (!s->attached) return fail(INFMLLM_ESTATE, "decode: stream has no workspace attached");
+    if (s->pending) return fail(INFMLLM_ESTATE, "decode: an eviction is pending on this stream");
+    if (!q || !k || !v || !out) return fail(INFMLLM_EINVAL, "decode: q, k, v and out must not be null");
+    if (n_tokens < 1) return fail(INFMLLM_EINVAL, "decode: n_tokens must be positive (got %d)", n_tokens);
+    if ((int64_t)s->len + n_tokens > (int64_t)s->g.B + s->g.max_decode)
+        return fail(INFMLLM_ECAPACITY, "decode: %d cached rows + %d tokens exceed budget + max_decode = %d rows", s->len,
+                    n_tokens, s->g.B + s->g.max_decode);
+    if (s->streamed + n_tokens > (int64_t)INT32_MAX)
+        return fail(INFMLLM_ECAPACITY, "decode: stream positions would exceed 2^31-1");
+    const size_t qrow = (size_t)s->g.Hq * s->g.d * s->g.elt, krow = (size_t)s->g.Hkv * s->g.d * s->g.elt;
+    for (int i = 0; i < n_tokens; ++i) {
+        const int rc = decode_one(s, (const char*)q + i * qrow, (const char*)k + i * krow, (const char*)v + i * krow,
+                                  (char*)out + i * qrow);
+        if (rc != INFMLLM_OK) return rc;
+    }
+    return INFMLLM_OK;
+}
+
+int infmllm_decode(infmllm_stream_t* s, const void* q, const void* k, const void* v, void* out)
+{
+    return infmllm_decode_n(s, q, k, v, out, 1);
 }
 
 int infmllm_stream_len(const infmllm_stream_t* s) { return s ? s->len : -1; }

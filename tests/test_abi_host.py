@@ -107,6 +107,8 @@ def test_optional_modes_are_checked_and_sized_on_the_host():
     # calls that need an attached stream are refused on the host
     one = ctypes.c_void_p(256)
     assert L.infmllm_decode(h, one, one, one, one) == B.ESTATE
+    assert L.infmllm_decode_n(h, one, one, one, one, 3) == B.ESTATE
+    assert L.infmllm_decode_n(None, one, one, one, one, 3) == B.EINVAL
     assert L.infmllm_step_attend(h, one, one, one, 4, one, None, None) == B.ESTATE
     assert L.infmllm_stream_pending(h) == 0 and L.infmllm_stream_pending(None) == -1
     arr = (ctypes.c_void_p * 1)(h)

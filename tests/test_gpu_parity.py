@@ -11,7 +11,7 @@ import torch
 from oracle import OracleStream
 from paper_2409_09086_amd import binding as B
 from paper_2409_09086_amd.workloads import CONFIGS, ChunkStream, random_chunk
-from _parity import LockStep
+from _parity import LockStep, OUT_TOL
 
 pytestmark = pytest.mark.gpu
 DT = {"fp32": torch.float32, "bf16": torch.bfloat16}
@@ -345,6 +345,38 @@ def test_decode_at_full_shape_cfg2():
     ls.step(*next(stream), check_state=True)
     assert len(ls.gpu) == cfg.budget
     print("decode cfg2: max err %.3g swaps %d" % (ls.max_err, ls.swaps), flush=True)
+
+
+@pytest.mark.parametrize("heads,kv,d,dtype", [(8, 2, 128, "bf16"), (4, 2, 64, "fp32")])
+def test_decode_n_equals_token_by_token(heads, kv, d, dtype):
+    """infmllm_decode_n enqueues n decoding steps from one call: outputs against the oracle token by token, and the
+    outputs and the cache bit for bit against a twin stream that calls infmllm_decode once per token."""
+    budget, recent, L, nd = 192, 48, 64, 12
+    ls = pair(budget, recent, heads, kv, d, dtype, 1e-3, max_chunk=L, max_decode=nd)
+    twin = B.Stream(budget, recent, heads, kv, d, dtype=ls.gpu.dtype, bias=1e-3, max_chunk=L, max_decode=nd)
+    for rnd in range(4):
+        q, k, v = random_chunk(520 + rnd, L, heads, kv, d, dtype)
+        ls.step(q, k, v, check_state=True)
+        twin.step(q.cuda(), k.cuda(), v.cuda())
+        n = (nd, 1, 5, nd)[rnd]
+        qn, kn, vn = random_chunk(620 + rnd, n, heads, kv, d, dtype)
+        out_n = ls.gpu.decode_n(qn.cuda(), kn.cuda(), vn.cuda())
+        for i in range(n):
+            out_o = ls.oracle.decode(qn[i:i + 1].double().numpy(), kn[i:i + 1].double().numpy(), vn[i:i + 1].double().numpy())
+            err = float(np.abs(out_n[i:i + 1].double().cpu().numpy() - out_o).max())
+            assert err <= OUT_TOL[ls.gpu.dtype], "token %d of decode_n off by %g" % (i, err)
+            out_1 = twin.decode(qn[i:i + 1].cuda().contiguous(), kn[i:i + 1].cuda().contiguous(), vn[i:i + 1].cuda().contiguous())
+            assert torch.equal(out_1.view(torch.int32 if dtype == "fp32" else torch.int16),
+                               out_n[i:i + 1].view(torch.int32 if dtype == "fp32" else torch.int16))
+        ls.check_state()
+        for a, b in zip(ls.gpu.export(), twin.export()):
+            assert torch.equal(a, b) or torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a, b.view(torch.int32) if b.dtype == torch.float32 else b)
+    qn, kn, vn = [x.cuda() for x in random_chunk(2, nd + 1, heads, kv, d, dtype)]
+    ls.step(*random_chunk(530, L, heads, kv, d, dtype))
+    before = len(ls.gpu)
+    with pytest.raises(B.InfMLLMError) as e:                     # one token too many: nothing is enqueued
+        ls.gpu.decode_n(qn, kn, vn)
+    assert e.value.code == B.ECAPACITY and len(ls.gpu) == before
 
 
 def test_decode_without_max_decode_is_refused():
