@@ -376,10 +376,10 @@ attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, 
 // A column is a physical cache row (col < tc; its stream-order index j is rank[col]) or a chunk row
 // (col >= tc, j = col).  Columns 0 .. ncol-1 are swept, ncol = max(tc, cnd): any cached row may be a
 // candidate; W' is written at index j, for the columns with j < cnd.
-// Workgroup = 8 wavefronts: 4 column groups (32*CB key columns each, held in registers) x 2 row
-// groups that take alternate 32-row query blocks and add their partial column sums through LDS
-// at the end.  Query blocks are double-buffered in LDS.  Every scored row sees every candidate
-// column, so there is no mask inside the block.
+// Workgroup = 8 wavefronts = 8 column groups of 32*CB key columns each, held in registers as MFMA
+// operands; every wavefront takes all four 32-row query blocks of an iteration, which are staged once
+// per workgroup (double-buffered in LDS) and so serve 256*CB columns.  Every scored row sees every
+// candidate column, so there is no mask inside the block.
 // ---------------------------------------------------------------------------------------------
 template <int D, int CB>
 __global__ void __launch_bounds__(512)
@@ -396,15 +396,13 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
     constexpr int BUF = QBYTES + TROWS * 4;                   // rows + their log-sum-exp
     constexpr int LSE_ROWS = 4096;                            // scored rows whose log-sum-exp is kept in LDS
     __shared__ __attribute__((aligned(16))) char smem[2 * BUF];
-    __shared__ float s_part[4 * CB * 32];
     __shared__ float s_lse[LSE_ROWS];
     __shared__ int s_ticket;
 
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: what depends on it stays scalar
-    // column group, row group: wavefronts 2k and 2k + 1 share the columns and take a row group each (measured
-    // 4 % faster than pairing k with k + 4)
-    const int cg = wave >> 1, rg = wave & 1;
+    const int cg = wave;                                      // column group
+    const int late = wave & 1;                                // odd wavefronts weigh their last block an iteration late
     // all column blocks of a kv-head get workgroup ids of one residue class mod 8, i.e. one XCD,
     // so that the head's scored queries are fetched into one L2 only
     // With rsplit > 1 the scored rows of a column block are shared out over rsplit workgroups (slice rs).
@@ -423,7 +421,7 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
         bx = rem % nxb;
         rs = rem / nxb;
     }
-    const int col0 = bx * (128 * CB) + cg * (32 * CB);
+    const int col0 = bx * (256 * CB) + cg * (32 * CB);
 
     f32x16 part[CB];
 #pragma unroll
@@ -510,29 +508,21 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
         if (tid < TROWS) *(float*)(base + QBYTES + tid * 4) = (stl_idx >= 0) ? s_lse[stl_idx] : stl;
     };
     if (niter > 0) fetch(true);
-    // Key fragments: B operand of S = Q.K^T, lane (column l32, half hh) holds K[col][16s + 8hh .. +8).
-    // Loaded in that layout straight from memory a wavefront touches 32 rows with every instruction; the
-    // workgroup's 128*CB key rows are therefore read once with whole-row (coalesced) loads into an LDS
-    // region of their own and the fragments are picked up from there, behind the same barrier that
-    // publishes the first query blocks.
-    constexpr int KROWS = 128 * CB, KLD = KROWS * CPR / 512;
-    __shared__ __attribute__((aligned(16))) char ktile[KROWS * QP];
-    {
-        u32x4 kt[KLD];
+    // Key fragments: B operand of S = Q.K^T, lane (column l32, half hh) holds K[col][16s + 8hh .. +8), loaded in
+    // that layout straight from memory (a wavefront's load touches 32 rows, 32 bytes of each; the four loads
+    // that share a row's 128-byte line follow one another).  A column past the last one is all zeros.
+    bf16x8 kf[CB][D / 16];
 #pragma unroll
-        for (int u = 0; u < KLD; ++u) {
-            const int ch = tid + u * 512, r = ch / CPR;
-            const int col = bx * KROWS + r;
-            const bool ok = col < ncol;
-            const int cc = ok ? col : 0;
-            const uint16_t* kp = (cc < tc ? K + ((size_t)h * cap + cc) * D : kc + ((size_t)(cc - tc) * Hkv + h) * D) + (ch % CPR) * 8;
-            kt[u] = *(const u32x4*)kp;
-            if (!ok) kt[u] = u32x4{0u, 0u, 0u, 0u};
-        }
+    for (int cb = 0; cb < CB; ++cb) {
+        const int col = col0 + 32 * cb + l32;
+        const bool ok = col < ncol;
+        const int cc = ok ? col : 0;
+        const uint16_t* kp = (cc < tc ? K + ((size_t)h * cap + cc) * D : kc + ((size_t)(cc - tc) * Hkv + h) * D) + 8 * hh;
 #pragma unroll
-        for (int u = 0; u < KLD; ++u) {
-            const int ch = tid + u * 512;
-            *(u32x4*)(ktile + (ch / CPR) * QP + (ch % CPR) * 16) = kt[u];
+        for (int s = 0; s < D / 16; ++s) {
+            u32x4 v = *(const u32x4*)(kp + 16 * s);
+            if (!ok) v = u32x4{0u, 0u, 0u, 0u};
+            kf[cb][s] = as_bf16x8(v);
         }
     }
     if (lse_in_lds) {
@@ -546,28 +536,21 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
         stash(0);
         if (niter > 1) fetch(true);
     }
-    __syncthreads();                                          // key tile, first query blocks and s_lse are complete
-    bf16x8 kf[CB][D / 16];
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb) {
-        const char* kp = ktile + (cg * 32 * CB + 32 * cb + l32) * QP + 16 * hh;
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) kf[cb][s] = as_bf16x8(*(const u32x4*)(kp + 32 * s));
-    }
-    // A row group takes two of the four blocks of an iteration: each is formed (8*CB MFMAs) and then weighed
-    // (exp2 of every logit).  The two wavefronts of a SIMD (row groups 0 and 1 of one column group) leave the
-    // barrier together; if both formed and weighed in the same order they would queue for the matrix pipe and
-    // then for the vector unit.  Row group 1 therefore weighs its second block one
-    // iteration late, at the head of the next iteration, while row group 0 forms its first block, and from
-    // then on one wavefront of the SIMD is in its MFMAs while the other is in its exponentials.
+    __syncthreads();                                          // first query blocks and s_lse are complete
+    // Each of the four blocks of an iteration is formed (8*CB MFMAs) and then weighed (exp2 of every logit)
+    // through one set of accumulators.  Wavefronts leave the barrier together; if all formed and weighed in
+    // the same order, the two that share a SIMD would queue for the matrix pipe and then for the vector unit.
+    // Odd wavefronts therefore weigh their fourth block one iteration late, at the head of the next iteration,
+    // while the even ones form their first, and from then on one is in its MFMAs while the other is in its
+    // exponentials.
     auto load_q = [&](const char* base, int k, bf16x8 (&qf)[D / 16]) {
-        const char* qp = base + (64 * rg + 32 * k + l32) * QP + 16 * hh;
+        const char* qp = base + (32 * k + l32) * QP + 16 * hh;
 #pragma unroll
         for (int s = 0; s < D / 16; ++s) qf[s] = as_bf16x8(*(const u32x4*)(qp + 32 * s));
     };
     // lane (column, half hh) holds rows 8a + 4hh + e of a block in register 4a + e
     auto load_ls = [&](const char* base, int k, f32x4 (&ls)[4]) {
-        const float* lp = (const float*)(base + QBYTES) + 64 * rg + 32 * k;
+        const float* lp = (const float*)(base + QBYTES) + 32 * k;
 #pragma unroll
         for (int a = 0; a < 4; ++a) ls[a] = *(const f32x4*)(lp + 8 * a + 4 * hh);
     };
@@ -591,39 +574,37 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
                 for (int cb = 0; cb < CB; ++cb)
                     part[cb][4 * a + e] += fast_exp2(__builtin_fmaf(acc[cb][4 * a + e], c, -ls[a][e]));
     };
-    f32x16 acc[CB];                                           // row group 1 carries its second block over the barrier
+    f32x16 acc[CB];                                           // odd wavefronts carry their fourth block over the barrier
     f32x4 pls[4];                                             // ... with the log-sum-exps of its rows
     for (int it = 0; it < niter; ++it) {
         const char* base = smem + (it & 1) * BUF;
         bf16x8 qf[D / 16];
         f32x4 ls[4];
         load_q(base, 0, qf);
-        if (rg == 1 && it > 0) {
+        if (late && it > 0) {
             weigh(acc, pls);
             __builtin_amdgcn_sched_barrier(0);
         }
-        form(qf, acc);
-        __builtin_amdgcn_sched_barrier(0);
-        load_q(base, 1, qf);
-        load_ls(base, 0, ls);
-        weigh(acc, ls);
-        __builtin_amdgcn_sched_barrier(0);
-        form(qf, acc);
-        __builtin_amdgcn_sched_barrier(0);
-        if (rg == 0) {
-            load_ls(base, 1, ls);
-            weigh(acc, ls);
-        } else {
-            load_ls(base, 1, pls);                            // taken now: the buffer is rewritten before they are used
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            form(qf, acc);
+            __builtin_amdgcn_sched_barrier(0);
+            if (k < 3) load_q(base, k + 1, qf);
+            if (k < 3 || !late) {
+                load_ls(base, k, ls);
+                weigh(acc, ls);
+            } else {
+                load_ls(base, k, pls);                        // taken now: the buffer is rewritten before they are used
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
         // the other buffer was last read one iteration ago, before the barrier that ended it
         if (it + 1 < niter) stash((it + 1) & 1);
         if (it + 2 < niter) fetch();
         __syncthreads();
     }
-    if (rg == 1 && niter > 0) weigh(acc, pls);
-    // column sums: 16 registers, the two half-waves, then the two row groups (fixed order)
+    if (late && niter > 0) weigh(acc, pls);
+    // column sums: 16 registers, then the two half-waves (fixed order)
     float sum[CB];
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
@@ -631,20 +612,17 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
 #pragma unroll
         for (int a = 0; a < 4; ++a) s0 += (part[cb][4 * a] + part[cb][4 * a + 1]) + (part[cb][4 * a + 2] + part[cb][4 * a + 3]);
         sum[cb] = s0 + xhalf(s0);
-        if (rg == 1 && hh == 0) s_part[(cg * CB + cb) * 32 + l32] = sum[cb];
     }
-    __syncthreads();
     // Row-split launch: every workgroup puts its raw column sums where the other slices' workgroups can read
     // them (agent-scope stores go through to memory), waits until they have left, and takes a ticket; the one
     // that arrives last adds the slices up and finishes the columns.  No workgroup waits for another one.
     float* my_part = nullptr;
     if (rsplit > 1) {
-        my_part = spart + ((size_t)(h * rsplit + rs) * nxb + bx) * 256;
-        if (rg == 0 && hh == 0) {
+        my_part = spart + ((size_t)(h * rsplit + rs) * nxb + bx) * (256 * CB);
+        if (hh == 0) {
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
-                __hip_atomic_store(my_part + cg * 32 * CB + 32 * cb + l32, sum[cb] + s_part[(cg * CB + cb) * 32 + l32],
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(my_part + cg * 32 * CB + 32 * cb + l32, sum[cb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         int* arrived = (int*)(spart + (size_t)SCORE_SPLIT_WGS * 256) + h * nxb + bx;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -654,19 +632,19 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
         if (s_ticket != rsplit - 1) return;
         if (tid == 0) __hip_atomic_store(arrived, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
     }
-    if (rg == 0 && hh == 0) {
+    if (hh == 0) {
         const float norm = (lq > 0) ? 1.0f / (float)(G * lq) : 0.f;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
             const int col = col0 + 32 * cb + l32;
             const int j = col < tc ? (col < ncol ? rank[(size_t)h * cap + col] : cnd) : col;   // stream-order index
             if (j < cnd) {
-                float tot = sum[cb] + s_part[(cg * CB + cb) * 32 + l32];
+                float tot = sum[cb];
                 if (rsplit > 1) {
                     // fixed order over the slices, whichever workgroup does the adding
                     tot = 0.f;
                     for (int sp = 0; sp < rsplit; ++sp)
-                        tot += __hip_atomic_load(my_part + (sp - rs) * nxb * 256 + cg * 32 * CB + 32 * cb + l32,
+                        tot += __hip_atomic_load(my_part + (sp - rs) * nxb * (256 * CB) + cg * 32 * CB + 32 * cb + l32,
                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
                 float w = tot * norm - (float)(cnd - 1 - j) * dstep;                       // Alg. 1 l.1, l.3-4
@@ -730,21 +708,23 @@ hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySou
     if (cnd <= 0) return hipSuccess;
     const int ncol = ks.rows > cnd ? ks.rows : cnd;          // every cached row, and the chunk rows below cnd
     const float cc = (float)(g.scale * (double)LOG2E);
-    // 256 columns per workgroup.  Where that leaves CUs without one, the scored rows of a column block are
-    // shared out over up to four workgroups (whose sums the last to finish adds up); where there are too few
-    // rows for that, a workgroup takes 128 columns.
-    const int nx256 = (ncol + 255) / 256;
-    const long wgs256 = (long)nx256 * g.Hkv;
+    // 512 columns per workgroup (256 at head_dim 64, where the wider variant runs out of registers).  Where
+    // that leaves CUs without one, the scored rows of a column block are shared out over up to four workgroups
+    // (whose sums the last to finish adds up); where there are too few rows for that, a workgroup takes 256 columns.
+    const int wcols = g.d == 128 ? 512 : 256;
+    const int nxw = (ncol + wcols - 1) / wcols;
+    const long wgsw = (long)nxw * g.Hkv;
     const int niter = (g.G * ((lq + 31) / 32) + 3) / 4;       // iterations of the kernel's row loop
+    const long wgs256 = (long)((ncol + 255) / 256) * g.Hkv;
     int rsplit = 1;
-    if (wgs256 < 200) {
-        rsplit = (int)(256 / wgs256);
+    if (wgsw < 200 && wgs256 < 200) {
+        rsplit = (int)(256 / wgsw);
         if (rsplit > 4) rsplit = 4;
         if (rsplit > niter / 2) rsplit = niter / 2;
-        if (rsplit < 1 || !sc.score_part || wgs256 * rsplit > SCORE_SPLIT_WGS) rsplit = 1;
+        if (rsplit < 1 || !sc.score_part || wgsw * rsplit * (wcols / 256) > SCORE_SPLIT_WGS) rsplit = 1;
     }
-    const bool wide = wgs256 >= 200 || rsplit > 1;
-    const int nxb = wide ? nx256 : (ncol + 127) / 128;
+    const bool wide = wgsw >= 200 || rsplit > 1;
+    const int nxb = wide ? nxw : (ncol + 255) / 256;
     const dim3 grid(nxb * g.Hkv * rsplit), block(512);
 #define INFMLLM_SCORE(DD, CB)                                                                              \
     hipLaunchKernelGGL((score_kernel<DD, CB>), grid, block, 0, st, (const uint16_t*)q, (const uint16_t*)c.K, \
@@ -754,7 +734,6 @@ hipError_t launch_score_mfma(const Geometry& g, const CacheView& c, const KeySou
                        cnd, ncol, nxb, cc, (float)(g.bias / (double)cnd), rsplit, sc.score_part)
     if (g.d == 128 && wide) INFMLLM_SCORE(128, 2);
     else if (g.d == 128) INFMLLM_SCORE(128, 1);
-    else if (g.d == 64 && wide) INFMLLM_SCORE(64, 2);
     else if (g.d == 64) INFMLLM_SCORE(64, 1);
     else return hipErrorInvalidValue;
 #undef INFMLLM_SCORE
