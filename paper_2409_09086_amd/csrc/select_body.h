@@ -103,9 +103,34 @@ struct PlanTables {
 // empty) is free.  There are exactly as many movers as free rows, and the k-th mover is paired with the k-th
 // free row, both in ascending order, which makes the layout a function of the retained set alone.  The K/V
 // copies and the movers' table entries are left to the placement launch.
+// What the plan reads from memory does not depend on the selection: the stream-order index of every physical
+// row and the score W' of that index.  The first PLAN_PRE items of every thread are therefore requested before
+// the selection starts and have long arrived when the plan wants them; a plan with more items (more than
+// PLAN_PRE * 1024 rows) loads the rest pass by pass.
+constexpr int PLAN_PRE = 12;
+struct PlanPre {
+    int jj[PLAN_PRE];
+    float w[PLAN_PRE];
+};
+// item q of the plan: a physical row below max(tc, B), then the chunk rows read in place; its token, or -1
+__device__ __forceinline__ int plan_item_token(const int32_t* __restrict__ rank, int q, int tc, int P1, int nitems)
+{
+    return q < tc ? rank[q] : (q >= P1 && q < nitems ? tc + (q - P1) : -1);
+}
+template <int TPB>
+__device__ __forceinline__ void plan_prefetch(PlanPre& pre, const int32_t* __restrict__ rank, const float* __restrict__ W,
+                                              int n, int tc, int cnd, int B)
+{
+    const int P1 = tc > B ? tc : B, nitems = P1 + (n - tc);
+#pragma unroll
+    for (int g = 0; g < PLAN_PRE; ++g) pre.jj[g] = plan_item_token(rank, g * TPB + (int)threadIdx.x, tc, P1, nitems);
+#pragma unroll
+    for (int g = 0; g < PLAN_PRE; ++g) pre.w[g] = (pre.jj[g] >= 0 && pre.jj[g] < cnd) ? W[pre.jj[g]] : __builtin_inff();
+}
+
 template <int TPB>
 __device__ __forceinline__ void plan_moves(const KeptMap& km, const float* __restrict__ W, int n, int tc, int cnd,
-                                           int B, int r, const PlanTables& pt)
+                                           int B, int r, const PlanTables& pt, const PlanPre& pre)
 {
     constexpr int NW = TPB / 64, CH = 64 / NW;                 // CH passes of TPB items share one table of 64 counts
     __shared__ uint32_t cnt_free[64], cnt_mov[64];
@@ -123,19 +148,15 @@ __device__ __forceinline__ void plan_moves(const KeptMap& km, const float* __res
     };
     uint32_t fbase = 0, mbase = 0;                            // free rows / movers listed so far (uniform)
     __syncthreads();                                          // the kept map is complete
-    for (int q0 = 0; q0 < nitems; q0 += CH * TPB) {
-        int jj[CH], xs[CH], src[CH];
+    static_assert(PLAN_PRE % CH == 0, "prefetched items are consumed in whole passes");
+    auto pass = [&](int q0, const int (&jj)[CH], const float (&wv)[CH]) {
+        int xs[CH], src[CH];
         uint64_t bfree[CH], bmov[CH];
-#pragma unroll
-        for (int u = 0; u < CH; ++u) {                        // every table load of the pass before any is used
-            const int q = q0 + u * TPB + tid;
-            jj[u] = q < tc ? pt.rank[q] : (q >= P1 && q < nitems ? tc + (q - P1) : -1);
-        }
         float sc[CH];
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
             xs[u] = jj[u] >= 0 ? new_index(jj[u]) : -1;
-            sc[u] = (xs[u] >= 0 && xs[u] < r) ? W[jj[u]] : __builtin_inff();
+            sc[u] = (xs[u] >= 0 && xs[u] < r) ? wv[u] : __builtin_inff();
         }
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
@@ -182,6 +203,25 @@ __device__ __forceinline__ void plan_moves(const KeptMap& km, const float* __res
         fbase += tot_free;
         mbase += tot_mov;
         __syncthreads();                                      // the count tables are rewritten by the next pass
+    };
+#pragma unroll
+    for (int p = 0; p < PLAN_PRE / CH; ++p) {                 // the passes whose loads were requested up front
+        if (p * CH * TPB < nitems) {
+            int jj[CH];
+            float wv[CH];
+#pragma unroll
+            for (int u = 0; u < CH; ++u) { jj[u] = pre.jj[p * CH + u]; wv[u] = pre.w[p * CH + u]; }
+            pass(p * CH * TPB, jj, wv);
+        }
+    }
+    for (int q0 = PLAN_PRE * TPB; q0 < nitems; q0 += CH * TPB) {
+        int jj[CH];
+        float wv[CH];
+#pragma unroll
+        for (int u = 0; u < CH; ++u) jj[u] = plan_item_token(pt.rank, q0 + u * TPB + tid, tc, P1, nitems);
+#pragma unroll
+        for (int u = 0; u < CH; ++u) wv[u] = (jj[u] >= 0 && jj[u] < cnd) ? W[jj[u]] : __builtin_inff();
+        pass(q0, jj, wv);
     }
     if (tid == 0) *pt.mv_count = (int32_t)mbase;               // = fbase: B tokens are retained, B rows lie below B
 }

@@ -143,11 +143,13 @@ select_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __
 {
     __shared__ KeptMap km;
     const int h = blockIdx.x;
-    select_body<KPT>(Wb, I, userI, user_count, h, cnd, r, R, B, cap, km);
     const size_t hb = (size_t)h * cap, mb = (size_t)h * mv.max;
+    PlanPre pre;
+    plan_prefetch<TPB>(pre, c.rank + hb, Wb + hb, cnd + R, tc, cnd, B);
+    select_body<KPT>(Wb, I, userI, user_count, h, cnd, r, R, B, cap, km);
     const PlanTables pt{c.rank + hb, c.row + hb, c.score + hb, mv.src + mb, mv.dst + mb, mv.x + mb, mv.score + mb,
                         mv.count + h};
-    plan_moves<TPB>(km, Wb + hb, cnd + R, tc, cnd, B, r, pt);
+    plan_moves<TPB>(km, Wb + hb, cnd + R, tc, cnd, B, r, pt, pre);
 }
 
 // Several streams of one geometry (the layers of a model, Alg. 1 Input note): stream j owns
@@ -160,11 +162,13 @@ select_batch_kernel(EvictBatch eb, int r, int R, int B, int cap, int Hkv)
     const EvictJob& job = eb.job[j];
     __shared__ KeptMap km;
     const int cnd = job.n - R;
-    select_body<KPT>(job.Wb, job.I, job.user_I, job.user_count, h, cnd, r, R, B, cap, km);
     const size_t hb = (size_t)h * cap, mb = (size_t)h * job.mv.max;
+    PlanPre pre;
+    plan_prefetch<TPB>(pre, job.c.rank + hb, job.Wb + hb, job.n, job.tc, cnd, B);
+    select_body<KPT>(job.Wb, job.I, job.user_I, job.user_count, h, cnd, r, R, B, cap, km);
     const PlanTables pt{job.c.rank + hb, job.c.row + hb, job.c.score + hb, job.mv.src + mb, job.mv.dst + mb,
                         job.mv.x + mb, job.mv.score + mb, job.mv.count + h};
-    plan_moves<TPB>(km, job.Wb + hb, job.n, job.tc, cnd, B, r, pt);
+    plan_moves<TPB>(km, job.Wb + hb, job.n, job.tc, cnd, B, r, pt, pre);
 }
 
 }  // namespace
