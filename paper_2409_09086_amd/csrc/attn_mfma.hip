@@ -402,7 +402,6 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: what depends on it stays scalar
     const int cg = wave;                                      // column group
-    const int late = wave & 1;                                // odd wavefronts weigh their last block an iteration late
     // all column blocks of a kv-head get workgroup ids of one residue class mod 8, i.e. one XCD,
     // so that the head's scored queries are fetched into one L2 only
     // With rsplit > 1 the scored rows of a column block are shared out over rsplit workgroups (slice rs).
@@ -537,73 +536,88 @@ score_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, con
         if (niter > 1) fetch(true);
     }
     __syncthreads();                                          // first query blocks and s_lse are complete
-    // Each of the four blocks of an iteration is formed (8*CB MFMAs) and then weighed (exp2 of every logit)
-    // through one set of accumulators.  Wavefronts leave the barrier together; if all formed and weighed in
-    // the same order, the two that share a SIMD would queue for the matrix pipe and then for the vector unit.
-    // Odd wavefronts therefore weigh their fourth block one iteration late, at the head of the next iteration,
-    // while the even ones form their first, and from then on one is in its MFMAs while the other is in its
-    // exponentials.
-    auto load_q = [&](const char* base, int k, bf16x8 (&qf)[D / 16]) {
-        const char* qp = base + (32 * k + l32) * QP + 16 * hh;
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) qf[s] = as_bf16x8(*(const u32x4*)(qp + 32 * s));
+    // Software pipeline over units of one 32-row block x one 32-column block (8 MFMAs at head_dim 128): while
+    // the MFMAs of a unit are issued, the 16 logits of the unit before (in the other accumulator) are weighed,
+    // two per MFMA slot: exp2(s c - lse) added to the column sums.  The slots are fenced so that the compiler
+    // keeps them as written; the wavefront then always has vector work beside its MFMAs, and the two wavefronts
+    // of a SIMD fill each other's gaps.  The query fragments of a block serve its CB units; each is replaced
+    // by the next block's right after its last MFMA, eight slots before it is needed again.  The last unit of an
+    // iteration is weighed beside the first of the next one (the log-sum-exps of its rows are in registers
+    // before the barrier lets the buffer be rewritten), the very last one after the loop.
+    constexpr int NS = D / 16;                                // MFMAs per unit
+    static_assert(16 % NS == 0, "the logits of a unit are spread evenly over the slots of the next");
+    constexpr int LPS = 16 / NS;                              // logits weighed per slot
+    f32x16 accA, accB;
+    f32x4 ls[4];                                              // log-sum-exps of the rows of the unit being weighed
+    bf16x8 qf[NS];
+    auto read_q = [&](const char* base, int k, int s) -> bf16x8 {
+        return as_bf16x8(*(const u32x4*)(base + (32 * k + l32) * QP + 16 * hh + 32 * s));
     };
     // lane (column, half hh) holds rows 8a + 4hh + e of a block in register 4a + e
-    auto load_ls = [&](const char* base, int k, f32x4 (&ls)[4]) {
+    auto load_ls = [&](const char* base, int k) {
         const float* lp = (const float*)(base + QBYTES) + 32 * k;
 #pragma unroll
         for (int a = 0; a < 4; ++a) ls[a] = *(const f32x4*)(lp + 8 * a + 4 * hh);
     };
-    auto form = [&](const bf16x8 (&qf)[D / 16], f32x16 (&acc)[CB]) {
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // unit (block k, column block CBI): MFMAs into `cur`, the logits of the unit before out of `prev` into the
+    // column sums of column block PCB
+    auto unit = [&](const char* base, auto K_, auto CBI_, f32x16& cur, const f32x16& prev) {
+        constexpr int k = decltype(K_)::value, cbi = decltype(CBI_)::value;
+        constexpr int pcb = (cbi + CB - 1) % CB;              // column block of the unit before
+        static_for<0, NS>([&](auto I) {
+            constexpr int sidx = decltype(I)::value;
+            cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[sidx], kf[cbi][sidx], sidx == 0 ? zero16 : cur, 0, 0, 0);
+            if constexpr (cbi == CB - 1 && k < 3) qf[sidx] = read_q(base, k + 1, sidx);
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[cb][i] = 0.f;
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s)
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
-                acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[s], kf[cb][s], acc[cb], 0, 0, 0);
-    };
-    auto weigh = [&](const f32x16 (&acc)[CB], const f32x4 (&ls)[4]) {
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
-                    part[cb][4 * a + e] += fast_exp2(__builtin_fmaf(acc[cb][4 * a + e], c, -ls[a][e]));
-    };
-    f32x16 acc[CB];                                           // odd wavefronts carry their fourth block over the barrier
-    f32x4 pls[4];                                             // ... with the log-sum-exps of its rows
-    for (int it = 0; it < niter; ++it) {
-        const char* base = smem + (it & 1) * BUF;
-        bf16x8 qf[D / 16];
-        f32x4 ls[4];
-        load_q(base, 0, qf);
-        if (late && it > 0) {
-            weigh(acc, pls);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            form(qf, acc);
-            __builtin_amdgcn_sched_barrier(0);
-            if (k < 3) load_q(base, k + 1, qf);
-            if (k < 3 || !late) {
-                load_ls(base, k, ls);
-                weigh(acc, ls);
-            } else {
-                load_ls(base, k, pls);                        // taken now: the buffer is rewritten before they are used
+            for (int x = 0; x < LPS; ++x) {
+                const int i = LPS * sidx + x;
+                part[pcb][i] += fast_exp2(__builtin_fmaf(prev[i], c, -ls[i / 4][i % 4]));
+                // the sums are not read before the end of the kernel: without a use here the compiler moves the
+                // weighing out of the slot, past the MFMAs that were to hide it
+                asm volatile("" : "+v"(part[pcb][i]));
             }
             __builtin_amdgcn_sched_barrier(0);
+        });
+        // the unit that follows weighs this one: from its last column block on, a block's rows are the next to be weighed
+        if constexpr (cbi == 0) load_ls(base, k);
+    };
+    // before the first unit there is nothing to weigh: log-sum-exps of +inf give weights of zero
+    accB = zero16;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) ls[a] = f32x4{__builtin_inff(), __builtin_inff(), __builtin_inff(), __builtin_inff()};
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+    for (int it = 0; it < niter; ++it) {
+        const char* base = smem + (it & 1) * BUF;
+#pragma unroll
+        for (int sidx = 0; sidx < NS; ++sidx) qf[sidx] = read_q(base, 0, sidx);
+        if constexpr (CB == 2) {
+            unit(base, I0{}, I0{}, accA, accB);               // beside it: the last unit of the iteration before
+            unit(base, I0{}, I1{}, accB, accA);
+            unit(base, I1{}, I0{}, accA, accB);
+            unit(base, I1{}, I1{}, accB, accA);
+            unit(base, I2{}, I0{}, accA, accB);
+            unit(base, I2{}, I1{}, accB, accA);
+            unit(base, I3{}, I0{}, accA, accB);
+            unit(base, I3{}, I1{}, accB, accA);
+        } else {
+            unit(base, I0{}, I0{}, accA, accB);
+            unit(base, I1{}, I0{}, accB, accA);
+            unit(base, I2{}, I0{}, accA, accB);
+            unit(base, I3{}, I0{}, accB, accA);
         }
         // the other buffer was last read one iteration ago, before the barrier that ended it
         if (it + 1 < niter) stash((it + 1) & 1);
         if (it + 2 < niter) fetch();
         __syncthreads();
     }
-    if (late && niter > 0) weigh(acc, pls);
+    if (niter > 0) {                                          // the last unit: block 3, column block CB - 1
+#pragma unroll
+        for (int i = 0; i < 16; ++i) part[CB - 1][i] += fast_exp2(__builtin_fmaf(accB[i], c, -ls[i / 4][i % 4]));
+    }
     // column sums: 16 registers, then the two half-waves (fixed order)
     float sum[CB];
 #pragma unroll

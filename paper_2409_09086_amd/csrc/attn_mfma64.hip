@@ -104,16 +104,6 @@ __device__ __forceinline__ uint32_t pack_bf16_after_nop(float lo, float hi)   //
 
 template <bool B> using Flag = std::integral_constant<bool, B>;
 
-// f(integral_constant<int, I0>) ... f(integral_constant<int, I1 - 1>), in order
-template <int I0, int I1, class F>
-__device__ __forceinline__ void static_for(F&& f)
-{
-    if constexpr (I0 < I1) {
-        f(std::integral_constant<int, I0>{});
-        static_for<I0 + 1, I1>(f);
-    }
-}
-
 __global__ void __launch_bounds__(w64::NT) __attribute__((amdgpu_waves_per_eu(1, 1)))
 attn_fwd64_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
                   const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc, int tc,

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace infmllm {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -18,6 +20,17 @@ constexpr float LOG2E = 1.4426950408889634f;
 // (base-2 exponent): exp2(s - ref) then stays below 2^8, well inside bf16/fp32 range, and the
 // accumulators are rescaled a handful of times per row instead of once per tile.
 constexpr float RESCALE_TAU = 8.0f;
+
+// f(integral_constant<int, I0>) ... f(integral_constant<int, I1 - 1>), in order: a loop whose index is a
+// compile-time constant inside the body
+template <int I0, int I1, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I0 < I1) {
+        f(std::integral_constant<int, I0>{});
+        static_for<I0 + 1, I1>(f);
+    }
+}
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
