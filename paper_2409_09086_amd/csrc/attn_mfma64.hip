@@ -250,22 +250,20 @@ attn_fwd64_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K
         kf[4] = lds_read_b128<O>(kaddr[4]); kf[5] = lds_read_b128<O>(kaddr[5]);
         kf[6] = lds_read_b128<O>(kaddr[6]); kf[7] = lds_read_b128<O>(kaddr[7]);
     };
-    // A V fragment arrives as two halves.  The halves stay variables of their own until the wait: a register
-    // copy that the compiler might make of them earlier would copy what the read has not delivered yet.  The
-    // wait names the first pair; the empty statements that follow it in program order name the others, so that
-    // no product that reads a fragment can be placed ahead of the wait.
-    bf16x4 vlo[8], vhi[8];
+    // A V fragment arrives as two halves, read straight into the two halves of the register quadruple the MFMA
+    // takes (a copy made between a read and the wait would copy what the read has not delivered yet; the
+    // compiler has no reason to make one, and tests/test_kernel_asm.py checks the generated code for it).  The
+    // wait names the first fragment; the empty statements that follow it in program order name the others, so
+    // that no product that reads a fragment can be placed ahead of the wait.
     auto wait_v = [&]() {
-        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(vlo[0]), "+v"(vhi[0]));
-        asm volatile("" : "+v"(vlo[1]), "+v"(vhi[1]));
-        asm volatile("" : "+v"(vlo[2]), "+v"(vhi[2]));
-        asm volatile("" : "+v"(vlo[3]), "+v"(vhi[3]));
-        asm volatile("" : "+v"(vlo[4]), "+v"(vhi[4]));
-        asm volatile("" : "+v"(vlo[5]), "+v"(vhi[5]));
-        asm volatile("" : "+v"(vlo[6]), "+v"(vhi[6]));
-        asm volatile("" : "+v"(vlo[7]), "+v"(vhi[7]));
-#pragma unroll
-        for (int i = 0; i < 8; ++i) vf[i] = __builtin_shufflevector(vlo[i], vhi[i], 0, 1, 2, 3, 4, 5, 6, 7);
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(vf[0]));
+        asm volatile("" : "+v"(vf[1]));
+        asm volatile("" : "+v"(vf[2]));
+        asm volatile("" : "+v"(vf[3]));
+        asm volatile("" : "+v"(vf[4]));
+        asm volatile("" : "+v"(vf[5]));
+        asm volatile("" : "+v"(vf[6]));
+        asm volatile("" : "+v"(vf[7]));
     };
     auto advance = [&](uint32_t (&a)[D / 16], int delta) {
 #pragma unroll
@@ -341,6 +339,10 @@ attn_fwd64_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K
         }
     };
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // (m_ref + 2^3 in the exponent) / c of block A in the lower half-wave, of block B in the upper one: what a raw
+    // logit has to exceed for the block's reference to move.  No reference yet: anything finite exceeds it.
+    const float inv_c = 1.0f / c;
+    float thr_mix = -__builtin_inff();
     // S c - m of the sub-block in its softmax stage; the second half of a period turns the entries into the
     // weights exp2(S c - m) in place, and the first half of the next period adds them to the row sums just
     // before it overwrites them (so that the additions, too, sit beside MFMAs that have time to spare)
@@ -397,9 +399,15 @@ attn_fwd64_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K
             if constexpr (i == 11) dma_step(4 * SUB + 1);
             __builtin_amdgcn_sched_barrier(0);
         });
-        const float mx0 = xhalf_max(mx[0]) * c, mx1 = xhalf_max(mx[1]) * c;
-        if (__any(mx0 > m_ref[0] + RESCALE_TAU || mx1 > m_ref[1] + RESCALE_TAU)) {
+        // One exchange between the half-waves serves both blocks: afterwards the lower half-wave holds block A's
+        // row maxima and the upper one block B's, each compared with its own block's threshold (kept in the
+        // logits' unscaled units).  Only if some row outgrew it are the maxima formed in every lane.
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx[0]), __float_as_uint(mx[1]), false, false);
+        float mmix;
+        asm("v_max_f32 %0, %1, %2" : "=v"(mmix) : "v"(__uint_as_float(sw[0])), "v"(__uint_as_float(sw[1])));
+        if (__any(mmix > thr_mix)) {
             // rare: O and the row sums hold all of sub-block m-1 (in the old reference) when they are rescaled
+            const float mx0 = xhalf_max(mx[0]) * c, mx1 = xhalf_max(mx[1]) * c;
 #pragma unroll
             for (int x = 0; x < 2; ++x) {
                 lsum[x] += lsa[x] + lsb[x];
@@ -410,6 +418,7 @@ attn_fwd64_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K
 #pragma unroll
                 for (int e = 0; e < 16; ++e) tw[x][e] += shift;
             }
+            thr_mix = ((hh ? m_ref[1] : m_ref[0]) + RESCALE_TAU) * inv_c;
         }
         lds_wait(kf);
         static_for<0, 16>([&](auto I) {
@@ -419,8 +428,9 @@ attn_fwd64_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K
             else mfma_qk(S[x], kf[s], qf[x][s]);
             if constexpr (i < 8) {
                 // V fragment i = [16-key step i / 4][column block i % 4]: key rows 0..7 and 8..15 of the step
-                vlo[i] = lds_read_tr16_b64<VO + (i >> 2) * 16 * ROWB>(vaddr[i & 3]);
-                vhi[i] = lds_read_tr16_b64<VO + (i >> 2) * 16 * ROWB + 8 * ROWB>(vaddr[i & 3]);
+                const bf16x4 lo = lds_read_tr16_b64<VO + (i >> 2) * 16 * ROWB>(vaddr[i & 3]);
+                const bf16x4 hi = lds_read_tr16_b64<VO + (i >> 2) * 16 * ROWB + 8 * ROWB>(vaddr[i & 3]);
+                vf[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             }
             constexpr int xw = i >> 3, e0 = 2 * (i & 7);     // weights e0, e0 + 1 of block xw: 16-key step e0 / 8
             tw[xw][e0] = fast_exp2(tw[xw][e0]);
@@ -450,7 +460,7 @@ attn_fwd64_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int p = 0; p < 4; ++p) { vlo[i][p] = (__bf16)0.f; vhi[i][p] = (__bf16)0.f; }
+        for (int p = 0; p < 8; ++p) vf[i][p] = (__bf16)0.f;
     asm volatile("s_waitcnt vmcnt(8)" ::: "memory");         // all but the newest tile's eight loads have landed
     __builtin_amdgcn_s_barrier();
     read_k(Flag<false>{});
