@@ -16,7 +16,7 @@ namespace infmllm {
 
 namespace {
 
-constexpr int DEC_THREADS = 256;
+constexpr int DEC_THREADS = 512;            // eight wavefronts: enough rows in flight per CU to cover the memory latency
 constexpr float DEC_TAU = 8.0f;             // the softmax reference moves only when a logit exceeds it by 2^8
 
 // Sum over the LPR consecutive lanes that cover one row, result in every lane (DPP butterflies).
@@ -191,9 +191,9 @@ decode_partial_kernel(const T* __restrict__ q, const T* __restrict__ knew, const
     __syncthreads();
     if (s_ticket != nsplit - 1) return;
     if (tid == 0) __hip_atomic_store(arrived + h, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
-    // out[head][x] = sum_s w_s o_s[x] / sum_s w_s l_s, w_s = 2^(m_s - max m); eight splits are requested at a
-    // time before any is used (a loop over the splits would serialise the trips to memory)
-    constexpr int CH = 8;
+    // out[head][x] = sum_s w_s o_s[x] / sum_s w_s l_s, w_s = 2^(m_s - max m); sixteen splits are requested at a
+    // time before any is used (a loop over the splits would serialise the trips to memory, about a microsecond each)
+    constexpr int CH = 16;
     for (int idx = tid; idx < G * D; idx += DEC_THREADS) {
         const int gq = h * G + idx / D, x = idx % D;
         const float* pp = part + (size_t)gq * nsplit * (D + 2);
@@ -233,7 +233,7 @@ hipError_t launch_decode(const Geometry& g, const CacheView& c, const void* q, c
 {
     const int n = t + 1;
     int nsplit = 256 / g.Hkv;                           // one workgroup per CU (more only add partials to merge) ...
-    if (nsplit > n / 128) nsplit = n / 128;             // ... of at least 128 keys each
+    if (nsplit > n / 256) nsplit = n / 256;             // ... of at least 256 keys each: two passes of its row slots
     if (nsplit > max_split) nsplit = max_split;
     if (nsplit < 1) nsplit = 1;
     const float cc = (float)(g.scale * 1.4426950408889634);
