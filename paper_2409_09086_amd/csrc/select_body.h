@@ -15,6 +15,14 @@ __device__ __forceinline__ uint32_t order_key(float f)
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 
+// Workgroup barrier for data handed over through LDS only.  `__syncthreads` also waits for every global store
+// and load of the wavefront to complete (about a microsecond for a store on its way to memory), which the
+// selection and the plan never need: nothing they write to memory is read again before the kernel ends.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Adds 1 to hist[digit] for every active lane whose `on` is true, one LDS atomic per distinct
 // digit per wavefront.
 __device__ __forceinline__ void wave_histogram(uint32_t* hist, uint32_t digit, bool on)
@@ -117,13 +125,18 @@ __device__ __forceinline__ int plan_item_token(const int32_t* __restrict__ rank,
 {
     return q < tc ? rank[q] : (q >= P1 && q < nitems ? tc + (q - P1) : -1);
 }
+// The two halves of the prefetch: the tokens of the items (table reads), and, once those have arrived, their scores.
+// The selection requests its candidates between the two, so that it does not wait for the second trip to memory.
 template <int TPB>
-__device__ __forceinline__ void plan_prefetch(PlanPre& pre, const int32_t* __restrict__ rank, const float* __restrict__ W,
-                                              int n, int tc, int cnd, int B)
+__device__ __forceinline__ void plan_prefetch_tokens(PlanPre& pre, const int32_t* __restrict__ rank, int n, int tc, int B)
 {
     const int P1 = tc > B ? tc : B, nitems = P1 + (n - tc);
 #pragma unroll
     for (int g = 0; g < PLAN_PRE; ++g) pre.jj[g] = plan_item_token(rank, g * TPB + (int)threadIdx.x, tc, P1, nitems);
+}
+template <int TPB>
+__device__ __forceinline__ void plan_prefetch_scores(PlanPre& pre, const float* __restrict__ W, int cnd)
+{
 #pragma unroll
     for (int g = 0; g < PLAN_PRE; ++g) pre.w[g] = (pre.jj[g] >= 0 && pre.jj[g] < cnd) ? W[pre.jj[g]] : __builtin_inff();
 }
@@ -147,7 +160,7 @@ __device__ __forceinline__ void plan_moves(const KeptMap& km, const float* __res
         return (int)km.base[j >> 6] + __popcll(bits & ((1ull << (j & 63)) - 1ull));
     };
     uint32_t fbase = 0, mbase = 0;                            // free rows / movers listed so far (uniform)
-    __syncthreads();                                          // the kept map is complete
+    lds_barrier();                                          // the kept map is complete
     static_assert(PLAN_PRE % CH == 0, "prefetched items are consumed in whole passes");
     auto pass = [&](int q0, const int (&jj)[CH], const float (&wv)[CH]) {
         int xs[CH], src[CH];
@@ -178,7 +191,7 @@ __device__ __forceinline__ void plan_moves(const KeptMap& km, const float* __res
                 cnt_mov[u * NW + w] = (uint32_t)__popcll(bmov[u]);
             }
         }
-        __syncthreads();
+        lds_barrier();
         if (w == 0) {
             const uint32_t v = cnt_free[l], incl = wave_inclusive_sum(v);
             cnt_free[l] = incl - v;
@@ -188,7 +201,7 @@ __device__ __forceinline__ void plan_moves(const KeptMap& km, const float* __res
             cnt_mov[l] = incl - v;
             if (l == 63) tot_mov = incl;
         }
-        __syncthreads();
+        lds_barrier();
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
             const int q = q0 + u * TPB + tid;
@@ -202,7 +215,7 @@ __device__ __forceinline__ void plan_moves(const KeptMap& km, const float* __res
         }
         fbase += tot_free;
         mbase += tot_mov;
-        __syncthreads();                                      // the count tables are rewritten by the next pass
+        lds_barrier();                                      // the count tables are rewritten by the next pass
     };
 #pragma unroll
     for (int p = 0; p < PLAN_PRE / CH; ++p) {                 // the passes whose loads were requested up front
@@ -234,10 +247,11 @@ __device__ __forceinline__ void plan_moves(const KeptMap& km, const float* __res
 // bin search and a pass costs two barriers.  The digits stop as soon as the bin that holds the
 // r-th largest key is wanted whole (as a rule after the second: few of a few thousand candidates
 // share 16 bits), and the ordered write needs two more barriers.
-template <int KPT, int TPB>
+template <int KPT, int TPB, typename AfterLoads>
 __device__ __forceinline__ void select_reg_body(const float* __restrict__ Wb, int32_t* __restrict__ I,
                                                 int32_t* __restrict__ userI, int32_t* __restrict__ user_count,
-                                                int h, int cnd, int r, int R, int B, int cap, KeptMap& km)
+                                                int h, int cnd, int r, int R, int B, int cap, KeptMap& km,
+                                                AfterLoads&& after_loads)
 {
     constexpr int NW = TPB / 64;
     static_assert(TPB >= 512, "one wavefront searches the bins while four others clear the next histogram");
@@ -254,22 +268,26 @@ __device__ __forceinline__ void select_reg_body(const float* __restrict__ Wb, in
         if (tid == 0) { s_min = 0xffffffffu; s_max = 0u; s_remaining = (uint32_t)r; s_ties = (uint32_t)cnd; s_done = 0; }
         if (tid < 256) hist[0][tid] = 0;
         uint32_t key[KPT];
+        float wj[KPT];
         uint32_t lo_key = 0xffffffffu, hi_key = 0u;
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) wj[k] = W[k * TPB + tid < cnd ? k * TPB + tid : 0];   // cnd >= 1 here
+        after_loads();                                        // further loads of the caller, behind the candidates
 #pragma unroll
         for (int k = 0; k < KPT; ++k) {
             const int j = k * TPB + tid;
             key[k] = 0u;
             if (j < cnd) {
-                key[k] = order_key(W[j]);
+                key[k] = order_key(wj[k]);
                 lo_key = key[k] < lo_key ? key[k] : lo_key;
                 hi_key = key[k] > hi_key ? key[k] : hi_key;
             }
         }
         lo_key = wave_extreme_to_last_lane<false>(lo_key);
         hi_key = wave_extreme_to_last_lane<true>(hi_key);
-        __syncthreads();
+        lds_barrier();
         if (l == 63) { atomicMin(&s_min, lo_key); atomicMax(&s_max, hi_key); }
-        __syncthreads();
+        lds_barrier();
         // bits [top, 32) are the same in every key; the digits cover bits [0, top) from the top down
         const uint32_t spread = s_min ^ s_max;
         int hi = spread ? 32 - __builtin_clz(spread) : 0;
@@ -281,7 +299,7 @@ __device__ __forceinline__ void select_reg_body(const float* __restrict__ Wb, in
 #pragma unroll
             for (int k = 0; k < KPT; ++k)
                 if ((k * TPB + tid < cnd) && ((key[k] & himask) == T)) atomicAdd(&hp[(key[k] >> lo) & dmask], 1u);
-            __syncthreads();
+            lds_barrier();
             if (tid < 64) {
                 // wavefront 0 walks the bins from the top; lane l owns bins 255-4l .. 252-4l
                 uint32_t c0 = hp[255 - 4 * l], c1 = hp[254 - 4 * l], c2 = hp[253 - 4 * l], c3 = hp[252 - 4 * l];
@@ -304,7 +322,7 @@ __device__ __forceinline__ void select_reg_body(const float* __restrict__ Wb, in
             } else if (tid >= 256 && tid < 512) {
                 hist[(pass + 1) & 1][tid - 256] = 0;
             }
-            __syncthreads();
+            lds_barrier();
             T = s_prefix;
             hi = s_done ? 0 : lo;
         }
@@ -324,10 +342,10 @@ __device__ __forceinline__ void select_reg_body(const float* __restrict__ Wb, in
                 tab_gt[k * NW + w] = (uint32_t)__popcll(bgt[k]);
             }
         }
-        __syncthreads();
+        lds_barrier();
         if (w == 0) wave_exclusive_table(tab_eq, KPT * NW);
         else if (w == 1) wave_exclusive_table(tab_gt, KPT * NW);
-        __syncthreads();
+        lds_barrier();
 #pragma unroll
         for (int k = 0; k < KPT; ++k) {
             const uint32_t eq_before = tab_eq[k * NW + w];
@@ -349,6 +367,7 @@ __device__ __forceinline__ void select_reg_body(const float* __restrict__ Wb, in
         }
     }
     else {
+        after_loads();
         for (int sgm = tid; sgm < (cnd + 63) / 64; sgm += TPB) { km.bits[sgm] = 0ull; km.base[sgm] = 0u; }   // nothing ranked
     }
     for (int x = tid; x < R; x += TPB) {                      // recent window: [c, n)

@@ -127,12 +127,17 @@ __device__ __forceinline__ void select_mem_body(const float* __restrict__ Wb, in
 
 
 // KPT = 0: candidates stay in memory.
-template <int KPT>
+// after_loads is called once, when the selection has requested its candidates and not yet used them.
+template <int KPT, typename AfterLoads>
 __device__ __forceinline__ void select_body(const float* Wb, int32_t* I, int32_t* userI, int32_t* user_count, int h,
-                                            int cnd, int r, int R, int B, int cap, KeptMap& km)
+                                            int cnd, int r, int R, int B, int cap, KeptMap& km, AfterLoads&& after_loads)
 {
-    if constexpr (KPT == 0) select_mem_body(Wb, I, userI, user_count, h, cnd, r, R, B, cap, km);
-    else select_reg_body<KPT, TPB>(Wb, I, userI, user_count, h, cnd, r, R, B, cap, km);
+    if constexpr (KPT == 0) {
+        after_loads();
+        select_mem_body(Wb, I, userI, user_count, h, cnd, r, R, B, cap, km);
+    } else {
+        select_reg_body<KPT, TPB>(Wb, I, userI, user_count, h, cnd, r, R, B, cap, km, after_loads);
+    }
 }
 
 // One workgroup per kv-head: selection, then the placement plan.
@@ -145,8 +150,9 @@ select_kernel(const float* __restrict__ Wb, int32_t* __restrict__ I, int32_t* __
     const int h = blockIdx.x;
     const size_t hb = (size_t)h * cap, mb = (size_t)h * mv.max;
     PlanPre pre;
-    plan_prefetch<TPB>(pre, c.rank + hb, Wb + hb, cnd + R, tc, cnd, B);
-    select_body<KPT>(Wb, I, userI, user_count, h, cnd, r, R, B, cap, km);
+    plan_prefetch_tokens<TPB>(pre, c.rank + hb, cnd + R, tc, B);
+    select_body<KPT>(Wb, I, userI, user_count, h, cnd, r, R, B, cap, km,
+                     [&]() __attribute__((always_inline)) { plan_prefetch_scores<TPB>(pre, Wb + hb, cnd); });
     const PlanTables pt{c.rank + hb, c.row + hb, c.score + hb, mv.src + mb, mv.dst + mb, mv.x + mb, mv.score + mb,
                         mv.count + h};
     plan_moves<TPB>(km, Wb + hb, cnd + R, tc, cnd, B, r, pt, pre);
@@ -164,8 +170,9 @@ select_batch_kernel(EvictBatch eb, int r, int R, int B, int cap, int Hkv)
     const int cnd = job.n - R;
     const size_t hb = (size_t)h * cap, mb = (size_t)h * job.mv.max;
     PlanPre pre;
-    plan_prefetch<TPB>(pre, job.c.rank + hb, job.Wb + hb, job.n, job.tc, cnd, B);
-    select_body<KPT>(job.Wb, job.I, job.user_I, job.user_count, h, cnd, r, R, B, cap, km);
+    plan_prefetch_tokens<TPB>(pre, job.c.rank + hb, job.n, job.tc, B);
+    select_body<KPT>(job.Wb, job.I, job.user_I, job.user_count, h, cnd, r, R, B, cap, km,
+                     [&]() __attribute__((always_inline)) { plan_prefetch_scores<TPB>(pre, job.Wb + hb, cnd); });
     const PlanTables pt{job.c.rank + hb, job.c.row + hb, job.c.score + hb, job.mv.src + mb, job.mv.dst + mb,
                         job.mv.x + mb, job.mv.score + mb, job.mv.count + h};
     plan_moves<TPB>(km, job.Wb + hb, job.n, job.tc, cnd, B, r, pt, pre);
