@@ -22,6 +22,10 @@
 // bf16 weights already laid out as the B operand of O^T += V^T.P^T); V is read with the LDS transpose read.
 // The softmax reference moves only when a row maximum outgrows it by 2^8; that rare step is taken on a side
 // path between the period's two scheduling regions.
+//
+// Under the causal mask the chunk's later rows see more keys.  A wavefront's two blocks are therefore one from
+// the front and one from the back of the head's rows, which gives every wavefront the same number of (row, key)
+// pairs; when block A has seen its last key the loop continues with a 16-slot period for block B alone.
 #include <type_traits>
 
 #include "launch.h"
@@ -134,14 +138,21 @@ attn_fwd64_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K
     const int ngrp = G / hpw;
     const int h = by / ngrp, hgrp = by % ngrp;
     const int g = h * G + hgrp * hpw + wave % hpw;           // query head of this wavefront
-    const int row0 = 64 * (bx * wph + wave / hpw);           // first query row of this wavefront
-    const int wg_rows_end = min(L, 64 * (bx + 1) * wph);
-    const int n_end = t + wg_rows_end;                       // keys any row of the workgroup can see
+    // The two 32-row blocks of a wavefront are block p from the front and block p from the back of the head's rows
+    // (p = the wavefront's index among the head's wavefronts): under the causal mask a row sees t + row + 1 keys,
+    // so every wavefront gets the same number of (row, key) pairs, where two neighbouring blocks would give the last
+    // wavefront a quarter more keys than the first and make the launch as long as that one.  Block A is finished
+    // first; the loop then goes on with block B alone (period1).
+    const int npair = ntile * wph;                           // wavefronts per head, over all workgroups
+    const int pair0 = bx * wph;                              // the workgroup's first pair
+    const int blkA = pair0 + wave / hpw, blkB = 2 * npair - 1 - blkA;
+    const int rowsB_end = min(L, 32 * (2 * npair - pair0));  // end of the workgroup's last block B (its first wavefront's)
+    const int n_end = t + rowsB_end;                         // keys any row of the workgroup can see
     const int Hkv = Hq / G, n = t + L;
     int my_row[2], my_lim[2];
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
-        my_row[x] = row0 + 32 * x + l32;
+        my_row[x] = 32 * (x == 0 ? blkA : blkB) + l32;
         my_lim[x] = t + min(my_row[x], L - 1);               // last visible key of my row
     }
     const uint16_t* Kh = K + (size_t)h * cap * D;
@@ -353,7 +364,8 @@ attn_fwd64_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K
 #pragma unroll
         for (int e = 0; e < 16; ++e) tw[x][e] = 0.f;
 
-    const int first_masked = (t + min(row0, L - 1) + 1) / 32;  // sub-blocks from here on reach past some row's limit
+    // sub-blocks from here on reach past the limit of some row of block A / of block B
+    const int first_maskedA = (t + min(32 * blkA, L - 1) + 1) / 32, first_maskedB = (t + min(32 * blkB, L - 1) + 1) / 32;
 
     // One period: sub-block m is in its softmax stage (its logits are in S), sub-block m-1 in its O += V^T P^T
     // stage (its V fragments were requested a period ago), sub-block m+1 in its S = K Q^T stage.  SUB = m & 1.
@@ -449,6 +461,72 @@ attn_fwd64_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K
         pf[1][1][3] = pack_bf16_after_nop(tw[1][14], tw[1][15]);
     };
 
+    // The same period for block B alone, once every row of the workgroup's blocks A has seen its last key: 16
+    // slots.  The logits are first read in the third slot, behind the two loads, so that the last product of the
+    // chain that formed them (the slot before this period) has long been written; block A's registers keep what
+    // they hold (weights of an all-masked sub-block, i.e. zeros, and finished sums).
+    auto period1 = [&](int m, auto sub, auto mask) {
+        constexpr int SUB = decltype(sub)::value;
+        constexpr int KO = (SUB == 0 ? 1 : 0) * 32 * ROWB;
+        constexpr int VO = SUB * 32 * ROWB;
+        wait_v();
+        float mx[2] = {-__builtin_inff(), -__builtin_inff()};
+        static_for<0, 8>([&](auto I) {
+            constexpr int i = decltype(I)::value;
+            constexpr int tt = i >> 2, b = i & 3;
+            o[1][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[4 * tt + b], as_bf16x8(pf[1][tt]), o[1][b], 0, 0, 0);
+            kf[i] = lds_read_b128<KO>(kaddr[i]);
+            if constexpr (i == 0) dma_step(4 * SUB);
+            if constexpr (i == 1) dma_step(4 * SUB + 1);
+            // logits 0..15 over slots 2..7: three, three, three, three, two, two
+            constexpr int e_lo = i < 2 ? 0 : (i < 6 ? 3 * (i - 2) : 12 + 2 * (i - 6));
+            constexpr int e_hi = i < 2 ? 0 : (i < 6 ? e_lo + 3 : e_lo + 2);
+            static_for<e_lo, e_hi>([&](auto E) {
+                constexpr int e = decltype(E)::value;
+                const float sv = masked_logit(mask, 1, e, m);
+                mx[1] = fmaxf(mx[1], sv);
+                if constexpr (e & 1) lsb[1] += tw[1][e];
+                else lsa[1] += tw[1][e];
+                tw[1][e] = __builtin_fmaf(sv, c, -m_use[1]);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx[0]), __float_as_uint(mx[1]), false, false);
+        float mmix;
+        asm("v_max_f32 %0, %1, %2" : "=v"(mmix) : "v"(__uint_as_float(sw[0])), "v"(__uint_as_float(sw[1])));
+        if (__any(mmix > thr_mix)) {                         // block A's half-wave compares -inf: never
+            const float mx1 = xhalf_max(mx[1]) * c;
+            lsum[1] += lsa[1] + lsb[1];
+            lsa[1] = 0.f; lsb[1] = 0.f;
+            const float old_use = m_use[1];
+            rescale(1, mx1);
+            const float shift = old_use - m_use[1];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) tw[1][e] += shift;
+            thr_mix = ((hh ? m_ref[1] : m_ref[0]) + RESCALE_TAU) * inv_c;
+        }
+        lds_wait(kf);
+        static_for<0, 8>([&](auto I) {
+            constexpr int i = decltype(I)::value;
+            if constexpr (i == 0) mfma_qk_first(S[1], kf[i], qf[1][i]);
+            else mfma_qk(S[1], kf[i], qf[1][i]);
+            const bf16x4 lo = lds_read_tr16_b64<VO + (i >> 2) * 16 * ROWB>(vaddr[i & 3]);
+            const bf16x4 hi = lds_read_tr16_b64<VO + (i >> 2) * 16 * ROWB + 8 * ROWB>(vaddr[i & 3]);
+            vf[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            constexpr int e0 = 2 * i;
+            tw[1][e0] = fast_exp2(tw[1][e0]);
+            tw[1][e0 + 1] = fast_exp2(tw[1][e0 + 1]);
+            if constexpr (i > 0) {                           // the pair of the slot before (see period)
+                constexpr int ep = 2 * (i - 1);
+                pf[1][ep >> 3][(ep & 7) >> 1] = pack_bf16(tw[1][ep], tw[1][ep + 1]);
+            }
+            if constexpr (i == 2) dma_step(4 * SUB + 2);
+            if constexpr (i == 6) dma_step(4 * SUB + 3);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        pf[1][1][3] = pack_bf16_after_nop(tw[1][14], tw[1][15]);
+    };
+
     // ---- prologue: tiles 0, 1 and 2 requested, 0 and 1 awaited, S(0) formed ------------------------------
     issue_tile(0, 0);
     issue_tile(min(1, ntiles - 1), 1);
@@ -476,13 +554,24 @@ attn_fwd64_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K
     // In iteration j the K fragments come from tile j (second half) and tile j+1 (first half), the V fragments
     // from tile j; tile j+3 is requested into the buffer tile j-1 has left, and tile j+2 is awaited before the
     // barrier.  Past the last tile the last one is requested again, into a buffer nobody reads any more.
-    const int j_masked = min(ntiles, first_masked >> 1);     // tiles from here on hold a masked sub-block
-    auto tile_iter = [&](int j, auto mask) {
+    // Block A's last visible key lies in sub-block mA (the workgroup's last block A decides for all its
+    // wavefronts, which keeps them in step); its weights are multiplied in period mA + 1, and the sub-block after
+    // it is all masked and leaves zeros in block A's weight registers.  From the tile after that period on the
+    // wavefront runs period1.
+    const int mA = (t + min(L, 32 * (pair0 + wph)) - 1) / 32;
+    const int j_single = min(ntiles, (mA + 3) >> 1);
+    const int j_maskedA = min(j_single, first_maskedA >> 1);  // tiles from here on hold a masked sub-block
+    const int j_maskedB = min(ntiles, first_maskedB >> 1);
+    auto tile_iter = [&](int j, auto mask, auto both) {
         const int wrap = ((j + 1) & (NBUF - 1)) == 0 ? TBYTES - NBUF * TBYTES : TBYTES;
         dma_begin(j + 3, j + 3);
-        period(2 * j, Flag<false>{}, mask);                  // K: tile j, sub-block 1;  V: tile j, sub-block 0
+        // K: tile j, sub-block 1;  V: tile j, sub-block 0
+        if constexpr (decltype(both)::value) period(2 * j, Flag<false>{}, mask);
+        else period1(2 * j, Flag<false>{}, mask);
         advance(kaddr, wrap);                                // K: on to tile j+1
-        period(2 * j + 1, Flag<true>{}, mask);               // K: tile j+1, sub-block 0;  V: tile j, sub-block 1
+        // K: tile j+1, sub-block 0;  V: tile j, sub-block 1
+        if constexpr (decltype(both)::value) period(2 * j + 1, Flag<true>{}, mask);
+        else period1(2 * j + 1, Flag<true>{}, mask);
         advance_v(wrap);
         // tile j+2 has landed (the eight loads of tile j+3 may still be on their way), and this wavefront's
         // LDS reads are done, before anyone overwrites what they read
@@ -490,8 +579,10 @@ attn_fwd64_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K
         __builtin_amdgcn_s_barrier();
     };
     int j = 0;
-    for (; j < j_masked; ++j) tile_iter(j, Flag<false>{});
-    for (; j < ntiles; ++j) tile_iter(j, Flag<true>{});
+    for (; j < j_maskedA; ++j) tile_iter(j, Flag<false>{}, Flag<true>{});
+    for (; j < j_single; ++j) tile_iter(j, Flag<true>{}, Flag<true>{});
+    for (; j < j_maskedB; ++j) tile_iter(j, Flag<false>{}, Flag<false>{});
+    for (; j < ntiles; ++j) tile_iter(j, Flag<true>{}, Flag<false>{});
 #pragma unroll
     for (int x = 0; x < 2; ++x) {                            // ... and its weights are not in the row sums yet
         float tail = 0.f;
