@@ -105,6 +105,24 @@ def test_every_attention_tile_shape(tile, heads, kv, budget, recent, chunks):
     print("max err %.3g swaps %d" % (ls.max_err, ls.swaps))
 
 
+@pytest.mark.parametrize("heads,kv,budget,recent,chunks", [
+    (4, 4, 768, 256, [768, 512, 300]),          # one head per wavefront: four pairs of row blocks per workgroup
+    (8, 2, 512, 192, [512, 448]),               # groups of four heads share a workgroup's K/V tiles
+    (4, 2, 512, 128, [512, 512, 200]),          # groups of two
+])
+def test_attention_row_block_pairs_on_long_chunks(heads, kv, budget, recent, chunks):
+    """The 64-rows-per-wavefront attention pairs a row block from the front of the chunk with one from its back
+    and finishes the back one alone.  Chunks of several hundred rows make every phase of that loop last several
+    tiles (both blocks, both blocks with block A masked, block B alone, block B masked), with ragged chunk
+    lengths leaving some back blocks empty; every output element is compared with the oracle."""
+    ls = pair(budget, recent, heads, kv, 128, "bf16", 1e-3, max_chunk=max(chunks), attn_tile=5)
+    for step, L in enumerate(chunks):
+        print("pairs", (heads, kv, budget, recent), "step", step, "L", L, flush=True)
+        q, k, v = random_chunk(1300 + step, L, heads, kv, 128, "bf16")
+        ls.step(q, k, v, check_state=True)
+    print("max err %.3g swaps %d" % (ls.max_err, ls.swaps))
+
+
 def test_bad_attention_tile_is_refused():
     with pytest.raises(B.InfMLLMError) as e:
         B.Stream(64, 16, 2, 2, 128, dtype=torch.bfloat16, attn_tile=6)
